@@ -1,0 +1,419 @@
+"""Pins of the CPU oracle to things other than itself: values the paper prints,
+closed forms, brute force on tiny inputs, library routines it must reduce to.
+All CPU; none of this touches the HIP path."""
+import itertools
+import math
+import os
+from decimal import ROUND_HALF_UP, Decimal
+
+import numpy as np
+import pytest
+
+from oracle import stc_oracle as O
+from tests.helpers import bits_to_f64, f32_to_bf16_bits, ints_bf16, randn_bf16
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# --------------------------------------------------------------------------- #
+# Budgets: the percentages printed in the paper (Sec. 4.2, App. C.2, LLM table)
+# --------------------------------------------------------------------------- #
+def _budget_rows():
+    rows = []
+    with open(os.path.join(GOLDEN, "budgets.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            r, S, K, printed, where = line.split()
+            rows.append((float(r), int(S), int(K), printed, where))
+    return rows
+
+
+@pytest.mark.parametrize("r,S,K,printed,where", _budget_rows())
+def test_budget_matches_printed_percentage(r, S, K, printed, where):
+    pct = Decimal(repr(O.rho_total(r, K, S) * 100.0))
+    digits = len(printed.split(".")[1])
+    got = pct.quantize(Decimal(1).scaleb(-digits), rounding=ROUND_HALF_UP)
+    assert str(got) == printed, (where, got, printed)
+
+
+@pytest.mark.parametrize("G,Kk", [(4, 1), (8, 2), (16, 4), (8, 7), (16, 12)])
+def test_packed_store_bytes_equal_value_budget(G, Kk):
+    """With K of S groups kept per token the packed store holds exactly K/S of
+    V's bytes, so K plus packed V is (1+K/S)/2 of the cache (Sec. 3.3)."""
+    rng = np.random.default_rng(1)
+    N, D = 48, 64
+    V = randn_bf16(rng, (N, D))
+    logits = rng.standard_normal((N, G)).astype(np.float32)
+    mask = O.route_mask(logits, Kk)
+    off = O.token_offsets(mask, G)
+    packed = O.pack_values(V, mask, off, G)
+    assert packed.nbytes * G == V.nbytes * Kk
+    kv_kept = (V.nbytes + packed.nbytes) / (2 * V.nbytes)   # K bytes == V bytes
+    assert kv_kept == O.rho_total(1.0, Kk, G)
+
+
+# --------------------------------------------------------------------------- #
+# Page bounds
+# --------------------------------------------------------------------------- #
+def test_bounds_brute_force_with_ragged_tail():
+    rng = np.random.default_rng(2)
+    N, D, P = 37, 8, 16                     # last page has 5 tokens
+    K = randn_bf16(rng, (N, D))
+    got = O.page_bounds(K, P)
+    Kf = bits_to_f64(K)
+    assert got.shape == (3, 2, D)
+    for p in range(3):
+        for c in range(D):
+            vals = [Kf[t, c] for t in range(p * P, min((p + 1) * P, N))]
+            assert bits_to_f64(got[p, 0, c]) == min(vals)
+            assert bits_to_f64(got[p, 1, c]) == max(vals)
+
+
+def test_bounds_signed_zero_order():
+    # one page, one channel per case: -0 sorts below +0 whatever the order.
+    for col, mn, mx in [([0x0000, 0x8000], 0x8000, 0x0000),
+                        ([0x8000, 0x0000], 0x8000, 0x0000),
+                        ([0x8000, 0x8000], 0x8000, 0x8000),
+                        ([0x0000, 0x0000], 0x0000, 0x0000),
+                        ([0x8000, 0x3F80], 0x8000, 0x3F80),     # -0, 1
+                        ([0x0000, 0xBF80], 0xBF80, 0x0000)]:    # +0, -1
+        K = np.array(col, dtype=np.uint16).reshape(2, 1)
+        b = O.page_bounds(K, 16)
+        assert (int(b[0, 0, 0]), int(b[0, 1, 0])) == (mn, mx)
+
+
+def test_score_is_upper_bound_of_every_token_logit():
+    rng = np.random.default_rng(3)
+    N, D, P, R = 160, 32, 16, 3
+    K = randn_bf16(rng, (N, D), 2.0)
+    q = randn_bf16(rng, (R, D))
+    U = O.head_page_bounds_score(q, O.page_bounds(K, P)).astype(np.float64)
+    logit = bits_to_f64(q) @ bits_to_f64(K).T          # [R, N]
+    for p in range(N // P):
+        top = logit[:, p * P:(p + 1) * P].max(axis=1)
+        assert np.all(U[:, p] >= top - 1e-4 * np.abs(top) - 1e-5)
+
+
+# --------------------------------------------------------------------------- #
+# Routing mask, offsets, packing
+# --------------------------------------------------------------------------- #
+def test_route_mask_equals_argsort_topk_when_no_ties():
+    rng = np.random.default_rng(4)
+    N, G = 200, 8
+    a = rng.standard_normal((N, G)).astype(np.float32)
+    c = rng.integers(0, G + 1, size=N)
+    got = O.route_mask(a, c)
+    for t in range(N):
+        top = np.argsort(-a[t].astype(np.float64), kind="stable")[:c[t]]
+        assert int(got[t]) == sum(1 << int(g) for g in top)
+
+
+def test_route_mask_ties_go_to_lowest_group_and_extremes():
+    a = np.array([[1, 1, 1, 1], [0, 2, 2, 0], [5, 5, 7, 5]], dtype=np.float32)
+    assert list(O.route_mask(a, 2)) == [0b0011, 0b0110, 0b0101]
+    assert list(O.route_mask(a, 0)) == [0, 0, 0]
+    assert list(O.route_mask(a, 4)) == [0b1111] * 3
+    assert list(O.route_mask(a, np.array([1, 3, 4]))) == [0b0001, 0b0111, 0b1111]
+
+
+def test_offsets_are_cumsum_of_popcounts():
+    rng = np.random.default_rng(5)
+    G = 16
+    mask = rng.integers(0, 1 << G, size=300).astype(np.uint16)
+    off = O.token_offsets(mask, G)
+    pc = np.array([bin(int(m)).count("1") for m in mask])
+    assert off.dtype == np.uint32 and off[0] == 0
+    assert np.array_equal(off[1:], np.cumsum(pc))
+
+
+@pytest.mark.parametrize("G", [1, 4, 8, 16])
+def test_pack_round_trip_and_order(G):
+    rng = np.random.default_rng(6)
+    N, D = 75, 64
+    gd = D // G
+    V = randn_bf16(rng, (N, D))
+    mask = rng.integers(0, 1 << G, size=N).astype(np.uint16)
+    mask[3] = 0
+    mask[4] = (1 << G) - 1
+    off = O.token_offsets(mask, G)
+    packed = O.pack_values(V, mask, off, G)
+    keep = ((mask[:, None] >> np.arange(G)[None, :]) & 1).astype(bool)      # [N, G]
+    # token order, then ascending group: row-major boolean selection
+    assert np.array_equal(packed, V.reshape(N, G, gd)[keep])
+    # unpack == mask * V, bit for bit (dropped groups are +0)
+    un = np.zeros((N, G, gd), dtype=np.uint16)
+    un[keep] = packed
+    assert np.array_equal(un.reshape(N, D), np.where(np.repeat(keep, gd, axis=1), V, 0))
+
+
+def test_pack_all_groups_kept_is_identity():
+    rng = np.random.default_rng(7)
+    N, D, G = 20, 32, 4
+    V = randn_bf16(rng, (N, D))
+    mask = O.route_mask(rng.standard_normal((N, G)).astype(np.float32), G)
+    off = O.token_offsets(mask, G)
+    assert np.array_equal(O.pack_values(V, mask, off, G).reshape(N, D), V)
+
+
+# --------------------------------------------------------------------------- #
+# Page score: value, summation order, sign handling, GQA rule
+# --------------------------------------------------------------------------- #
+def test_score_summation_order_is_adjacent_pair_tree():
+    """terms 1, 1.5e, e, 3e with e = 2^-24, u = 2^-23 = ulp(1), all factors bf16.
+    Adjacent pairs: (1+1.5e) -> 1+u (0.75u rounds up); (e+3e) = 2u; total 1+3u exact.
+    A half-stride tree gives 1+2u ((1+e) ties to 1, then 1+2.25u -> 1+2u);
+    a left-to-right sum gives 1+4u.  Only the adjacent tree yields 1+3u."""
+    e = 2.0 ** -24
+    t = np.array([1.0, 1.5 * e, e, 3 * e], dtype=np.float32)
+    b = f32_to_bf16_bits(t)
+    assert np.array_equal(bits_to_f64(b), t.astype(np.float64))
+    bounds = np.stack([b, b])[None]                           # mn == mx
+    q = f32_to_bf16_bits(np.ones((1, 4), dtype=np.float32))
+    U = O.head_page_bounds_score(q, bounds)
+    assert U.dtype == np.float32
+    assert float(U[0, 0]) == 1.0 + 3 * 2.0 ** -23
+
+
+def test_score_exact_on_small_integers():
+    rng = np.random.default_rng(8)
+    R, NP, D = 2, 9, 16
+    q = ints_bf16(rng, (R, D), -4, 4)
+    lo = rng.integers(-8, 8, size=(NP, D))
+    hi = lo + rng.integers(0, 5, size=(NP, D))
+    bounds = np.stack([f32_to_bf16_bits(lo.astype(np.float32)),
+                       f32_to_bf16_bits(hi.astype(np.float32))], axis=1)
+    U = O.head_page_bounds_score(q, bounds)
+    qi = bits_to_f64(q).astype(int)
+    for h, p in itertools.product(range(R), range(NP)):
+        want = sum(max(int(qi[h, c]) * int(lo[p, c]), int(qi[h, c]) * int(hi[p, c]))
+                   for c in range(D))
+        assert float(U[h, p]) == float(want)
+
+
+def test_score_close_to_float64_and_per_channel_max():
+    rng = np.random.default_rng(9)
+    R, N, D = 7, 256, 128
+    K = randn_bf16(rng, (N, D), 3.0)
+    q = randn_bf16(rng, (R, D))
+    bounds = O.page_bounds(K)
+    U = O.head_page_bounds_score(q, bounds).astype(np.float64)
+    qf, bf = bits_to_f64(q), bits_to_f64(bounds)
+    for h in range(R):
+        for p in range(N // 16):
+            terms = [max(qf[h, c] * bf[p, 0, c], qf[h, c] * bf[p, 1, c]) for c in range(D)]
+            assert abs(U[h, p] - math.fsum(terms)) <= 1e-5 * math.fsum(abs(x) for x in terms)
+
+
+def test_stream_score_is_max_over_group_heads_and_zero_is_positive():
+    rng = np.random.default_rng(10)
+    R, N, D = 4, 64, 16
+    bounds = O.page_bounds(randn_bf16(rng, (N, D)))
+    q = randn_bf16(rng, (R, D))
+    per_head = np.stack([O.page_scores(q[h:h + 1], bounds) for h in range(R)])
+    assert np.array_equal(O.page_scores(q, bounds), per_head.max(axis=0))
+    zq = np.full((R, D), 0x8000, dtype=np.uint16)             # q = -0 everywhere
+    s = O.page_scores(zq, bounds)
+    assert np.array_equal(s.view(np.uint32), np.zeros(N // 16, dtype=np.uint32))
+
+
+# --------------------------------------------------------------------------- #
+# Selection
+# --------------------------------------------------------------------------- #
+def test_select_brute_force_with_ties():
+    rng = np.random.default_rng(11)
+    for trial in range(50):
+        NP = int(rng.integers(1, 40))
+        k = int(rng.integers(1, NP + 3))
+        score = rng.integers(-3, 4, size=NP).astype(np.float32)      # many ties
+        got = O.select_pages(score, k)
+        # brute force: repeatedly take the best remaining (first of equals)
+        left, want = list(range(NP)), []
+        for _ in range(min(k, NP)):
+            best = left[0]
+            for p in left:
+                if score[p] > score[best]:
+                    best = p
+            want.append(best)
+            left.remove(best)
+        assert got.dtype == np.int32
+        assert list(got) == sorted(want)
+
+
+def test_select_zero_query_takes_first_pages():
+    rng = np.random.default_rng(12)
+    bounds = O.page_bounds(randn_bf16(rng, (320, 32)))
+    q = np.zeros((2, 32), dtype=np.uint16)
+    assert list(O.select_pages(O.page_scores(q, bounds), 5)) == [0, 1, 2, 3, 4]
+
+
+def test_select_on_constant_pages_is_topk_of_token_logits():
+    """If every token of a page has the same key, min == max, so the page score
+    is exactly that key's dot product with q and selection is a plain top-k."""
+    rng = np.random.default_rng(13)
+    NP, D, P, k = 24, 8, 16, 6
+    page_key = ints_bf16(rng, (NP, D), -6, 6)
+    K = np.repeat(page_key, P, axis=0)
+    q = ints_bf16(rng, (1, D), -3, 3)
+    idx = O.select_pages(O.page_scores(q, O.page_bounds(K, P)), k)
+    logit = (bits_to_f64(page_key) @ bits_to_f64(q)[0])
+    want = sorted(sorted(range(NP), key=lambda p: (-logit[p], p))[:k])
+    assert list(idx) == want
+
+
+def test_select_all_pages_when_k_at_least_np():
+    s = np.array([3, 1, 2], dtype=np.float32)
+    assert list(O.select_pages(s, 3)) == [0, 1, 2]
+    assert list(O.select_pages(s, 10)) == [0, 1, 2]
+
+
+# --------------------------------------------------------------------------- #
+# Attention
+# --------------------------------------------------------------------------- #
+def _dense_attention_f64(q, K, V):
+    """softmax(q K^T / sqrt(D)) V with library routines, float64."""
+    from scipy.special import softmax
+    D = q.shape[-1]
+    return softmax(q @ K.T / np.sqrt(D), axis=-1) @ V
+
+
+def test_attention_full_budget_all_groups_is_dense_attention():
+    rng = np.random.default_rng(14)
+    N, D, G, R = 96, 64, 4, 3
+    q, K, V = randn_bf16(rng, (R, D)), randn_bf16(rng, (N, D)), randn_bf16(rng, (N, D))
+    mask = np.full(N, (1 << G) - 1, dtype=np.uint16)
+    got = O.decode_attention(q, K, V, mask, np.arange(N // 16), G)
+    want = _dense_attention_f64(bits_to_f64(q), bits_to_f64(K), bits_to_f64(V))
+    assert np.abs(got - want).max() <= 1e-6
+    import torch
+    tq = torch.from_numpy(bits_to_f64(q))[None, :, None, :]            # [1, R, 1, D]
+    tk = torch.from_numpy(bits_to_f64(K))[None, None].expand(1, R, N, D)
+    tv = torch.from_numpy(bits_to_f64(V))[None, None].expand(1, R, N, D)
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv)[0, :, 0].numpy()
+    assert np.abs(got - ref).max() <= 1e-6
+
+
+def test_attention_masked_equals_dense_on_zero_filled_values():
+    rng = np.random.default_rng(15)
+    N, D, G, R, P = 100, 64, 8, 2, 16                   # ragged last page (4 tokens)
+    gd = D // G
+    q, K, V = randn_bf16(rng, (R, D), 4.0), randn_bf16(rng, (N, D)), randn_bf16(rng, (N, D))
+    mask = rng.integers(0, 1 << G, size=N).astype(np.uint16)
+    mask &= np.uint16(~(1 << 5) & 0xFFFF)               # nobody keeps group 5
+    pages = np.array([0, 2, 3, 6], dtype=np.int32)      # page 6 is the ragged one
+    got = O.decode_attention(q, K, V, mask, pages, G, P)
+    toks = np.concatenate([np.arange(p * P, min((p + 1) * P, N)) for p in pages])
+    keep = np.repeat(((mask[:, None] >> np.arange(G)) & 1), gd, axis=1)
+    Vz = bits_to_f64(V) * keep
+    want = _dense_attention_f64(bits_to_f64(q), bits_to_f64(K)[toks], Vz[toks])
+    assert np.abs(got - want).max() <= 1e-6
+    assert np.all(got[:, 5 * gd:6 * gd] == 0.0)         # dropped groups give exactly 0
+    assert np.any(got[:, :gd] != 0.0)
+
+
+def test_attention_closed_form_uniform_weights():
+    """q = 0: every weight is 1/|T| (|T| = 64), so out = (sum of kept V)/64 exactly."""
+    rng = np.random.default_rng(16)
+    N, D, G, P = 128, 32, 4, 16
+    gd = D // G
+    K = randn_bf16(rng, (N, D))
+    Vi = rng.integers(-8, 9, size=(N, D))
+    V = f32_to_bf16_bits(Vi.astype(np.float32))
+    mask = rng.integers(0, 1 << G, size=N).astype(np.uint16)
+    pages = np.array([1, 3, 4, 7], dtype=np.int32)
+    got = O.decode_attention(np.zeros((1, D), dtype=np.uint16), K, V, mask, pages, G, P)
+    for c in range(D):
+        tot = sum(int(Vi[t, c]) for p in pages for t in range(p * P, (p + 1) * P)
+                  if (int(mask[t]) >> (c // gd)) & 1)
+        assert float(got[0, c]) == tot / 64.0
+
+
+def test_attention_token_without_groups_still_counts_in_denominator():
+    D, G = 16, 2
+    K = np.zeros((2, D), dtype=np.uint16)
+    V = f32_to_bf16_bits(np.full((2, D), 6.0, dtype=np.float32))
+    mask = np.array([0b11, 0b00], dtype=np.uint16)
+    got = O.decode_attention(np.zeros((1, D), dtype=np.uint16), K, V, mask, np.array([0]), G)
+    assert np.all(got == 3.0)
+
+
+def test_single_group_is_token_level_quest():
+    """G = 1 with every token kept: output is dense attention over the selected pages."""
+    rng = np.random.default_rng(17)
+    N, D, P, k = 256, 32, 16, 5
+    q, K, V = randn_bf16(rng, (1, D), 3.0), randn_bf16(rng, (N, D)), randn_bf16(rng, (N, D))
+    idx = O.select_pages(O.page_scores(q, O.page_bounds(K, P)), k)
+    mask = np.ones(N, dtype=np.uint16)
+    got = O.decode_attention(q, K, V, mask, idx, 1, P)
+    toks = np.concatenate([np.arange(p * P, (p + 1) * P) for p in idx])
+    want = _dense_attention_f64(bits_to_f64(q), bits_to_f64(K)[toks], bits_to_f64(V)[toks])
+    assert np.abs(got - want).max() <= 1e-6
+
+
+def test_attention_page_order_invariance_and_ones():
+    rng = np.random.default_rng(18)
+    N, D, G = 160, 32, 4
+    q, K, V = randn_bf16(rng, (2, D)), randn_bf16(rng, (N, D)), randn_bf16(rng, (N, D))
+    mask = rng.integers(0, 1 << G, size=N).astype(np.uint16)
+    pages = np.array([0, 2, 5, 7, 9])
+    a = O.decode_attention(q, K, V, mask, pages, G)
+    b = O.decode_attention(q, K, V, mask, pages[::-1].copy(), G)
+    assert np.abs(a - b).max() <= 1e-6
+    ones = f32_to_bf16_bits(np.ones((N, D), dtype=np.float32))
+    full = np.full(N, (1 << G) - 1, dtype=np.uint16)
+    assert np.abs(O.decode_attention(q, K, ones, full, pages, G) - 1.0).max() <= 1e-6
+
+
+def test_attention_peaked_softmax_picks_the_matching_token():
+    """A query equal to 16x one key (all other keys orthogonal-ish small) puts
+    essentially all weight on that token: out == its kept values."""
+    N, D, G = 32, 16, 4
+    gd = D // G
+    K = np.zeros((N, D), dtype=np.float32)
+    for t in range(N):
+        K[t, t % D] = 1.0 + (t // D)                    # token 21: K[21, 5] = 2
+    q = np.zeros((1, D), dtype=np.float32)
+    q[0, 5] = 200.0
+    V = np.arange(N * D, dtype=np.float32).reshape(N, D) % 97
+    mask = np.full(N, 0b1011, dtype=np.uint16)
+    got = O.decode_attention(f32_to_bf16_bits(q), f32_to_bf16_bits(K), f32_to_bf16_bits(V),
+                             mask, np.array([0, 1]), G)
+    want = V[21].copy()
+    want[2 * gd:3 * gd] = 0.0
+    assert np.abs(got[0] - want).max() <= 1e-6
+
+
+def test_all_wrappers_use_gqa_head_layout_of_sdpa():
+    """Query head j reads KV head j // (Hq/Hkv), the usual GQA convention
+    (checked against torch SDPA on K, V repeated per query head)."""
+    import torch
+    rng = np.random.default_rng(19)
+    B, Hq, Hkv, N, D, G = 2, 6, 2, 64, 32, 4
+    q = randn_bf16(rng, (B, Hq, D))
+    K = randn_bf16(rng, (B, Hkv, N, D))
+    V = randn_bf16(rng, (B, Hkv, N, D))
+    mask = np.full((B, Hkv, N), (1 << G) - 1, dtype=np.uint16)
+    bounds = O.build_page_bounds_all(K)
+    idx, score = O.select_pages_all(q, bounds, N // 16)
+    assert np.array_equal(idx, np.broadcast_to(np.arange(N // 16, dtype=np.int32), idx.shape))
+    got = O.decode_attention_all(q, K, V, mask, idx, G)
+    R = Hq // Hkv
+    tq = torch.from_numpy(bits_to_f64(q))[:, :, None, :]
+    tk = torch.from_numpy(bits_to_f64(K)).repeat_interleave(R, dim=1)
+    tv = torch.from_numpy(bits_to_f64(V)).repeat_interleave(R, dim=1)
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv)[:, :, 0].numpy()
+    assert np.abs(got - ref).max() <= 1e-6
+
+
+def test_route_and_pack_all_modes_agree():
+    rng = np.random.default_rng(20)
+    B, Hkv, N, D, G = 2, 2, 40, 32, 8
+    V = randn_bf16(rng, (B, Hkv, N, D))
+    logits = rng.standard_normal((B, Hkv, N, G)).astype(np.float32)
+    kc = rng.integers(0, G + 1, size=(B, Hkv, N)).astype(np.uint8)
+    m1, o1, p1 = O.route_and_pack_all(V, G, logits=logits, kcount=kc)
+    m2, o2, p2 = O.route_and_pack_all(V, G, mask_in=m1 | np.uint16(0xFF00))
+    assert np.array_equal(m1, m2) and np.array_equal(o1, o2)
+    assert all(np.array_equal(a, b) for a, b in zip(p1, p2))
+    assert np.array_equal(o1[..., -1], np.array(kc, dtype=np.int64).sum(axis=-1))
