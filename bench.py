@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Decode-step benchmark of libstc on one MI355X.
+
+A step is one pass of the whole hot path over one layer's cache: Quest page
+selection (stc_select_pages) followed by routed attention over the selected
+pages (stc_decode_attention), for every stream of the batch.  Inputs are
+synthetic, resident in HBM before the timed region; the step rotates over
+several independent cache replicas and uses a fresh query every step so that
+no step is served from the 256 MB last-level cache.
+
+Prints ONE JSON line (see README / DESIGN for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+METRIC = "decode-attention us/step + achieved HBM GB/s (% of peak), Qwen2.5-7B 32K"
+
+# replicas so that the bytes touched between two uses of a cache exceed ~2x the 256 MB
+# last-level cache
+REPLICAS = {"tiny": 8, "llama2_7b_4k": 4, "qwen25_7b_32k": 6, "llava15_7b_prefix": 4,
+            "qwen25_7b_128k": 1}
+
+
+def algorithmic_bytes(w, mean_kept):
+    """Bytes the method must move per decode step (one layer's cache)."""
+    P, gd = 16, w.D // w.G
+    k = min(w.k_pages, w.NP)
+    bounds = w.streams * w.NP * 2 * w.D * 2 if w.k_pages < w.NP else 0
+    Kb = w.streams * k * P * w.D * 2
+    Vb = w.streams * k * P * mean_kept * gd * 2
+    meta = w.streams * k * P * 2 + 2 * w.streams * k * 4      # masks, page offsets, page indices
+    return {"select": bounds + w.streams * k * 4, "attention": Kb + Vb + meta,
+            "step": bounds + Kb + Vb + meta,
+            "parts": {"bounds": bounds, "K": Kb, "V": Vb, "meta": meta}}
+
+
+def build_replicas(stc, W, w, n_rep, dev):
+    import torch
+    caches = []
+    kept = 0
+    for r in range(n_rep * w.layers):
+        inp = W.make_cache_inputs(w, dev, layer=r)
+        K, V, logits = inp["K"], inp["V"], inp["logits"]
+        if w.routing == "vlm":
+            n_src = w.n_visual + w.n_text
+            Kc = torch.empty(w.B, w.Hkv, w.N, w.D, dtype=torch.bfloat16, device=dev)
+            Vc = torch.empty_like(Kc)
+            stc.stc_compact_tokens(K, inp["token_idx"], Kc, w.B, w.Hkv, n_src, w.N, w.D)
+            stc.stc_compact_tokens(V, inp["token_idx"], Vc, w.B, w.Hkv, n_src, w.N, w.D)
+            K, V = Kc, Vc
+        c = stc.RoutedCache(w.B, w.Hq, w.Hkv, w.D, w.N, w.G, w.k_pages, device=dev,
+                            keep_scores=False)
+        c.build(K, V, logits=logits, kcount=inp["kcount"], mask_in=inp["mask_in"])
+        torch.cuda.synchronize()
+        assert int(c.dev_status.item()) == 0
+        kept += int(c.tok_off[..., -1].to(torch.int64).sum().item())
+        caches.append(c)
+        del V, inp
+    mean_kept = kept / float(len(caches) * w.streams * w.N)
+    return caches, mean_kept
+
+
+def timed(fn, n, torch):
+    """Average milliseconds per call of fn(i) over n back-to-back calls (HIP events on
+    the current stream)."""
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    for i in range(n):
+        fn(i)
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / n
+
+
+def cpu_baseline(W, w, dev, budget_s=12.0):
+    """The oracle, as it stands, on a bounded sample of streams of the same workload
+    (per-step part only: page scores, selection, attention).  Single-threaded numpy."""
+    import numpy as np
+
+    from oracle import stc_oracle as O
+    inp = W.make_cache_inputs(W.shrink(w, B=1), dev, layer=0)     # batch element 0 only
+    q = W.bf16_bits(W.make_query(W.shrink(w, B=1), 0, dev))
+    R = w.R
+    prepared = []
+    for h in range(min(w.Hkv, 4)):                                 # oracle-built cache (untimed)
+        K, V = W.bf16_bits(inp["K"][0, h]), W.bf16_bits(inp["V"][0, h])
+        if w.routing == "vlm":
+            ti = inp["token_idx"][0].cpu().numpy()
+            K, V = K[ti], V[ti]
+        if inp["logits"] is not None:
+            lg = inp["logits"][0, h].cpu().numpy()
+        if inp["mask_in"] is not None:
+            m = W.u16_numpy(inp["mask_in"][0, h]) & np.uint16((1 << w.G) - 1)
+        else:
+            m = O.route_mask(lg, inp["kcount"][0, h].cpu().numpy())
+        prepared.append((K, V, m, O.page_bounds(K), q[0, h * R:(h + 1) * R]))
+    t0 = time.perf_counter()
+    done = 0
+    while True:
+        K, V, m, bounds, qh = prepared[done % len(prepared)]
+        if w.k_pages < w.NP:
+            idx = O.select_pages(O.page_scores(qh, bounds), w.k_pages)
+        else:
+            idx = np.arange(w.NP, dtype=np.int32)
+        O.decode_attention(qh, K, V, m, idx, w.G)
+        done += 1
+        el = time.perf_counter() - t0
+        if el > budget_s or done >= 4 * w.streams:
+            break
+    per_stream = el / done
+    return {"value": per_stream * w.streams * w.layers * 1e6, "unit": "us/step", "cores": 1,
+            "kind": "oracle",
+            "sample": "%d stream-steps of %s (oracle select+attention, %.2f s CPU), scaled to %d "
+                      "streams x %d layer(s)" % (done, w.name, el, w.streams, w.layers)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="qwen25_7b_32k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding or collectives); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2604_21335_amd as stc
+    from paper_2604_21335_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    w = W.WORKLOADS[args.workload]
+    n_rep = REPLICAS[w.name]
+    caches, mean_kept = build_replicas(stc, W, w, n_rep, dev)
+    nq = args.steps + args.warmup
+    queries = [W.make_query(w, s, dev) for s in range(min(nq, 64))]
+    L, C = w.layers, len(caches)
+
+    def step(i):                       # one decode step = `layers` (select, attend) pairs
+        qv = queries[i % len(queries)]
+        for l in range(L):
+            caches[(i * L + l) % C].step(qv)
+
+    def select_only(i):
+        caches[i % C].select(queries[i % len(queries)])
+
+    def attend_only(i):
+        caches[i % C].attend(queries[i % len(queries)])
+
+    for i in range(args.warmup):
+        step(i)
+    ms_step = timed(step, args.steps, torch)
+    ms_sel = timed(select_only, args.steps, torch) if w.k_pages < w.NP else 0.0
+    ms_att = timed(attend_only, args.steps, torch)
+
+    ab = algorithmic_bytes(w, mean_kept)
+    gbps = lambda nbytes, ms: (nbytes / (ms * 1e-3) / 1e9) if ms > 0 else 0.0  # noqa: E731
+    step_gbps = gbps(ab["step"] * L, ms_step)
+    calls = {
+        "select": {"us": ms_sel * 1e3, "bytes": ab["select"], "GBps": gbps(ab["select"], ms_sel)},
+        "attention": {"us": ms_att * 1e3, "bytes": ab["attention"],
+                      "GBps": gbps(ab["attention"], ms_att)},
+    }
+    dom = "select" if ms_sel >= ms_att else "attention"
+    kernel = {"select": "score_kernel (+ topk_kernel) of stc_select_pages",
+              "attention": "attn_split_kernel (+ attn_combine_kernel) of stc_decode_attention"}[dom]
+    roofline = {"bound": "hbm", "kernel": kernel, "achieved": calls[dom]["GBps"],
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": calls[dom]["GBps"] / HBM_PEAK_GBPS, "traffic": None,
+                "algorithmic_bytes": calls[dom]["bytes"], "avg_us": calls[dom]["us"]}
+    out = {
+        "metric": METRIC, "value": ms_step * 1e3, "unit": "us/step", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "N": w.N,
+                   "page": 16, "k_pages": min(w.k_pages, w.NP), "G": w.G,
+                   "mean_kept_groups": mean_kept, "layers_per_step": L, "cache_replicas": n_rep},
+        "hbm_GBps": step_gbps, "hbm_frac": step_gbps / HBM_PEAK_GBPS,
+        "algorithmic_bytes_per_step": ab["step"] * L, "bytes_parts": ab["parts"],
+        "calls": calls, "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(W, w, dev)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

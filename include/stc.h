@@ -1,0 +1,171 @@
+/*
+ * stc.h - C ABI of libstc: decode-step attention over a two-level compressed KV
+ * cache on AMD MI355X (gfx950).
+ *
+ * Level 1 is Quest-style page selection over the cached keys (the paper's
+ * Stage I, Sec. 3.2, with the chunk size 16 of its LLM training-config table in
+ * App. C.1).  Level 2 is sub-token value-group routing (Stage II, Sec. 3.3): the
+ * value vector of every cached token is split into G groups (the paper's S), a
+ * per-token bitmask records which groups the router kept, and only kept groups
+ * are stored ("group-packed store").  Attention follows the equation of
+ * Sec. 3.3: softmax(q K^T / sqrt(d_h)) applied to the routed value matrix;
+ * queries and keys are never compressed, dropped groups contribute nothing and
+ * the softmax is not renormalised over kept groups.
+ *
+ * Conventions shared by every call
+ *   - "stream" = one (batch b, KV head h) pair; streams are independent.
+ *     Query head j belongs to KV head j / (Hq/Hkv).
+ *   - Every data pointer is a DEVICE pointer owned by the caller, 16-byte
+ *     aligned, to a contiguous row-major tensor of the stated shape.  It is
+ *     borrowed until the work enqueued by the call has completed.
+ *     stc_shape_t is HOST memory, read during the call only.
+ *   - bf16 tensors are passed as void* (2 bytes per element).
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream).  No call synchronises, allocates, frees or keeps
+ *     state between calls.
+ *   - Return value: STC_OK (0) or a negative STC_ERR_* code.  On error nothing
+ *     has been enqueued.  Inputs are expected to be finite (no NaN/Inf).
+ *   - Ties in every top-k are broken towards the lowest index.
+ */
+#ifndef STC_H
+#define STC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct stc_shape {
+  int32_t B;            /* batch size, >= 1 */
+  int32_t Hq;           /* query heads; Hq % Hkv == 0, Hq/Hkv <= 16 */
+  int32_t Hkv;          /* KV heads */
+  int32_t D;            /* head dimension: 64 or 128 */
+  int32_t N;            /* cached tokens per stream, >= 1 */
+  int32_t P;            /* page size in tokens: 16 */
+  int32_t G;            /* value groups per token (paper's S): 1..16, D % G == 0,
+                           group width gd = D/G >= 8 (16-byte multiples) */
+  int32_t reserved;     /* must be 0 */
+  int64_t v_cap_groups; /* capacity of each stream's packed value store, in groups */
+} stc_shape_t;
+
+enum {
+  STC_OK = 0,
+  STC_ERR_NULL = -1,      /* a required pointer is NULL */
+  STC_ERR_SHAPE = -2,     /* a shape constraint above is violated, or k/mode out of range */
+  STC_ERR_ALIGN = -3,     /* a pointer is not 16-byte aligned */
+  STC_ERR_WORKSPACE = -4, /* workspace missing or smaller than stc_workspace_bytes() */
+  STC_ERR_LAUNCH = -5     /* the HIP runtime refused a launch */
+};
+
+/* which_call values for stc_workspace_bytes */
+enum { STC_WS_ROUTE = 1, STC_WS_SELECT = 2, STC_WS_ATTENTION = 3 };
+
+/* routing modes of stc_route_and_pack_values */
+enum {
+  STC_ROUTE_MASK = 0, /* mask_in gives the kept groups (bits >= G are ignored) */
+  STC_ROUTE_TOPK = 1  /* top-k of `logits` per token; count from kcount[] or fixed_k */
+};
+
+int stc_version(void);
+const char *stc_status_string(int status);
+
+/* Bytes of device workspace the given call needs for this shape (0 = none).
+ * k_pages is only used by STC_WS_SELECT / STC_WS_ATTENTION.  Returns 0 for an
+ * invalid shape (the call itself then reports the error). */
+size_t stc_workspace_bytes(const stc_shape_t *shape, int which_call, int k_pages);
+
+/*
+ * Quest page summary (Stage I, Sec. 3.2; chunk 16, App. C.1).
+ *   K      [B, Hkv, N, D]  bf16, in
+ *   bounds [B, Hkv, NP, 2, D] bf16, out; NP = ceil(N/P); row 0 = per-channel
+ *          minimum over the page's valid tokens (t < N), row 1 = maximum.
+ * Exact (comparisons only); -0 orders below +0.
+ */
+int stc_build_page_bounds(const stc_shape_t *shape, const void *K, void *bounds,
+                          void *stream);
+
+/*
+ * Routing mask and group-packed value store (Stage II, Sec. 3.3 "Value-group
+ * decomposition" and "Routing mask"; fixed per-token K of App. B.1).
+ *   mode STC_ROUTE_TOPK: bit g of mask[t] is set iff group g is among the c_t
+ *        largest of logits[t, 0..G) (equal logits: lower g first), where
+ *        c_t = kcount[t] (clamped to G) if kcount != NULL, else fixed_k (0..G).
+ *   mode STC_ROUTE_MASK: mask[t] = mask_in[t] & ((1<<G)-1).
+ *   V       [B, Hkv, N, D] bf16, in
+ *   logits  [B, Hkv, N, G] float, in (TOPK only)
+ *   kcount  [B, Hkv, N] uint8, in (TOPK, may be NULL)
+ *   mask_in [B, Hkv, N] uint16, in (MASK only)
+ *   mask    [B, Hkv, N] uint16, out (may alias mask_in)
+ *   tok_off [B, Hkv, N+1] uint32, out: exclusive prefix sum of popcount(mask)
+ *           per stream, in group units; tok_off[N] = kept groups of the stream
+ *   vpacked [B, Hkv, v_cap_groups, D/G] bf16, out: group g of token t (if kept)
+ *           is stored at group slot tok_off[t] + popcount(mask[t] & ((1<<g)-1));
+ *           slots >= tok_off[N] are left untouched
+ *   dev_status int32 on the device, out (may be NULL): set to 1 if any stream's
+ *           tok_off[N] exceeds v_cap_groups; writes beyond the capacity are
+ *           dropped, mask and tok_off are still exact.  The caller zeroes it.
+ *   ws      device workspace of stc_workspace_bytes(shape, STC_WS_ROUTE, 0) bytes
+ */
+int stc_route_and_pack_values(const stc_shape_t *shape, int mode, const void *V,
+                              const float *logits, const uint8_t *kcount, int fixed_k,
+                              const uint16_t *mask_in, uint16_t *mask, uint32_t *tok_off,
+                              void *vpacked, int32_t *dev_status, void *ws, size_t ws_bytes,
+                              void *stream);
+
+/*
+ * Query-aware page selection (Quest upper-bound score, top-k pages).
+ *   per query head h and page p, in float:
+ *     U_h[p] = sum_c max(q_h[c]*min[p,c], q_h[c]*max[p,c])
+ *   the D terms are summed by a balanced tree over adjacent channels
+ *   ((c0+c1)+(c2+c3))+..., every addition rounded to float;
+ *   score[p] = max over the query heads of the stream's KV head; -0 becomes +0.
+ *   The k_eff = min(k_pages, NP) pages of largest score (ties: lowest p) are
+ *   written in ascending order of p.
+ *   q          [B, Hq, D] bf16, in
+ *   bounds     [B, Hkv, NP, 2, D] bf16, in (not read when k_pages >= NP)
+ *   page_idx   [B, Hkv, k_eff] int32, out
+ *   page_score [B, Hkv, NP] float, out, may be NULL (then the scores live in ws);
+ *              not written when k_pages >= NP
+ *   ws         stc_workspace_bytes(shape, STC_WS_SELECT, k_pages) bytes
+ */
+int stc_select_pages(const stc_shape_t *shape, const void *q, const void *bounds, int k_pages,
+                     int32_t *page_idx, float *page_score, void *ws, size_t ws_bytes,
+                     void *stream);
+
+/*
+ * Routed decode attention over the selected pages (attention equation of
+ * Sec. 3.3 with the routed value matrix).  With T = all tokens t < N of the
+ * listed pages and s_t = (q_h . K[t]) / sqrt(D):
+ *   out_h[g*gd + j] = sum_{t in T, bit g of mask[t]} softmax_T(s)_t *
+ *                     vpacked[tok_off[t] + popcount(mask[t] & ((1<<g)-1))][j]
+ * bf16 inputs, float accumulation, float output.
+ *   q, K as above; vpacked, mask, tok_off as written by stc_route_and_pack_values
+ *   page_idx [B, Hkv, k_pages] int32, in; 1 <= k_pages <= NP; entries outside
+ *            [0, NP) are skipped; a page must not be listed twice
+ *   out      [B, Hq, D] float, out
+ *   ws       stc_workspace_bytes(shape, STC_WS_ATTENTION, k_pages) bytes
+ * Value slots at or beyond v_cap_groups are treated as dropped.
+ */
+int stc_decode_attention(const stc_shape_t *shape, const void *q, const void *K,
+                         const void *vpacked, const uint16_t *mask, const uint32_t *tok_off,
+                         const int32_t *page_idx, int k_pages, float *out, void *ws,
+                         size_t ws_bytes, void *stream);
+
+/*
+ * Token-level compaction helper for caches reduced by a visual-token method
+ * (Stage I for VLMs, Sec. 3.2: only the retained tokens stay in the cache).
+ * Gathers rows of a [B, Hkv, N_src, D] bf16 tensor:
+ *   dst[b, h, i, :] = src[b, h, token_idx[b, i], :],  i < n_keep.
+ *   token_idx [B, n_keep] int32, in; an index outside [0, N_src) writes a zero
+ *             row and sets *dev_status (device int32, may be NULL) to 1.
+ */
+int stc_compact_tokens(const void *src, const int32_t *token_idx, void *dst, int32_t B,
+                       int32_t Hkv, int32_t N_src, int32_t n_keep, int32_t D,
+                       int32_t *dev_status, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STC_H */

@@ -1,0 +1,218 @@
+"""Python binding of libstc (HIP, MI355X): decode attention over a Quest-selected,
+group-packed KV cache.  The functions below have the names of the C entry
+points in include/stc.h and only marshal arguments; every step of the path runs
+in the HIP kernels.  PyTorch is used for device memory and the current stream.
+
+There is no CPU fallback: if libstc.so cannot be loaded the calls raise.
+"""
+import ctypes
+import os
+
+import torch
+
+from . import workloads  # noqa: F401  (seeded synthetic inputs)
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libstc.so")
+
+STC_OK = 0
+STC_ERR_NULL, STC_ERR_SHAPE, STC_ERR_ALIGN, STC_ERR_WORKSPACE, STC_ERR_LAUNCH = -1, -2, -3, -4, -5
+STC_WS_ROUTE, STC_WS_SELECT, STC_WS_ATTENTION = 1, 2, 3
+STC_ROUTE_MASK, STC_ROUTE_TOPK = 0, 1
+
+EXPORTS = ["stc_version", "stc_status_string", "stc_workspace_bytes", "stc_build_page_bounds",
+           "stc_route_and_pack_values", "stc_select_pages", "stc_decode_attention",
+           "stc_compact_tokens"]
+
+
+class StcError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s failed: %d (%s)" % (where, status, status_string(status)))
+
+
+class stc_shape_t(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+                ("D", ctypes.c_int32), ("N", ctypes.c_int32), ("P", ctypes.c_int32),
+                ("G", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("v_cap_groups", ctypes.c_int64)]
+
+
+def make_shape(B, Hq, Hkv, D, N, G, v_cap_groups, P=16):
+    return stc_shape_t(B, Hq, Hkv, D, N, P, G, 0, v_cap_groups)
+
+
+_lib = None
+
+
+def load_library():
+    """dlopen libstc.so from the package directory; build it first only if it is
+    absent.  Raises if it can neither be found nor built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from .build import build_library
+        build_library()
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    shp = ctypes.POINTER(stc_shape_t)
+    lib.stc_version.restype = ctypes.c_int
+    lib.stc_version.argtypes = []
+    lib.stc_status_string.restype = ctypes.c_char_p
+    lib.stc_status_string.argtypes = [ctypes.c_int]
+    lib.stc_workspace_bytes.restype = sz
+    lib.stc_workspace_bytes.argtypes = [shp, ctypes.c_int, ctypes.c_int]
+    lib.stc_build_page_bounds.restype = ctypes.c_int
+    lib.stc_build_page_bounds.argtypes = [shp, vp, vp, vp]
+    lib.stc_route_and_pack_values.restype = ctypes.c_int
+    lib.stc_route_and_pack_values.argtypes = [shp, ctypes.c_int, vp, vp, vp, ctypes.c_int, vp, vp,
+                                              vp, vp, vp, vp, sz, vp]
+    lib.stc_select_pages.restype = ctypes.c_int
+    lib.stc_select_pages.argtypes = [shp, vp, vp, ctypes.c_int, vp, vp, vp, sz, vp]
+    lib.stc_decode_attention.restype = ctypes.c_int
+    lib.stc_decode_attention.argtypes = [shp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp, sz, vp]
+    lib.stc_compact_tokens.restype = ctypes.c_int
+    lib.stc_compact_tokens.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
+    _lib = lib
+    return lib
+
+
+def status_string(status):
+    return load_library().stc_status_string(int(status)).decode()
+
+
+def _ptr(t, dtype=None, name="tensor"):
+    """Device pointer of a contiguous CUDA tensor (None -> NULL)."""
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a CUDA tensor" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if dtype is not None and t.dtype not in (dtype if isinstance(dtype, tuple) else (dtype,)):
+        raise TypeError("%s has dtype %s" % (name, t.dtype))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def _check(status, where):
+    if status != STC_OK:
+        raise StcError(status, where)
+
+
+_U16 = (torch.int16, torch.uint16)
+_U32 = (torch.int32, torch.uint32)
+
+
+def stc_version():
+    return load_library().stc_version()
+
+
+def stc_workspace_bytes(shape, which_call, k_pages=0):
+    return int(load_library().stc_workspace_bytes(ctypes.byref(shape), which_call, k_pages))
+
+
+def stc_build_page_bounds(shape, K, bounds):
+    _check(load_library().stc_build_page_bounds(
+        ctypes.byref(shape), _ptr(K, torch.bfloat16, "K"), _ptr(bounds, torch.bfloat16, "bounds"),
+        _stream()), "stc_build_page_bounds")
+
+
+def stc_route_and_pack_values(shape, mode, V, logits, kcount, fixed_k, mask_in, mask, tok_off,
+                              vpacked, dev_status, ws):
+    _check(load_library().stc_route_and_pack_values(
+        ctypes.byref(shape), mode, _ptr(V, torch.bfloat16, "V"),
+        _ptr(logits, torch.float32, "logits"), _ptr(kcount, torch.uint8, "kcount"), int(fixed_k),
+        _ptr(mask_in, _U16, "mask_in"), _ptr(mask, _U16, "mask"), _ptr(tok_off, _U32, "tok_off"),
+        _ptr(vpacked, torch.bfloat16, "vpacked"), _ptr(dev_status, torch.int32, "dev_status"),
+        _ptr(ws, None, "ws"), _nbytes(ws), _stream()), "stc_route_and_pack_values")
+
+
+def stc_select_pages(shape, q, bounds, k_pages, page_idx, page_score, ws):
+    _check(load_library().stc_select_pages(
+        ctypes.byref(shape), _ptr(q, torch.bfloat16, "q"), _ptr(bounds, torch.bfloat16, "bounds"),
+        int(k_pages), _ptr(page_idx, torch.int32, "page_idx"),
+        _ptr(page_score, torch.float32, "page_score"), _ptr(ws, None, "ws"), _nbytes(ws),
+        _stream()), "stc_select_pages")
+
+
+def stc_decode_attention(shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, out, ws):
+    _check(load_library().stc_decode_attention(
+        ctypes.byref(shape), _ptr(q, torch.bfloat16, "q"), _ptr(K, torch.bfloat16, "K"),
+        _ptr(vpacked, torch.bfloat16, "vpacked"), _ptr(mask, _U16, "mask"),
+        _ptr(tok_off, _U32, "tok_off"), _ptr(page_idx, torch.int32, "page_idx"), int(k_pages),
+        _ptr(out, torch.float32, "out"), _ptr(ws, None, "ws"), _nbytes(ws), _stream()),
+        "stc_decode_attention")
+
+
+def stc_compact_tokens(src, token_idx, dst, B, Hkv, N_src, n_keep, D, dev_status=None):
+    _check(load_library().stc_compact_tokens(
+        _ptr(src, torch.bfloat16, "src"), _ptr(token_idx, torch.int32, "token_idx"),
+        _ptr(dst, torch.bfloat16, "dst"), B, Hkv, N_src, n_keep, D,
+        _ptr(dev_status, torch.int32, "dev_status"), _stream()), "stc_compact_tokens")
+
+
+class RoutedCache:
+    """Device buffers of one layer's compressed cache plus per-step outputs.
+
+    Allocation (through torch) and nothing else: every computation is one of the
+    stc_* calls above.
+    """
+
+    def __init__(self, B, Hq, Hkv, D, N, G, k_pages, v_cap_groups=None, device="cuda:0",
+                 keep_scores=True):
+        self.device = torch.device(device)
+        self.B, self.Hq, self.Hkv, self.D, self.N, self.G = B, Hq, Hkv, D, N, G
+        self.NP = (N + 15) // 16
+        self.k_pages = k_pages
+        self.k_eff = min(k_pages, self.NP)
+        cap = N * G if v_cap_groups is None else v_cap_groups
+        self.shape = make_shape(B, Hq, Hkv, D, N, G, cap)
+        dev = self.device
+        self.bounds = torch.empty(B, Hkv, self.NP, 2, D, dtype=torch.bfloat16, device=dev)
+        self.mask = torch.empty(B, Hkv, N, dtype=torch.int16, device=dev)
+        self.tok_off = torch.empty(B, Hkv, N + 1, dtype=torch.int32, device=dev)
+        self.vpacked = torch.empty(B, Hkv, cap, D // G, dtype=torch.bfloat16, device=dev)
+        self.dev_status = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.page_idx = torch.empty(B, Hkv, self.k_eff, dtype=torch.int32, device=dev)
+        self.page_score = (torch.empty(B, Hkv, self.NP, dtype=torch.float32, device=dev)
+                           if keep_scores else None)
+        self.out = torch.empty(B, Hq, D, dtype=torch.float32, device=dev)
+        self._ws_route = self._ws(STC_WS_ROUTE, 0)
+        self._ws_select = self._ws(STC_WS_SELECT, k_pages)
+        self._ws_attn = self._ws(STC_WS_ATTENTION, self.k_eff)
+        self.K = None
+
+    def _ws(self, which, k):
+        n = stc_workspace_bytes(self.shape, which, k)
+        return torch.empty(max(n, 16), dtype=torch.uint8, device=self.device)
+
+    def build(self, K, V, logits=None, kcount=None, fixed_k=0, mask_in=None):
+        """Cache construction: page bounds of K, routing mask + packed store of V."""
+        self.K = K
+        stc_build_page_bounds(self.shape, K, self.bounds)
+        mode = STC_ROUTE_MASK if mask_in is not None else STC_ROUTE_TOPK
+        stc_route_and_pack_values(self.shape, mode, V, logits, kcount, fixed_k, mask_in, self.mask,
+                                  self.tok_off, self.vpacked, self.dev_status, self._ws_route)
+
+    def select(self, q):
+        stc_select_pages(self.shape, q, self.bounds, self.k_pages, self.page_idx, self.page_score,
+                         self._ws_select)
+
+    def attend(self, q):
+        stc_decode_attention(self.shape, q, self.K, self.vpacked, self.mask, self.tok_off,
+                             self.page_idx, self.k_eff, self.out, self._ws_attn)
+
+    def step(self, q):
+        """One decode step: page selection, then routed attention."""
+        self.select(q)
+        self.attend(q)
+        return self.out

@@ -1,0 +1,272 @@
+// Query-aware page selection (Quest): upper-bound score of every page from its
+// per-channel key bounds, then the k best pages of each stream.
+#include "stc_common.hpp"
+#include "stc_kernels.hpp"
+
+namespace stc {
+
+// ---------------------------------------------------------------------------
+// Page scores.
+//   U_h[p] = sum_c max(q_h[c]*mn[p,c], q_h[c]*mx[p,c]),  score[p] = max_h U_h[p]
+// Float arithmetic in a fixed order: a lane owns 8 adjacent channels and sums
+// them as a balanced tree over adjacent pairs; the D/8 lanes of a page are then
+// combined by an xor butterfly, which continues the same tree.  Every product
+// of two bf16 values is exact in float, so fusing a product into the following
+// addition does not change any bit.
+// ---------------------------------------------------------------------------
+template <int D, int R>
+__global__ __launch_bounds__(256) void score_kernel(const uint4* __restrict__ bounds,
+                                                    const uint4* __restrict__ q,
+                                                    float* __restrict__ score, int NP, int Hq,
+                                                    int Hkv, int pages_per_block) {
+  constexpr int LPP = D / 8;     // lanes per page
+  constexpr int PPW = 64 / LPP;  // pages per wavefront pass
+  const int stream = blockIdx.y;
+  const int b = stream / Hkv, kvh = stream % Hkv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % LPP, pw = lane / LPP;
+
+  float qf[R][8];
+#pragma unroll
+  for (int h = 0; h < R; ++h) {
+    const uint4 v = q[((size_t)b * Hq + kvh * R + h) * LPP + sub];
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      qf[h][2 * i] = bf16_lo(w[i]);
+      qf[h][2 * i + 1] = bf16_hi(w[i]);
+    }
+  }
+
+  const int p0 = blockIdx.x * pages_per_block;
+  const int p1 = min(p0 + pages_per_block, NP);
+  const uint4* base = bounds + (size_t)stream * NP * (2 * LPP);
+  float* out = score + (size_t)stream * NP;
+
+  int p = p0 + wave * PPW + pw;
+  uint4 mnv = make_uint4(0, 0, 0, 0), mxv = mnv;
+  if (p < p1) {
+    mnv = base[(size_t)p * (2 * LPP) + sub];
+    mxv = base[(size_t)p * (2 * LPP) + LPP + sub];
+  }
+  for (; p < p1; p += 4 * PPW) {
+    const uint4 cmn = mnv, cmx = mxv;
+    const int pn = p + 4 * PPW;
+    if (pn < p1) {  // next pass of this lane, in flight during the arithmetic
+      mnv = base[(size_t)pn * (2 * LPP) + sub];
+      mxv = base[(size_t)pn * (2 * LPP) + LPP + sub];
+    }
+    const uint32_t wn[4] = {cmn.x, cmn.y, cmn.z, cmn.w};
+    const uint32_t wx[4] = {cmx.x, cmx.y, cmx.z, cmx.w};
+    float mn[8], mx[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      mn[2 * i] = bf16_lo(wn[i]);
+      mn[2 * i + 1] = bf16_hi(wn[i]);
+      mx[2 * i] = bf16_lo(wx[i]);
+      mx[2 * i + 1] = bf16_hi(wx[i]);
+    }
+    float best = 0.f;
+#pragma unroll
+    for (int h = 0; h < R; ++h) {
+      float t[8];
+#pragma unroll
+      for (int c = 0; c < 8; ++c) t[c] = fmaxf(qf[h][c] * mn[c], qf[h][c] * mx[c]);
+      const float s01 = t[0] + t[1], s23 = t[2] + t[3], s45 = t[4] + t[5], s67 = t[6] + t[7];
+      float u = (s01 + s23) + (s45 + s67);
+      u = row_tree_sum<LPP>(u);
+      best = h == 0 ? u : fmaxf(best, u);
+    }
+    if (sub == 0) out[p] = best == 0.f ? 0.f : best;  // -0 -> +0
+  }
+}
+
+// Fallback for group sizes without a specialisation: one query head at a time.
+template <int D>
+__global__ __launch_bounds__(256) void score_kernel_any(const uint4* __restrict__ bounds,
+                                                        const uint4* __restrict__ q,
+                                                        float* __restrict__ score, int NP, int Hq,
+                                                        int Hkv, int R, int pages_per_block) {
+  constexpr int LPP = D / 8;
+  constexpr int PPW = 64 / LPP;
+  const int stream = blockIdx.y;
+  const int b = stream / Hkv, kvh = stream % Hkv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % LPP, pw = lane / LPP;
+  const int p0 = blockIdx.x * pages_per_block;
+  const int p1 = min(p0 + pages_per_block, NP);
+  const uint4* base = bounds + (size_t)stream * NP * (2 * LPP);
+  float* out = score + (size_t)stream * NP;
+  for (int p = p0 + wave * PPW + pw; p < p1; p += 4 * PPW) {
+    const uint4 cmn = base[(size_t)p * (2 * LPP) + sub];
+    const uint4 cmx = base[(size_t)p * (2 * LPP) + LPP + sub];
+    const uint32_t wn[4] = {cmn.x, cmn.y, cmn.z, cmn.w};
+    const uint32_t wx[4] = {cmx.x, cmx.y, cmx.z, cmx.w};
+    float best = 0.f;
+    for (int h = 0; h < R; ++h) {
+      const uint4 v = q[((size_t)b * Hq + kvh * R + h) * LPP + sub];
+      const uint32_t wq[4] = {v.x, v.y, v.z, v.w};
+      float t[8];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float ql = bf16_lo(wq[i]), qh = bf16_hi(wq[i]);
+        t[2 * i] = fmaxf(ql * bf16_lo(wn[i]), ql * bf16_lo(wx[i]));
+        t[2 * i + 1] = fmaxf(qh * bf16_hi(wn[i]), qh * bf16_hi(wx[i]));
+      }
+      const float s01 = t[0] + t[1], s23 = t[2] + t[3], s45 = t[4] + t[5], s67 = t[6] + t[7];
+      float u = (s01 + s23) + (s45 + s67);
+      u = row_tree_sum<LPP>(u);
+      best = h == 0 ? u : fmaxf(best, u);
+    }
+    if (sub == 0) out[p] = best == 0.f ? 0.f : best;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Top-k pages of a stream: radix select of the k-th largest key (4 passes of 8
+// bits), then an order-preserving compaction.  Equal scores are taken in
+// ascending page order; the output is ascending in page index.
+// ---------------------------------------------------------------------------
+constexpr int kSelThreads = 1024;
+
+__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
+  for (int d = 1; d < 64; d <<= 1) {
+    const int o = __shfl_up(v, d);
+    if (lane >= d) v += o;
+  }
+  return v;
+}
+
+// Exclusive scan over the block (thread order); *total = block sum.
+__device__ __forceinline__ int block_exscan(int v, int* lds_waves, int* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nw = blockDim.x >> 6;
+  const int inc = wave_incl_scan(v, lane);
+  if (lane == 63) lds_waves[wave] = inc;
+  __syncthreads();
+  int base = 0, tot = 0;
+  for (int w = 0; w < nw; ++w) {
+    const int x = lds_waves[w];
+    if (w < wave) base += x;
+    tot += x;
+  }
+  *total = tot;
+  __syncthreads();
+  return base + inc - v;
+}
+
+__global__ __launch_bounds__(kSelThreads) void topk_kernel(const float* __restrict__ score,
+                                                           int32_t* __restrict__ page_idx, int NP,
+                                                           int k) {
+  __shared__ int hist[256];
+  __shared__ int waves[kSelThreads / 64];
+  __shared__ uint32_t s_prefix;
+  __shared__ int s_remaining;
+  const int stream = blockIdx.x;
+  const float* sc = score + (size_t)stream * NP;
+  int32_t* out = page_idx + (size_t)stream * k;
+  const int tid = threadIdx.x;
+
+  uint32_t prefix = 0;  // leading bits of the k-th largest key found so far
+  int remaining = k;    // rank of that key among the keys sharing the prefix
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    for (int i = tid; i < NP; i += kSelThreads) {
+      const uint32_t key = float_key(sc[i]);
+      const bool in = shift == 24 || (key >> (shift + 8)) == (prefix >> (shift + 8));
+      if (in) atomicAdd(&hist[(key >> shift) & 255u], 1);
+    }
+    __syncthreads();
+    // digits in descending order: thread t looks at digit 255 - t
+    const int cnt = tid < 256 ? hist[255 - tid] : 0;
+    int tot;
+    const int above = block_exscan(cnt, waves, &tot);  // keys with a larger digit
+    if (tid < 256 && above < remaining && remaining <= above + cnt) {
+      s_prefix = prefix | ((uint32_t)(255 - tid) << shift);
+      s_remaining = remaining - above;
+    }
+    __syncthreads();
+    prefix = s_prefix;
+    remaining = s_remaining;
+    __syncthreads();
+  }
+  // prefix = key of the k-th largest score; `remaining` of the pages equal to
+  // it are taken, lowest page index first.
+  const int per = (NP + kSelThreads - 1) / kSelThreads;
+  const int i0 = min(tid * per, NP), i1 = min(i0 + per, NP);
+  int eq = 0;
+  for (int i = i0; i < i1; ++i) eq += float_key(sc[i]) == prefix;
+  int tot;
+  int eq_before = block_exscan(eq, waves, &tot);
+  int sel = 0;
+  {
+    int e = eq_before;
+    for (int i = i0; i < i1; ++i) {
+      const uint32_t key = float_key(sc[i]);
+      if (key > prefix) ++sel;
+      else if (key == prefix) sel += (e++ < remaining);
+    }
+  }
+  int pos = block_exscan(sel, waves, &tot);
+  for (int i = i0; i < i1; ++i) {
+    const uint32_t key = float_key(sc[i]);
+    bool take = key > prefix;
+    if (key == prefix) take = eq_before++ < remaining;
+    if (take && pos < k) out[pos++] = i;
+  }
+}
+
+__global__ void iota_pages_kernel(int32_t* __restrict__ page_idx, int NP, int total) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < total) page_idx[i] = i % NP;
+}
+
+template <int D>
+static void launch_score(const stc_shape_t& s, const void* q, const void* bounds, float* score,
+                         int NP, hipStream_t st) {
+  constexpr int PPW = 64 / (D / 8);
+  const int streams = s.B * s.Hkv;
+  const int R = s.Hq / s.Hkv;
+  // aim for a few thousand wavefronts; every block takes at least one pass of its 4 waves
+  const int want_blocks = max(1, 2048 / streams);
+  int ppb = (NP + want_blocks - 1) / want_blocks;
+  ppb = max(4 * PPW, (ppb + 4 * PPW - 1) / (4 * PPW) * (4 * PPW));
+  dim3 grid((NP + ppb - 1) / ppb, streams);
+  const uint4* b4 = (const uint4*)bounds;
+  const uint4* q4 = (const uint4*)q;
+#define STC_SCORE_CASE(RR)                                                                     \
+  case RR:                                                                                     \
+    score_kernel<D, RR><<<grid, 256, 0, st>>>(b4, q4, score, NP, s.Hq, s.Hkv, ppb);            \
+    break;
+  switch (R) {
+    STC_SCORE_CASE(1)
+    STC_SCORE_CASE(2)
+    STC_SCORE_CASE(4)
+    STC_SCORE_CASE(7)
+    STC_SCORE_CASE(8)
+    default:
+      score_kernel_any<D><<<grid, 256, 0, st>>>(b4, q4, score, NP, s.Hq, s.Hkv, R, ppb);
+  }
+#undef STC_SCORE_CASE
+}
+
+int launch_select(const stc_shape_t& s, const void* q, const void* bounds, int k_pages,
+                  int32_t* page_idx, float* score, hipStream_t st) {
+  const int NP = (s.N + kPage - 1) / kPage;
+  const int streams = s.B * s.Hkv;
+  if (k_pages >= NP) {
+    const int total = streams * NP;
+    iota_pages_kernel<<<(total + 255) / 256, 256, 0, st>>>(page_idx, NP, total);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+  }
+  if (s.D == 128)
+    launch_score<128>(s, q, bounds, score, NP, st);
+  else
+    launch_score<64>(s, q, bounds, score, NP, st);
+  if (hipGetLastError() != hipSuccess) return -1;
+  topk_kernel<<<streams, kSelThreads, 0, st>>>(score, page_idx, NP, k_pages);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+}  // namespace stc

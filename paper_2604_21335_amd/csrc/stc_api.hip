@@ -1,0 +1,146 @@
+// C ABI of libstc: argument validation and dispatch to the kernel launchers.
+#include "../../include/stc.h"
+#include "stc_kernels.hpp"
+
+namespace {
+
+constexpr int kMaxGridY = 65535;
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool shape_ok(const stc_shape_t* s) {
+  if (s->B < 1 || s->Hq < 1 || s->Hkv < 1 || s->N < 1) return false;
+  if (s->Hq % s->Hkv != 0 || s->Hq / s->Hkv > 16) return false;
+  if (s->D != 64 && s->D != 128) return false;
+  if (s->P != 16) return false;
+  if (s->G < 1 || s->G > 16 || (s->G & (s->G - 1)) != 0) return false;
+  if (s->D % s->G != 0 || s->D / s->G < 8) return false;
+  if (s->reserved != 0 || s->v_cap_groups < 0) return false;
+  if ((long long)s->B * s->Hkv > kMaxGridY) return false;
+  if ((long long)s->N > (1ll << 30)) return false;
+  // the packed store is addressed with 32-bit group offsets
+  if ((long long)s->N * s->G >= (1ll << 32)) return false;
+  return true;
+}
+
+int num_pages(const stc_shape_t* s) { return (s->N + s->P - 1) / s->P; }
+
+size_t select_ws_bytes(const stc_shape_t* s) {
+  return (size_t)s->B * s->Hkv * num_pages(s) * sizeof(float);
+}
+
+}  // namespace
+
+extern "C" {
+
+int stc_version(void) { return 1; }
+
+const char* stc_status_string(int status) {
+  switch (status) {
+    case STC_OK: return "ok";
+    case STC_ERR_NULL: return "a required pointer is NULL";
+    case STC_ERR_SHAPE: return "shape or argument out of range";
+    case STC_ERR_ALIGN: return "pointer is not 16-byte aligned";
+    case STC_ERR_WORKSPACE: return "workspace missing or too small";
+    case STC_ERR_LAUNCH: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+size_t stc_workspace_bytes(const stc_shape_t* shape, int which_call, int k_pages) {
+  if (!shape || !shape_ok(shape)) return 0;
+  switch (which_call) {
+    case STC_WS_ROUTE: return stc::route_ws_bytes(*shape);
+    case STC_WS_SELECT: return k_pages >= num_pages(shape) ? 0 : select_ws_bytes(shape);
+    case STC_WS_ATTENTION:
+      if (k_pages < 1 || k_pages > num_pages(shape)) return 0;
+      return stc::attention_ws_bytes(*shape, k_pages);
+    default: return 0;
+  }
+}
+
+int stc_build_page_bounds(const stc_shape_t* shape, const void* K, void* bounds, void* stream) {
+  if (!shape || !K || !bounds) return STC_ERR_NULL;
+  if (!shape_ok(shape)) return STC_ERR_SHAPE;
+  if (!aligned16(K) || !aligned16(bounds)) return STC_ERR_ALIGN;
+  return stc::launch_bounds(*shape, K, bounds, (hipStream_t)stream) ? STC_ERR_LAUNCH : STC_OK;
+}
+
+int stc_route_and_pack_values(const stc_shape_t* shape, int mode, const void* V,
+                              const float* logits, const uint8_t* kcount, int fixed_k,
+                              const uint16_t* mask_in, uint16_t* mask, uint32_t* tok_off,
+                              void* vpacked, int32_t* dev_status, void* ws, size_t ws_bytes,
+                              void* stream) {
+  if (!shape || !V || !mask || !tok_off || !vpacked) return STC_ERR_NULL;
+  if (!shape_ok(shape)) return STC_ERR_SHAPE;
+  if (mode == STC_ROUTE_TOPK) {
+    if (!logits) return STC_ERR_NULL;
+    if (!kcount && (fixed_k < 0 || fixed_k > shape->G)) return STC_ERR_SHAPE;
+  } else if (mode == STC_ROUTE_MASK) {
+    if (!mask_in) return STC_ERR_NULL;
+  } else {
+    return STC_ERR_SHAPE;
+  }
+  if (!aligned16(V) || !aligned16(vpacked) || !aligned16(mask) || !aligned16(tok_off) ||
+      (logits && !aligned16(logits)) || (mask_in && !aligned16(mask_in)))
+    return STC_ERR_ALIGN;
+  if (!ws || ws_bytes < stc::route_ws_bytes(*shape) || !aligned16(ws)) return STC_ERR_WORKSPACE;
+  return stc::launch_route_pack(*shape, mode, V, logits, kcount, fixed_k, mask_in, mask, tok_off,
+                                vpacked, dev_status, ws, (hipStream_t)stream)
+             ? STC_ERR_LAUNCH
+             : STC_OK;
+}
+
+int stc_select_pages(const stc_shape_t* shape, const void* q, const void* bounds, int k_pages,
+                     int32_t* page_idx, float* page_score, void* ws, size_t ws_bytes,
+                     void* stream) {
+  if (!shape || !page_idx) return STC_ERR_NULL;
+  if (!shape_ok(shape) || k_pages < 1) return STC_ERR_SHAPE;
+  if (!aligned16(page_idx)) return STC_ERR_ALIGN;
+  float* score = page_score;
+  if (k_pages < num_pages(shape)) {
+    if (!q || !bounds) return STC_ERR_NULL;
+    if (!aligned16(q) || !aligned16(bounds) || (page_score && !aligned16(page_score)))
+      return STC_ERR_ALIGN;
+    if (!score) {
+      if (!ws || ws_bytes < select_ws_bytes(shape) || !aligned16(ws)) return STC_ERR_WORKSPACE;
+      score = (float*)ws;
+    }
+  }
+  return stc::launch_select(*shape, q, bounds, k_pages, page_idx, score, (hipStream_t)stream)
+             ? STC_ERR_LAUNCH
+             : STC_OK;
+}
+
+int stc_decode_attention(const stc_shape_t* shape, const void* q, const void* K,
+                         const void* vpacked, const uint16_t* mask, const uint32_t* tok_off,
+                         const int32_t* page_idx, int k_pages, float* out, void* ws,
+                         size_t ws_bytes, void* stream) {
+  if (!shape || !q || !K || !vpacked || !mask || !tok_off || !page_idx || !out)
+    return STC_ERR_NULL;
+  if (!shape_ok(shape) || k_pages < 1 || k_pages > num_pages(shape)) return STC_ERR_SHAPE;
+  if (!aligned16(q) || !aligned16(K) || !aligned16(vpacked) || !aligned16(mask) ||
+      !aligned16(tok_off) || !aligned16(page_idx) || !aligned16(out))
+    return STC_ERR_ALIGN;
+  const size_t need = stc::attention_ws_bytes(*shape, k_pages);
+  if (need && (!ws || ws_bytes < need || !aligned16(ws))) return STC_ERR_WORKSPACE;
+  return stc::launch_attention(*shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, out, ws,
+                               (hipStream_t)stream)
+             ? STC_ERR_LAUNCH
+             : STC_OK;
+}
+
+int stc_compact_tokens(const void* src, const int32_t* token_idx, void* dst, int32_t B,
+                       int32_t Hkv, int32_t N_src, int32_t n_keep, int32_t D,
+                       int32_t* dev_status, void* stream) {
+  if (!src || !token_idx || !dst) return STC_ERR_NULL;
+  if (B < 1 || Hkv < 1 || N_src < 1 || n_keep < 1 || (D != 64 && D != 128)) return STC_ERR_SHAPE;
+  if ((long long)B * Hkv > kMaxGridY) return STC_ERR_SHAPE;
+  if (!aligned16(src) || !aligned16(dst) || !aligned16(token_idx)) return STC_ERR_ALIGN;
+  return stc::launch_compact(src, token_idx, dst, B, Hkv, N_src, n_keep, D, dev_status,
+                             (hipStream_t)stream)
+             ? STC_ERR_LAUNCH
+             : STC_OK;
+}
+
+}  // extern "C"

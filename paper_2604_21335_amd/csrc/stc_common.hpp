@@ -1,0 +1,74 @@
+// Shared device helpers for the libstc kernels (gfx950 only, 64-wide wavefronts).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace stc {
+
+constexpr int kWave = 64;
+constexpr int kPage = 16;
+
+// bf16 pair in one dword: element 2i in the low half, 2i+1 in the high half.
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// DPP lane moves inside a row of 16 lanes.  Control codes of the gfx9 DPP
+// encoding: quad_perm = 2 bits per lane of the quad; 0x140 row_mirror
+// (lane i <- lane 15-i); 0x141 row_half_mirror (lane i <- lane 7-i in each half).
+constexpr int kDppXor1 = 0xB1;       // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;       // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;
+constexpr int kDppMirror = 0x140;
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x) {
+  return __int_as_float(
+      __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
+}
+
+// Sum over an aligned block of LANES (2..16) lanes; every lane of the block
+// ends with the same bits.  Pairs are combined in xor-butterfly order
+// (distance 1, 2, 4, 8), i.e. as a balanced tree over adjacent lanes.  For
+// distances 4 and 8 the mirrored partner holds the same value as the xor
+// partner because the value is already uniform over quads / halves.
+template <int LANES>
+__device__ __forceinline__ float row_tree_sum(float x) {
+  static_assert(LANES == 2 || LANES == 4 || LANES == 8 || LANES == 16, "row of 16");
+  x = x + dpp_f32<kDppXor1>(x);
+  if (LANES >= 4) x = x + dpp_f32<kDppXor2>(x);
+  if (LANES >= 8) x = x + dpp_f32<kDppHalfMirror>(x);
+  if (LANES >= 16) x = x + dpp_f32<kDppMirror>(x);
+  return x;
+}
+
+template <int LANES>
+__device__ __forceinline__ float row_max(float x) {
+  x = fmaxf(x, dpp_f32<kDppXor1>(x));
+  if (LANES >= 4) x = fmaxf(x, dpp_f32<kDppXor2>(x));
+  if (LANES >= 8) x = fmaxf(x, dpp_f32<kDppHalfMirror>(x));
+  if (LANES >= 16) x = fmaxf(x, dpp_f32<kDppMirror>(x));
+  return x;
+}
+
+// Value of lane `src_lane` (wave-uniform index) as a scalar.
+__device__ __forceinline__ float readlane_f32(float x, int src_lane) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), src_lane));
+}
+
+// Order-preserving map of float bits to unsigned keys (finite inputs).
+__device__ __forceinline__ uint32_t float_key(float f) {
+  uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Total order on bf16 bit patterns as signed integers: -0 sorts below +0.
+__device__ __forceinline__ int bf16_order(uint32_t bits16) {
+  int s = (int)(bits16 << 16);
+  return s ^ ((s >> 31) & 0x7fffffff);
+}
+__device__ __forceinline__ uint32_t bf16_unorder(int k) {
+  int s = k ^ ((k >> 31) & 0x7fffffff);
+  return ((uint32_t)s) >> 16;
+}
+
+}  // namespace stc

@@ -1,0 +1,33 @@
+// Internal launch interface between the C ABI (stc_api.hip) and the kernels.
+// Every launcher enqueues on `st`, never synchronises, and returns 0 or -1
+// (the HIP runtime refused a launch).  Shapes have been validated by the caller.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/stc.h"
+
+namespace stc {
+
+int launch_bounds(const stc_shape_t& s, const void* K, void* bounds, hipStream_t st);
+
+size_t route_ws_bytes(const stc_shape_t& s);
+int launch_route_pack(const stc_shape_t& s, int mode, const void* V, const float* logits,
+                      const uint8_t* kcount, int fixed_k, const uint16_t* mask_in, uint16_t* mask,
+                      uint32_t* tok_off, void* vpacked, int32_t* dev_status, void* ws,
+                      hipStream_t st);
+
+int launch_select(const stc_shape_t& s, const void* q, const void* bounds, int k_pages,
+                  int32_t* page_idx, float* score, hipStream_t st);
+
+int attention_splits(const stc_shape_t& s, int k_pages);
+size_t attention_ws_bytes(const stc_shape_t& s, int k_pages);
+int launch_attention(const stc_shape_t& s, const void* q, const void* K, const void* vpacked,
+                     const uint16_t* mask, const uint32_t* tok_off, const int32_t* page_idx,
+                     int k_pages, float* out, void* ws, hipStream_t st);
+
+int launch_compact(const void* src, const int32_t* token_idx, void* dst, int B, int Hkv, int N_src,
+                   int n_keep, int D, int32_t* dev_status, hipStream_t st);
+
+}  // namespace stc

@@ -1,0 +1,132 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2604_21335_amd as stc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "stc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(stc_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = stc.load_library()
+    names = _declared_symbols()
+    assert set(names) == set(stc.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert stc.stc_version() >= 1
+    assert stc.status_string(0) == "ok"
+    assert "aligned" in stc.status_string(stc.STC_ERR_ALIGN)
+
+
+def _shape(**kw):
+    d = dict(B=2, Hq=8, Hkv=2, D=128, N=100, G=8, v_cap_groups=800)
+    d.update(kw)
+    return stc.make_shape(**d)
+
+
+FAKE = ctypes.c_void_p(0x1000)      # aligned, never dereferenced: calls must fail earlier
+ODD = ctypes.c_void_p(0x1004)
+
+
+@pytest.mark.parametrize("kw", [dict(D=96), dict(P=8), dict(G=3), dict(G=32), dict(Hq=7),
+                                dict(Hq=64, Hkv=2), dict(N=0), dict(B=0), dict(D=64, G=16),
+                                dict(v_cap_groups=-1), dict(B=70000, Hkv=1, Hq=1)])
+def test_bad_shapes_are_rejected(kw):
+    lib = stc.load_library()
+    s = _shape(**kw)
+    assert lib.stc_build_page_bounds(ctypes.byref(s), FAKE, FAKE, None) == stc.STC_ERR_SHAPE
+    assert stc.stc_workspace_bytes(s, stc.STC_WS_ROUTE) == 0
+    assert lib.stc_select_pages(ctypes.byref(s), FAKE, FAKE, 2, FAKE, None, FAKE, 1 << 30,
+                                None) == stc.STC_ERR_SHAPE
+    assert lib.stc_decode_attention(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 2, FAKE,
+                                    FAKE, 1 << 30, None) == stc.STC_ERR_SHAPE
+
+
+def test_null_alignment_and_workspace_errors():
+    lib = stc.load_library()
+    s = _shape()
+    r = ctypes.byref(s)
+    assert lib.stc_build_page_bounds(r, None, FAKE, None) == stc.STC_ERR_NULL
+    assert lib.stc_build_page_bounds(None, FAKE, FAKE, None) == stc.STC_ERR_NULL
+    assert lib.stc_build_page_bounds(r, ODD, FAKE, None) == stc.STC_ERR_ALIGN
+    # route: mode checks, missing inputs, workspace too small
+    big = 1 << 30
+    args = lambda mode, logits, kc, fk, min_, ws, wsb: lib.stc_route_and_pack_values(  # noqa: E731
+        r, mode, FAKE, logits, kc, fk, min_, FAKE, FAKE, FAKE, None, ws, wsb, None)
+    assert args(stc.STC_ROUTE_TOPK, None, None, 2, None, FAKE, big) == stc.STC_ERR_NULL
+    assert args(stc.STC_ROUTE_MASK, None, None, 0, None, FAKE, big) == stc.STC_ERR_NULL
+    assert args(stc.STC_ROUTE_TOPK, FAKE, None, 9, None, FAKE, big) == stc.STC_ERR_SHAPE
+    assert args(stc.STC_ROUTE_TOPK, FAKE, None, -1, None, FAKE, big) == stc.STC_ERR_SHAPE
+    assert args(7, FAKE, None, 2, FAKE, FAKE, big) == stc.STC_ERR_SHAPE
+    assert args(stc.STC_ROUTE_TOPK, FAKE, None, 2, None, FAKE, 0) == stc.STC_ERR_WORKSPACE
+    assert args(stc.STC_ROUTE_TOPK, FAKE, None, 2, None, None, big) == stc.STC_ERR_WORKSPACE
+    # select: k out of range, scores need a workspace when page_score is NULL
+    assert lib.stc_select_pages(r, FAKE, FAKE, 0, FAKE, None, FAKE, big, None) == stc.STC_ERR_SHAPE
+    assert lib.stc_select_pages(r, FAKE, FAKE, 2, FAKE, None, None, 0, None) == stc.STC_ERR_WORKSPACE
+    assert lib.stc_select_pages(r, None, FAKE, 2, FAKE, None, FAKE, big, None) == stc.STC_ERR_NULL
+    assert lib.stc_select_pages(r, FAKE, ODD, 2, FAKE, FAKE, FAKE, big, None) == stc.STC_ERR_ALIGN
+    # attention: k_pages beyond NP (= 7), missing workspace
+    att = lambda k, ws, wsb, out=FAKE: lib.stc_decode_attention(  # noqa: E731
+        r, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, k, out, ws, wsb, None)
+    assert att(8, FAKE, big) == stc.STC_ERR_SHAPE
+    assert att(0, FAKE, big) == stc.STC_ERR_SHAPE
+    assert att(7, FAKE, big, None) == stc.STC_ERR_NULL
+    need = stc.stc_workspace_bytes(s, stc.STC_WS_ATTENTION, 7)
+    assert need > 0
+    assert att(7, FAKE, need - 1) == stc.STC_ERR_WORKSPACE
+    assert att(7, None, big) == stc.STC_ERR_WORKSPACE
+    # compact
+    assert lib.stc_compact_tokens(FAKE, FAKE, FAKE, 1, 1, 10, 4, 100, None, None) == stc.STC_ERR_SHAPE
+    assert lib.stc_compact_tokens(FAKE, None, FAKE, 1, 1, 10, 4, 128, None, None) == stc.STC_ERR_NULL
+
+
+def test_workspace_sizes():
+    s = _shape(N=4096, v_cap_groups=4096 * 8)
+    assert stc.stc_workspace_bytes(s, stc.STC_WS_ROUTE) == 2 * 2 * 16 * 4
+    assert stc.stc_workspace_bytes(s, stc.STC_WS_SELECT, 64) == 2 * 2 * 256 * 4
+    assert stc.stc_workspace_bytes(s, stc.STC_WS_SELECT, 256) == 0       # all pages: no scores
+    assert stc.stc_workspace_bytes(s, stc.STC_WS_ATTENTION, 300) == 0    # k beyond NP
+    assert stc.stc_workspace_bytes(s, 99, 1) == 0
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    s = _shape()
+    with pytest.raises(TypeError):
+        stc.stc_build_page_bounds(s, torch.zeros(4, dtype=torch.bfloat16),
+                                  torch.zeros(4, dtype=torch.bfloat16))
+
+
+def test_workload_generator_is_counter_based_and_seeded():
+    import torch
+    from paper_2604_21335_amd import workloads as W
+    a = W.normal(5, W.TAG_K, 1000)
+    b = torch.cat([W.normal(5, W.TAG_K, 400), W.normal(5, W.TAG_K, 600, offset=400)])
+    assert torch.equal(a, b)
+    assert not torch.equal(a, W.normal(6, W.TAG_K, 1000))
+    assert not torch.equal(a, W.normal(5, W.TAG_V, 1000))
+    big = W.normal(0, W.TAG_K, 200000)
+    assert abs(float(big.mean())) < 0.01 and abs(float(big.std()) - 1.0) < 0.01
+    w = W.WORKLOADS["qwen25_7b_32k"]
+    kc = W.counts_from_pmf(2, W.TAG_KCOUNT, (50000,), W._pmf(w)).to(torch.float64)
+    assert kc.min() == 1 and kc.max() == 8 and abs(float(kc.mean()) - 4.01) < 0.05
+    w4 = W.WORKLOADS["qwen25_7b_128k"]
+    kc = W.counts_from_pmf(4, W.TAG_KCOUNT, (50000,), W._pmf(w4)).to(torch.float64)
+    assert kc.min() >= 1 and kc.max() <= 16 and abs(float(kc.mean()) - 4.0) < 0.05
+    tiny = W.make_cache_inputs(W.shrink(W.WORKLOADS["tiny"], N=64))
+    m = W.u16_numpy(tiny["mask_in"])
+    assert m.min() >= 1 and m.max() < 16
+    vlm = W.make_cache_inputs(W.shrink(W.WORKLOADS["llava15_7b_prefix"], B=2, Hq=2, Hkv=2))
+    ti = vlm["token_idx"]
+    assert ti.shape == (2, 208) and bool((ti[:, 1:] > ti[:, :-1]).all())
+    assert int(ti[:, 143].max()) < 576 and int(ti[0, 144]) == 576
