@@ -1,188 +1,336 @@
 // Routed decode attention over the selected pages (paper Sec. 3.3: softmax over
 // full-width keys, values read from the group-packed store, dropped groups
-// contribute nothing, no renormalisation).  Split over pages with per-split
-// online-softmax partials and a fixed-order combine.
+// contribute nothing, no renormalisation).  Split over pages with online-softmax
+// partials, merged inside the workgroup and then by a fixed-order combine.
+//
+// The R <= 16 query heads of a KV head share every K page and every packed V
+// run, so both contractions are 16-wide dense tiles and run on the matrix cores
+// (v_mfma_f32_16x16x32_bf16, float accumulation):
+//   S^T[token][head] = K_page[token][:] . q[head][:]        (contract channels)
+//   O^T[chan][head] += V~^T[chan][token] . P^T[token][head] (contract tokens)
+// S^T leaves the first MFMA with tokens along the registers of a lane, which is
+// the operand layout the second MFMA wants for P^T, so the weights never leave
+// registers.  Each weight is split into two bf16 parts (p = hi + lo) so the
+// product with V carries ~2^-17 relative error instead of bf16's 2^-9.
+// V~^T (zero-filled, token-contiguous per channel) is gathered from an LDS copy
+// of the page's packed run through a per-page table of group addresses.
 #include "stc_common.hpp"
 #include "stc_kernels.hpp"
 
 namespace stc {
 
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f;  // "no token seen yet" running maximum
+constexpr int kAttnWaves = 4;        // wavefronts per workgroup
 
 // Partial result of one (query head, split): [0] running max (base-2 logits),
 // [1] sum of weights, [2 .. 2+D) weighted value sum.
 __host__ __device__ constexpr int partial_stride(int D) { return D + 2; }
 
-// ---------------------------------------------------------------------------
-// General kernel: one wavefront per (query head, split); the R wavefronts of a
-// block share the stream's pages.
-//   QK: a page of K is 16*D*2 contiguous bytes; load instruction j takes bytes
-//       [j*1024, (j+1)*1024) of it, 16 bytes per lane, so lane l holds 8
-//       channels (l % (D/8))*8.. of token j*TPI + l/(D/8).  The D/8 lanes of a
-//       token are reduced with DPP; every lane of the token ends with its logit.
-//   PV: lane l owns channels 2l, 2l+1 (D = 128) of the output; for every token
-//       of the page it fetches its dword of the token's packed group if the
-//       group was kept.
-// ---------------------------------------------------------------------------
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));  // round to nearest even
+}
+
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 template <int D>
-__global__ __launch_bounds__(1024) void attn_split_kernel(
-    const uint4* __restrict__ q, const uint4* __restrict__ K, const uint32_t* __restrict__ vpacked,
-    const uint16_t* __restrict__ mask, const uint32_t* __restrict__ tok_off,
-    const int32_t* __restrict__ page_idx, float* __restrict__ partial, float* __restrict__ out,
-    int Hq, int Hkv, int N, int NP, int G, long long cap, int k_pages, int splits,
-    int pages_per_split) {
-  constexpr int LPT = D / 8;         // lanes per token row
-  constexpr int TPI = 64 / LPT;      // tokens per load instruction
-  constexpr int NJ = kPage / TPI;    // load instructions per page
-  constexpr int CL = D / 2;          // lanes that own output channels (2 each)
-  const int stream = blockIdx.y;
-  const int split = blockIdx.x;
+struct AttnCfg {
+  static constexpr int KC = D / 32;                  // QK MFMAs per page (32 channels each)
+  static constexpr int CB = D / 16;                  // output channel blocks of 16
+  static constexpr int UNITS = D / 8;                // 16-byte value units per token
+  static constexpr int VBYTES = kPage * D * 2;       // largest packed run of a page
+  static constexpr int TBYTES = kPage * UNITS * 4;   // address table of a page
+  static constexpr int ZBYTES = 32;                  // zeros read for dropped groups
+  static constexpr int WAVE_LDS = 2 * VBYTES + 2 * TBYTES + ZBYTES;
+};
+
+// One wavefront walks `ppw` pages of one stream, two at a time; the 4 wavefronts
+// of a workgroup then merge their partial results in LDS.
+template <int D>
+__global__ __launch_bounds__(64 * kAttnWaves) void attn_mfma_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ K,
+    const unsigned char* __restrict__ vpacked, const uint16_t* __restrict__ mask,
+    const uint32_t* __restrict__ tok_off, const int32_t* __restrict__ page_idx,
+    float* __restrict__ partial, float* __restrict__ out, int Hq, int Hkv, int N, int NP, int G,
+    long long cap, int k_pages, int splits, int ppw) {
+  using C = AttnCfg<D>;
+  __shared__ __align__(16) unsigned char lds[kAttnWaves * C::WAVE_LDS];
+  const int stream = blockIdx.y, split = blockIdx.x;
   const int b = stream / Hkv, kvh = stream % Hkv;
   const int R = Hq / Hkv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int head = b * Hq + kvh * R + wave;  // flat (b, query head)
-  const int sub = lane % LPT, row = lane / LPT;
+  const int r16 = lane & 15, kg = lane >> 4;  // MFMA row/column and k-group of this lane
   const int gd = D / G;
+  const int gbytes = gd * 2;
   const float scale = kLog2e / sqrtf((float)D);
 
-  float qf[8];
-  {
-    const uint4 v = q[(size_t)head * LPT + sub];
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  unsigned char* wl = lds + wave * C::WAVE_LDS;
+  const uint32_t zero_addr = 2 * C::VBYTES + 2 * C::TBYTES;  // offsets relative to wl
+  if (lane < C::ZBYTES / 4) ((uint32_t*)(wl + zero_addr))[lane] = 0;
+
+  // B operand of the QK product: this lane's 8 channels of head r16 for every 32-channel step
+  uint4 qreg[C::KC];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      qf[2 * i] = bf16_lo(w[i]) * scale;
-      qf[2 * i + 1] = bf16_hi(w[i]) * scale;
-    }
+  for (int j = 0; j < C::KC; ++j) {
+    qreg[j] = make_uint4(0, 0, 0, 0);
+    if (r16 < R)
+      qreg[j] = *(const uint4*)(q + ((size_t)b * Hq + kvh * R + r16) * D + 32 * j + 8 * kg);
   }
-  // value side: which group this lane's two channels belong to
-  const bool vlane = lane < CL;
-  const int g = vlane ? (2 * lane) / gd : 0;
-  const int within = vlane ? (2 * lane) % gd : 0;  // channel offset inside the group
-  const uint32_t below = (1u << g) - 1u;
-  const uint32_t* vbase = vpacked + (size_t)stream * (size_t)cap * (gd / 2);
 
-  float m_run = kNegBig, l_part = 0.f, acc0 = 0.f, acc1 = 0.f;
+  f32x4 acc[C::CB];
+#pragma unroll
+  for (int cb = 0; cb < C::CB; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run = kNegBig, l_part = 0.f;
 
-  const int pi0 = split * pages_per_split;
-  const int pi1 = min(pi0 + pages_per_split, k_pages);
-  for (int pi = pi0; pi < pi1; ++pi) {
-    const int p = page_idx[(size_t)stream * k_pages + pi];
-    if (p < 0 || p >= NP) continue;  // wave-uniform
-    const int t0 = p * kPage;
-    // per-token mask and offset of the page, one token per lane (lanes 0..15)
-    uint32_t mk = 0, off = 0;
-    if (lane < kPage && t0 + lane < N) {
-      mk = mask[(size_t)stream * N + t0 + lane];
-      off = tok_off[(size_t)stream * (N + 1) + t0 + lane];
-    }
-    // ---- logits
-    const uint4* kp = K + ((size_t)stream * N + t0) * LPT;
-    float s[NJ];
-    float m_page = kNegBig;
+  const uint16_t* Ks = K + (size_t)stream * N * D;
+  const uint16_t* mask_s = mask + (size_t)stream * N;
+  const uint32_t* off_s = tok_off + (size_t)stream * (N + 1);
+  const unsigned char* vs = vpacked + (size_t)stream * (size_t)cap * gbytes;
+  const int32_t* pidx = page_idx + (size_t)stream * k_pages;
+
+  const int pi0 = (split * kAttnWaves + wave) * ppw;
+  const int pi1 = min(pi0 + ppw, k_pages);
+  const int ttok = lane >> 2, tq = lane & 3;  // table-building role: token and quarter of its units
+  const uint32_t j2 = (uint32_t)(r16 & 7) * 2;  // byte offset of this lane's channel inside a unit
+  const int half = r16 >> 3;
+
+  for (int pi = pi0; pi < pi1; pi += 2) {
+    int pg[2];
+    pg[0] = pidx[pi];
+    pg[1] = (pi + 1 < pi1) ? pidx[pi + 1] : -1;
+    uint4 kreg[2][C::KC];
+    bool tokvalid[2];
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-      const int tok = j * TPI + row;
-      const bool valid = t0 + tok < N;
-      float d = 0.f;
-      if (valid) {
-        const uint4 v = kp[j * 64 + lane];
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    for (int x = 0; x < 2; ++x) {
+      const bool pvalid = pg[x] >= 0 && pg[x] < NP;  // wave-uniform
+      const int t0 = pvalid ? pg[x] * kPage : 0;
+      // ---- K rows: lane (token r16, k-group kg) takes 16 bytes per 32-channel step
+      tokvalid[x] = pvalid && (t0 + r16 < N);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          d = fmaf(qf[2 * i], bf16_lo(w[i]), d);
-          d = fmaf(qf[2 * i + 1], bf16_hi(w[i]), d);
-        }
+      for (int j = 0; j < C::KC; ++j) {
+        kreg[x][j] = make_uint4(0, 0, 0, 0);
+        if (tokvalid[x])
+          kreg[x][j] = *(const uint4*)(Ks + (size_t)(t0 + r16) * D + 32 * j + 8 * kg);
       }
-      d = row_tree_sum<LPT>(d);
-      s[j] = valid ? d : kNegBig;
-      m_page = fmaxf(m_page, s[j]);
+      // ---- packed V run of the page -> LDS, plus the table of unit addresses
+      unsigned char* vbuf = wl + x * C::VBYTES;
+      uint32_t* tab = (uint32_t*)(wl + 2 * C::VBYTES + x * C::TBYTES);
+      uint32_t mk = 0, off = 0;
+      long long run0 = 0, run1 = 0;
+      if (pvalid) {
+        if (t0 + ttok < N) {
+          mk = mask_s[t0 + ttok];
+          off = off_s[t0 + ttok];
+        }
+        run0 = off_s[t0];
+        run1 = off_s[min(t0 + kPage, N)];
+      }
+      run1 = min(run1, cap);
+      long long rg = run1 - run0;               // groups of this page present in the store
+      rg = max(0ll, min(rg, (long long)kPage * G));
+      const int run_bytes = (int)rg * gbytes;
+      const unsigned char* vsrc = vs + run0 * gbytes;
+#pragma unroll
+      for (int i = 0; i < C::VBYTES / 1024; ++i) {
+        const int bo = (i * 64 + lane) * 16;
+        if (bo < run_bytes) *(uint4*)(vbuf + bo) = *(const uint4*)(vsrc + bo);
+      }
+#pragma unroll
+      for (int uu = 0; uu < C::UNITS / 4; ++uu) {
+        const int u = tq * (C::UNITS / 4) + uu;      // 8-channel unit of token ttok
+        const int g = (u * 8) / gd;
+        const int within = u * 16 - g * gbytes;      // bytes into the group
+        const long long slot = (long long)off - run0 + __popc(mk & ((1u << g) - 1u));
+        const bool kept = ((mk >> g) & 1u) && slot >= 0 && slot < rg;
+        const uint32_t ent = kept ? (uint32_t)(x * C::VBYTES + (int)slot * gbytes + within)
+                                  : zero_addr;
+        tab[((u & 1) * C::CB + (u >> 1)) * kPage + ttok] = ent;
+      }
     }
-    // maximum over the page: across the token rows of the wavefront
-    for (int dlt = LPT; dlt < 64; dlt <<= 1) m_page = fmaxf(m_page, __shfl_xor(m_page, dlt));
-    const float m_new = fmaxf(m_run, m_page);
+    wave_lds_sync();
+
+    // ---- logits S^T[token][head] for both pages
+    float s[2][4];
+    float mx = kNegBig;
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      f32x4 sv = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < C::KC; ++j)
+        sv = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kreg[x][j]), as_bf16x8(qreg[j]), sv,
+                                                     0, 0, 0);
+      // this lane holds tokens 4*kg + i of page x for head r16
+      const bool pvalid = pg[x] >= 0 && pg[x] < NP;
+      const int t0 = pvalid ? pg[x] * kPage : 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const bool tv = pvalid && (t0 + 4 * kg + i < N);
+        s[x][i] = tv ? sv[i] * scale : kNegBig;
+        mx = fmaxf(mx, s[x][i]);
+      }
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx);
     const float rescale = exp2f(m_run - m_new);
     m_run = m_new;
-    float pw[NJ];
+    float p[8];
     float psum = 0.f;
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-      pw[j] = s[j] > 0.5f * kNegBig ? exp2f(s[j] - m_new) : 0.f;
-      psum += pw[j];
-    }
-    l_part = l_part * rescale + psum;  // this lane's token row only
-    acc0 *= rescale;
-    acc1 *= rescale;
-    // ---- values: issue the page's loads, then accumulate
-    uint32_t vv[kPage];
+    for (int x = 0; x < 2; ++x)
 #pragma unroll
-    for (int tt = 0; tt < kPage; ++tt) {
-      const uint32_t mt = __builtin_amdgcn_readlane(mk, tt);
-      const uint32_t ot = __builtin_amdgcn_readlane(off, tt);
-      const long long slot = (long long)ot + __popc(mt & below);
-      vv[tt] = 0;
-      if (vlane && ((mt >> g) & 1u) && slot < cap) vv[tt] = vbase[slot * (gd / 2) + within / 2];
-    }
+      for (int i = 0; i < 4; ++i) {
+        p[x * 4 + i] = s[x][i] > 0.5f * kNegBig ? exp2f(s[x][i] - m_new) : 0.f;
+        psum += p[x * 4 + i];
+      }
+    l_part = l_part * rescale + psum;
 #pragma unroll
-    for (int tt = 0; tt < kPage; ++tt) {
-      const float pt = readlane_f32(pw[tt / TPI], (tt % TPI) * LPT);
-      acc0 = fmaf(pt, bf16_lo(vv[tt]), acc0);
-      acc1 = fmaf(pt, bf16_hi(vv[tt]), acc1);
+    for (int cb = 0; cb < C::CB; ++cb) acc[cb] *= rescale;
+    // weights as two bf16 parts; contraction index: (kg, e) e<4 page 0, e>=4 page 1
+    uint4 phi, plo;
+    {
+      uint32_t h[4], l[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        h[r] = pack_bf16(p[2 * r], p[2 * r + 1]);
+        l[r] = pack_bf16(p[2 * r] - bf16_lo(h[r]), p[2 * r + 1] - bf16_hi(h[r]));
+      }
+      phi = make_uint4(h[0], h[1], h[2], h[3]);
+      plo = make_uint4(l[0], l[1], l[2], l[3]);
     }
+    // ---- O^T += V~^T . P^T per 16-channel block
+#pragma unroll
+    for (int cb = 0; cb < C::CB; ++cb) {
+      uint32_t a[4];
+#pragma unroll
+      for (int x = 0; x < 2; ++x) {
+        const uint32_t* tab = (const uint32_t*)(wl + 2 * C::VBYTES + x * C::TBYTES);
+        const uint4 e = *(const uint4*)(tab + (half * C::CB + cb) * kPage + 4 * kg);
+        const uint32_t v0 = *(const uint16_t*)(wl + e.x + j2);
+        const uint32_t v1 = *(const uint16_t*)(wl + e.y + j2);
+        const uint32_t v2 = *(const uint16_t*)(wl + e.z + j2);
+        const uint32_t v3 = *(const uint16_t*)(wl + e.w + j2);
+        a[2 * x] = v0 | (v1 << 16);
+        a[2 * x + 1] = v2 | (v3 << 16);
+      }
+      const bf16x8 av = as_bf16x8(make_uint4(a[0], a[1], a[2], a[3]));
+      acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(phi), acc[cb], 0, 0, 0);
+      acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(plo), acc[cb], 0, 0, 0);
+    }
+    wave_lds_sync();  // the next pair overwrites the staging buffers
   }
-  // sum of weights: one lane per token row holds that row's share
-  float l = (sub == 0) ? l_part : 0.f;
-  for (int dlt = 32; dlt >= 1; dlt >>= 1) l += __shfl_xor(l, dlt);
 
-  if (splits == 1) {
-    if (vlane) {
-      const float inv = l > 0.f ? 1.f / l : 0.f;
-      float2* o = (float2*)(out + (size_t)head * D) + lane;
-      *o = make_float2(acc0 * inv, acc1 * inv);
+  // sum of weights of head r16 over this wavefront's tokens
+  float l = l_part + __shfl_xor(l_part, 16);
+  l += __shfl_xor(l, 32);
+
+  // ---- merge the 4 wavefronts: each leaves (m, l, acc[R][D]) in its own LDS region
+  float* macc = (float*)wl;                    // [16][D]
+  float* mml = (float*)(wl + 16 * D * 4);      // [16][2]
+  static_assert(16 * D * 4 + 16 * 2 * 4 <= C::WAVE_LDS, "merge buffer fits the staging area");
+#pragma unroll
+  for (int cb = 0; cb < C::CB; ++cb)
+    *(f32x4*)(macc + r16 * D + cb * 16 + 4 * kg) = acc[cb];  // channels cb*16 + 4*kg + i
+  if (kg == 0) {
+    mml[r16 * 2] = m_run;
+    mml[r16 * 2 + 1] = l;
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < R * D; i += 64 * kAttnWaves) {
+    const int head = i / D, c = i % D;
+    float mw[kAttnWaves], m = kNegBig;
+#pragma unroll
+    for (int w = 0; w < kAttnWaves; ++w) {
+      mw[w] = ((const float*)(lds + w * C::WAVE_LDS + 16 * D * 4))[head * 2];
+      m = fmaxf(m, mw[w]);
     }
-  } else {
-    float* pr = partial + ((size_t)head * splits + split) * partial_stride(D);
-    if (lane == 0) {
-      pr[0] = m_run;
-      pr[1] = l;
+    float lsum = 0.f, a = 0.f;
+#pragma unroll
+    for (int w = 0; w < kAttnWaves; ++w) {
+      const float wgt = exp2f(mw[w] - m);
+      lsum = fmaf(wgt, ((const float*)(lds + w * C::WAVE_LDS + 16 * D * 4))[head * 2 + 1], lsum);
+      a = fmaf(wgt, ((const float*)(lds + w * C::WAVE_LDS))[head * D + c], a);
     }
-    if (vlane) {
-      pr[2 + 2 * lane] = acc0;
-      pr[2 + 2 * lane + 1] = acc1;
+    const size_t hf = (size_t)b * Hq + kvh * R + head;
+    if (splits == 1) {
+      out[hf * D + c] = lsum > 0.f ? a / lsum : 0.f;
+    } else {
+      float* pr = partial + (hf * splits + split) * partial_stride(D);
+      pr[2 + c] = a;
+      if (c == 0) {
+        pr[0] = m;
+        pr[1] = lsum;
+      }
     }
   }
 }
 
-// Merge the split partials of one query head in ascending split order.
+// Merge the split partials of one query head in ascending split order.  Each
+// thread owns one channel; partials are fetched 8 splits at a time so the loads
+// of a batch are in flight together.
 template <int D>
 __global__ __launch_bounds__(D) void attn_combine_kernel(const float* __restrict__ partial,
                                                          float* __restrict__ out, int splits) {
+  constexpr int ST = partial_stride(D);
   const int head = blockIdx.x;
   const int c = threadIdx.x;
-  const float* pr = partial + (size_t)head * splits * partial_stride(D);
+  const float* pr = partial + (size_t)head * splits * ST;
   float m = kNegBig;
-  for (int s = 0; s < splits; ++s) m = fmaxf(m, pr[s * partial_stride(D)]);
+  for (int s0 = 0; s0 < splits; s0 += 8) {
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = s0 + i < splits ? pr[(s0 + i) * ST] : kNegBig;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) m = fmaxf(m, v[i]);
+  }
   float l = 0.f, a = 0.f;
-  for (int s = 0; s < splits; ++s) {
-    const float* ps = pr + s * partial_stride(D);
-    const float w = exp2f(ps[0] - m);
-    l = fmaf(w, ps[1], l);
-    a = fmaf(w, ps[2 + c], a);
+  for (int s0 = 0; s0 < splits; s0 += 8) {
+    float ms[8], ls[8], as[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const bool ok = s0 + i < splits;
+      const float* ps = pr + (s0 + i) * ST;
+      ms[i] = ok ? ps[0] : kNegBig;
+      ls[i] = ok ? ps[1] : 0.f;
+      as[i] = ok ? ps[2 + c] : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float w = exp2f(ms[i] - m);
+      l = fmaf(w, ls[i], l);
+      a = fmaf(w, as[i], a);
+    }
   }
   out[(size_t)head * D + c] = l > 0.f ? a / l : 0.f;
 }
 
-int attention_splits(const stc_shape_t& s, int k_pages) {
+// Pages per wavefront: as many as keep at least ~1024 workgroups in the grid
+// (4 per CU), and never more than the pages there are.
+static int attention_ppw(const stc_shape_t& s, int k_pages) {
   const int streams = s.B * s.Hkv;
-  // enough workgroups to fill 256 CUs several times over, at least 2 pages each
-  int want = (2048 + streams - 1) / streams;
-  int max_splits = (k_pages + 1) / 2;
-  int splits = want < 1 ? 1 : want;
-  if (splits > max_splits) splits = max_splits;
-  if (splits < 1) splits = 1;
-  const int pps = (k_pages + splits - 1) / splits;
-  return (k_pages + pps - 1) / pps;  // no empty splits
+  int ppw = 8;
+  while (ppw > 2 &&
+         (long long)streams * ((k_pages + kAttnWaves * ppw - 1) / (kAttnWaves * ppw)) < 1024)
+    ppw >>= 1;
+  while (ppw > 2 && kAttnWaves * (ppw / 2) >= k_pages) ppw >>= 1;  // no idle wavefronts
+  return ppw;
+}
+
+int attention_splits(const stc_shape_t& s, int k_pages) {
+  const int per_block = kAttnWaves * attention_ppw(s, k_pages);
+  return (k_pages + per_block - 1) / per_block;
 }
 
 size_t attention_ws_bytes(const stc_shape_t& s, int k_pages) {
@@ -196,19 +344,20 @@ int launch_attention(const stc_shape_t& s, const void* q, const void* K, const v
                      int k_pages, float* out, void* ws, hipStream_t st) {
   const int NP = (s.N + kPage - 1) / kPage;
   const int streams = s.B * s.Hkv;
-  const int R = s.Hq / s.Hkv;
+  const int ppw = attention_ppw(s, k_pages);
   const int splits = attention_splits(s, k_pages);
-  const int pps = (k_pages + splits - 1) / splits;
   dim3 grid(splits, streams);
   float* partial = (float*)ws;
   if (s.D == 128)
-    attn_split_kernel<128><<<grid, 64 * R, 0, st>>>(
-        (const uint4*)q, (const uint4*)K, (const uint32_t*)vpacked, mask, tok_off, page_idx,
-        partial, out, s.Hq, s.Hkv, s.N, NP, s.G, (long long)s.v_cap_groups, k_pages, splits, pps);
+    attn_mfma_kernel<128><<<grid, 64 * kAttnWaves, 0, st>>>(
+        (const uint16_t*)q, (const uint16_t*)K, (const unsigned char*)vpacked, mask, tok_off,
+        page_idx, partial, out, s.Hq, s.Hkv, s.N, NP, s.G, (long long)s.v_cap_groups, k_pages,
+        splits, ppw);
   else
-    attn_split_kernel<64><<<grid, 64 * R, 0, st>>>(
-        (const uint4*)q, (const uint4*)K, (const uint32_t*)vpacked, mask, tok_off, page_idx,
-        partial, out, s.Hq, s.Hkv, s.N, NP, s.G, (long long)s.v_cap_groups, k_pages, splits, pps);
+    attn_mfma_kernel<64><<<grid, 64 * kAttnWaves, 0, st>>>(
+        (const uint16_t*)q, (const uint16_t*)K, (const unsigned char*)vpacked, mask, tok_off,
+        page_idx, partial, out, s.Hq, s.Hkv, s.N, NP, s.G, (long long)s.v_cap_groups, k_pages,
+        splits, ppw);
   if (hipGetLastError() != hipSuccess) return -1;
   if (splits > 1) {
     if (s.D == 128)
