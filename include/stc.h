@@ -146,7 +146,9 @@ int stc_select_pages(const stc_shape_t *shape, const void *q, const void *bounds
  *            [0, NP) are skipped; a page must not be listed twice
  *   out      [B, Hq, D] float, out
  *   ws       stc_workspace_bytes(shape, STC_WS_ATTENTION, k_pages) bytes
- * Value slots at or beyond v_cap_groups are treated as dropped.
+ * Value slots at or beyond v_cap_groups are treated as dropped; v_cap_groups >= 1.
+ * One stream's keys (N*D*2 bytes) and packed store (v_cap_groups*(D/G)*2 bytes) must
+ * each stay below 4 GiB.
  */
 int stc_decode_attention(const stc_shape_t *shape, const void *q, const void *K,
                          const void *vpacked, const uint16_t *mask, const uint32_t *tok_off,

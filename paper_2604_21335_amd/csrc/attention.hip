@@ -12,8 +12,9 @@
 // the operand layout the second MFMA wants for P^T, so the weights never leave
 // registers.  Each weight is split into two bf16 parts (p = hi + lo) so the
 // product with V carries ~2^-17 relative error instead of bf16's 2^-9.
-// V~^T (zero-filled, token-contiguous per channel) is gathered from an LDS copy
-// of the page's packed run through a per-page table of group addresses.
+// Both K and the routed (zero-filled) V of a page pass through a dense LDS tile.
+#include <stdlib.h>
+
 #include "stc_common.hpp"
 #include "stc_kernels.hpp"
 
@@ -23,6 +24,10 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
+// 16-byte register values are native vectors: copies of the HIP uint4 struct go through
+// memcpy, which can leave a register array in scratch memory
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f;  // "no token seen yet" running maximum
@@ -32,7 +37,7 @@ constexpr int kAttnWaves = 4;        // wavefronts per workgroup
 // [1] sum of weights, [2 .. 2+D) weighted value sum.
 __host__ __device__ constexpr int partial_stride(int D) { return D + 2; }
 
-__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   f32x2 v = {a, b};
@@ -47,25 +52,66 @@ __device__ __forceinline__ void wave_lds_sync() {
 
 template <int D>
 struct AttnCfg {
-  static constexpr int KC = D / 32;                  // QK MFMAs per page (32 channels each)
-  static constexpr int CB = D / 16;                  // output channel blocks of 16
-  static constexpr int UNITS = D / 8;                // 16-byte value units per token
-  static constexpr int VBYTES = kPage * D * 2;       // largest packed run of a page
-  static constexpr int TBYTES = kPage * UNITS * 4;   // address table of a page
-  static constexpr int ZBYTES = 32;                  // zeros read for dropped groups
-  static constexpr int WAVE_LDS = 2 * VBYTES + 2 * TBYTES + ZBYTES;
+  static constexpr int KC = D / 32;         // QK MFMAs per page (32 channels each)
+  static constexpr int CB = D / 16;         // output channels per lane and token (see PV below)
+  static constexpr int LPR = D / 8;         // 16-byte pieces (lanes of a flat load) per token row
+  static constexpr int NLD = kPage * D * 2 / 1024;  // flat 1 KiB loads per page of K (or of a full V run)
+  static constexpr int ROW = D * 2 + 16;    // LDS bytes per token row of the K tile (padded)
+  static constexpr int TILE = kPage * ROW;  // K tile of a page; reused for the page's packed V run
+  static constexpr int META = 2 * TILE;     // per pair: 2 x 16 words (mask | relative offset << 16)
+  static constexpr int ZERO = META + 128;   // 16 zero bytes: what dropped units read
+  static constexpr int WAVE_LDS = ZERO + 16;
+  static_assert(16 * D * 4 + 16 * 2 * 4 <= 2 * TILE, "merge buffer fits the tiles");
 };
 
-// One wavefront walks `ppw` pages of one stream, two at a time; the 4 wavefronts
+// 16 zero bytes in device memory: where lanes beyond the end of a packed run read
+__device__ u32x4 stc_zero16 = {0u, 0u, 0u, 0u};  // never written
+
+#ifdef STC_TUNE
+// tuning builds only: per-workgroup phase timestamps (100 MHz counter) of wave 0
+__device__ long long* stc_dbg_ptr = nullptr;
+#define STC_MARK(slot, dep)                                                                  \
+  do {                                                                                       \
+    if (dbg && wave == 0) {                                                                  \
+      unsigned long long t_;                                                                 \
+      asm volatile("s_memrealtime %0\n s_waitcnt lgkmcnt(0)" : "=s"(t_) : "v"(dep) : "memory"); \
+      if (lane == 0) dbg[(blockIdx.y * gridDim.x + blockIdx.x) * 16 + (slot)] = (long long)t_; \
+    }                                                                                        \
+  } while (0)
+#else
+#define STC_MARK(slot, dep) do {} while (0)
+#endif
+
+// One wavefront walks 2*PAIRS pages of one stream, two at a time; the 4 wavefronts
 // of a workgroup then merge their partial results in LDS.
-template <int D>
+//
+// Per pair of pages:
+//   1. K pages and packed V runs are read flat (every request is 1 KiB of adjacent
+//      addresses, 16 bytes per lane) and staged in LDS.  Loading straight into the
+//      MFMA operand layout, or unit by unit for V, turns each request into scattered
+//      32..64-byte pieces and costs about 30 % of the achievable bandwidth.
+//   2. QK: lane (token r16, k-group kg) reads 16 bytes per 32-channel step from the
+//      K tile; S^T = K.q^T; online softmax per head; weights split into hi+lo bf16.
+//   3. PV: lane (r16, kg) owns the CB adjacent channels r16*CB.. (one 16-byte value
+//      unit for D = 128).  For each of its 8 tokens it computes where that unit sits
+//      in the staged run (slot = offset of the token + rank of the group among the
+//      kept ones) or takes zeros if the group was dropped, reads it, transposes the
+//      8x8 block in registers with byte permutes and feeds MFMA row m of block cb
+//      <-> channel m*CB + cb.  The accumulators of a lane cover channels 32*kg...
+// Request order: page indices; masks/offsets of every page and the K rows of the
+// first pair; then, as soon as the offsets are there, the pair's V runs and the
+// next pair's K rows.  All loads are unconditional (addresses of absent pages or
+// tokens collapse to one valid location and the result is discarded) so that they
+// stay in flight across the arithmetic.
+template <int D, int PAIRS>
 __global__ __launch_bounds__(64 * kAttnWaves) void attn_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K,
     const unsigned char* __restrict__ vpacked, const uint16_t* __restrict__ mask,
     const uint32_t* __restrict__ tok_off, const int32_t* __restrict__ page_idx,
     float* __restrict__ partial, float* __restrict__ out, int Hq, int Hkv, int N, int NP, int G,
-    long long cap, int k_pages, int splits, int ppw) {
+    uint32_t cap, int k_pages, int splits) {
   using C = AttnCfg<D>;
+  constexpr int ppw = 2 * PAIRS;  // pages per wavefront
   __shared__ __align__(16) unsigned char lds[kAttnWaves * C::WAVE_LDS];
   const int stream = blockIdx.y, split = blockIdx.x;
   const int b = stream / Hkv, kvh = stream % Hkv;
@@ -73,118 +119,168 @@ __global__ __launch_bounds__(64 * kAttnWaves) void attn_mfma_kernel(
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r16 = lane & 15, kg = lane >> 4;  // MFMA row/column and k-group of this lane
   const int gd = D / G;
-  const int gbytes = gd * 2;
+  const uint32_t gbytes = gd * 2;
+  const int lg_upg = 31 - __clz(gd / 8);  // log2(16-byte units per group)
   const float scale = kLog2e / sqrtf((float)D);
 
   unsigned char* wl = lds + wave * C::WAVE_LDS;
-  const uint32_t zero_addr = 2 * C::VBYTES + 2 * C::TBYTES;  // offsets relative to wl
-  if (lane < C::ZBYTES / 4) ((uint32_t*)(wl + zero_addr))[lane] = 0;
+#ifdef STC_TUNE
+  long long* dbg = stc_dbg_ptr;
+#endif
+  STC_MARK(0, lane);
+  if (lane < 4) *(uint32_t*)(wl + C::ZERO + lane * 4) = 0;
 
-  // B operand of the QK product: this lane's 8 channels of head r16 for every 32-channel step
-  uint4 qreg[C::KC];
-#pragma unroll
-  for (int j = 0; j < C::KC; ++j) {
-    qreg[j] = make_uint4(0, 0, 0, 0);
-    if (r16 < R)
-      qreg[j] = *(const uint4*)(q + ((size_t)b * Hq + kvh * R + r16) * D + 32 * j + 8 * kg);
+  // per-stream bases (wave-uniform); everything below is addressed with 32-bit byte offsets
+  const unsigned char* Ks = (const unsigned char*)K + (size_t)stream * N * D * 2;
+  const unsigned char* mask_s = (const unsigned char*)mask + (size_t)stream * N * 2;
+  const unsigned char* off_s = (const unsigned char*)tok_off + (size_t)stream * (N + 1) * 4;
+  const unsigned char* vs = vpacked + (size_t)stream * (size_t)cap * gbytes;
+
+  // this wavefront's pages: lane i holds page pi0 + i (or -1)
+  const int pi0 = (split * kAttnWaves + wave) * ppw;
+  const int npages = max(0, min(ppw, k_pages - pi0));
+  int my_pg = -1;
+  if (lane < npages) {
+    my_pg = page_idx[(size_t)stream * k_pages + pi0 + lane];
+    if (my_pg < 0 || my_pg >= NP) my_pg = -1;
   }
+  const int npairs = (npages + 1) / 2;
+
+  // PV role: the value unit this lane reads for each of its tokens
+  const uint32_t unit = (D == 128) ? r16 : (r16 >> 1);
+  const uint32_t u_g = unit >> lg_upg;                    // its group
+  const uint32_t u_below = (1u << u_g) - 1u;              // groups stored before it
+  const uint32_t u_within = (unit - (u_g << lg_upg)) * 16 + ((D == 128) ? 0 : (r16 & 1) * 8);
+
+  // lanes 0..15 carry the tokens of the pair's first page, 16..31 of its second page
+  uint32_t mk[PAIRS], off[PAIRS], run0[PAIRS][2], run1[PAIRS][2];
+  bool mvalid[PAIRS];
+  u32x4 kreg[PAIRS][2][C::NLD];
+  int pgs[PAIRS][2];
+
+  // Lanes 0..15 fetch mask and offset of the tokens of the pair's first page, lanes
+  // 16..31 of its second page; lanes 32 and 33 fetch the offset just past each page
+  // (the end of its packed run).  Vector loads on purpose: scalar loads of these
+  // scattered words queue up in the scalar cache for several microseconds.
+  auto issue_meta = [&](int it) {
+#pragma unroll
+    for (int x = 0; x < 2; ++x) pgs[it][x] = __builtin_amdgcn_readlane(my_pg, 2 * it + x);
+    const int pg = (lane & 1) ? pgs[it][1] : pgs[it][0];          // lanes 32, 33
+    const int pgt = (lane & 16) ? pgs[it][1] : pgs[it][0];        // token lanes
+    const uint32_t t = (pgt < 0 ? 0 : pgt * kPage) + r16;
+    const bool tv = lane < 32 && pgt >= 0 && t < (uint32_t)N;
+    const uint32_t tend = pg < 0 ? 0u : min((uint32_t)pg * kPage + kPage, (uint32_t)N);
+    const uint32_t oi = tv ? t : ((lane == 32 || lane == 33) ? tend : 0u);
+    mvalid[it] = tv;
+    mk[it] = *(const uint16_t*)(mask_s + (tv ? t : 0u) * 2);  // discarded later if !tv
+    off[it] = *(const uint32_t*)(off_s + oi * 4);
+  };
+  // start and end of the packed runs of a pair (wave-uniform), once the offsets are there
+  auto finish_meta = [&](int it) {
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      run0[it][x] = __builtin_amdgcn_readlane(off[it], 16 * x);  // token 0 of a page is valid
+      run1[it][x] = __builtin_amdgcn_readlane(off[it], 32 + x);
+    }
+  };
+  auto issue_k = [&](int it) {
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      const int pg = pgs[it][x];
+      const uint32_t t0 = pg < 0 ? 0 : pg * kPage;
+#pragma unroll
+      for (int j = 0; j < C::NLD; ++j) {
+        const uint32_t tok = (j * 64 + lane) / C::LPR;
+        const bool tv = pg >= 0 && (t0 + tok < (uint32_t)N);
+        // rows of absent tokens read the stream's first bytes: their logits are discarded
+        const uint32_t ko = tv ? t0 * (D * 2) + (j * 64 + lane) * 16 : 0;
+        kreg[it][x][j] = *(const u32x4*)(Ks + ko);
+      }
+    }
+  };
+  // Groups of a page present in the store (wave-uniform).
+  auto run_groups = [&](int it, int x) -> uint32_t {
+    const uint32_t r0 = run0[it][x];
+    const uint32_t r1 = pgs[it][x] < 0 ? 0u : min(run1[it][x], cap);
+    const uint32_t rg = r1 > r0 ? r1 - r0 : 0u;
+    return min(rg, (uint32_t)(kPage * G));
+  };
+  // Packed V runs of a pair, flat; lanes past the end of a run read the zero line.
+#define STC_ISSUE_V(it, vreg)                                                                  \
+  static_for<0, 2>([&](auto x) {                                                               \
+    const uint32_t rbytes = run_groups(it, x) * gbytes + vgate;                                \
+    const unsigned char* vrun = vs + (size_t)run0[it][x] * gbytes;                             \
+    static_for<0, C::NLD>([&](auto j) {                                                        \
+      const uint32_t bo = (j * 64 + lane) * 16;                                                \
+      /* one address computed with integer selects, so that it stays a single request */      \
+      const uintptr_t a = bo < rbytes ? (uintptr_t)vrun + bo : (uintptr_t)&stc_zero16;         \
+      vreg[x][j] = *(const __attribute__((address_space(1))) u32x4*)a; /* global, not flat */  \
+    });                                                                                        \
+  })
 
   f32x4 acc[C::CB];
 #pragma unroll
   for (int cb = 0; cb < C::CB; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
   float m_run = kNegBig, l_part = 0.f;
 
-  const uint16_t* Ks = K + (size_t)stream * N * D;
-  const uint16_t* mask_s = mask + (size_t)stream * N;
-  const uint32_t* off_s = tok_off + (size_t)stream * (N + 1);
-  const unsigned char* vs = vpacked + (size_t)stream * (size_t)cap * gbytes;
-  const int32_t* pidx = page_idx + (size_t)stream * k_pages;
+  STC_MARK(1, my_pg);
+  // The scheduling fences keep the request order stated above.
+#pragma unroll
+  for (int it = 0; it < PAIRS; ++it) issue_meta(it);
+  __builtin_amdgcn_sched_barrier(0);
+  STC_MARK(12, lane);
+  issue_k(0);
+  __builtin_amdgcn_sched_barrier(0);
+  STC_MARK(13, lane);
 
-  const int pi0 = (split * kAttnWaves + wave) * ppw;
-  const int pi1 = min(pi0 + ppw, k_pages);
-  const int ttok = lane >> 2, tq = lane & 3;  // table-building role: token and quarter of its units
-  const uint32_t j2 = (uint32_t)(r16 & 7) * 2;  // byte offset of this lane's channel inside a unit
-  const int half = r16 >> 3;
+  // B operand of the QK product: this lane's 8 channels of head r16 for every 32-channel step
+  u32x4 qreg[C::KC];
+  {
+    const unsigned char* qs = (const unsigned char*)q + ((size_t)b * Hq + kvh * R) * D * 2;
+    const uint32_t qo = ((r16 < R ? r16 : 0) * D + 8 * kg) * 2;
+#pragma unroll
+    for (int j = 0; j < C::KC; ++j)
+      qreg[j] = *(const u32x4*)(qs + (qo + 64 * j));  // columns >= R repeat head 0, never used
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  STC_MARK(7, lane);
 
-  for (int pi = pi0; pi < pi1; pi += 2) {
-    int pg[2];
-    pg[0] = pidx[pi];
-    pg[1] = (pi + 1 < pi1) ? pidx[pi + 1] : -1;
-    uint4 kreg[2][C::KC];
-    bool tokvalid[2];
+  // logits of a pair, online softmax; leaves the weights of the pair in phi/plo
+  u32x4 phi, plo;
+  auto qk_softmax = [&](int it) {
+    // K rows of the pair -> LDS tiles (row stride ROW), then back in MFMA operand layout
 #pragma unroll
-    for (int x = 0; x < 2; ++x) {
-      const bool pvalid = pg[x] >= 0 && pg[x] < NP;  // wave-uniform
-      const int t0 = pvalid ? pg[x] * kPage : 0;
-      // ---- K rows: lane (token r16, k-group kg) takes 16 bytes per 32-channel step
-      tokvalid[x] = pvalid && (t0 + r16 < N);
+    for (int x = 0; x < 2; ++x)
 #pragma unroll
-      for (int j = 0; j < C::KC; ++j) {
-        kreg[x][j] = make_uint4(0, 0, 0, 0);
-        if (tokvalid[x])
-          kreg[x][j] = *(const uint4*)(Ks + (size_t)(t0 + r16) * D + 32 * j + 8 * kg);
-      }
-      // ---- packed V run of the page -> LDS, plus the table of unit addresses
-      unsigned char* vbuf = wl + x * C::VBYTES;
-      uint32_t* tab = (uint32_t*)(wl + 2 * C::VBYTES + x * C::TBYTES);
-      uint32_t mk = 0, off = 0;
-      long long run0 = 0, run1 = 0;
-      if (pvalid) {
-        if (t0 + ttok < N) {
-          mk = mask_s[t0 + ttok];
-          off = off_s[t0 + ttok];
-        }
-        run0 = off_s[t0];
-        run1 = off_s[min(t0 + kPage, N)];
-      }
-      run1 = min(run1, cap);
-      long long rg = run1 - run0;               // groups of this page present in the store
-      rg = max(0ll, min(rg, (long long)kPage * G));
-      const int run_bytes = (int)rg * gbytes;
-      const unsigned char* vsrc = vs + run0 * gbytes;
-#pragma unroll
-      for (int i = 0; i < C::VBYTES / 1024; ++i) {
-        const int bo = (i * 64 + lane) * 16;
-        if (bo < run_bytes) *(uint4*)(vbuf + bo) = *(const uint4*)(vsrc + bo);
-      }
-#pragma unroll
-      for (int uu = 0; uu < C::UNITS / 4; ++uu) {
-        const int u = tq * (C::UNITS / 4) + uu;      // 8-channel unit of token ttok
-        const int g = (u * 8) / gd;
-        const int within = u * 16 - g * gbytes;      // bytes into the group
-        const long long slot = (long long)off - run0 + __popc(mk & ((1u << g) - 1u));
-        const bool kept = ((mk >> g) & 1u) && slot >= 0 && slot < rg;
-        const uint32_t ent = kept ? (uint32_t)(x * C::VBYTES + (int)slot * gbytes + within)
-                                  : zero_addr;
-        tab[((u & 1) * C::CB + (u >> 1)) * kPage + ttok] = ent;
-      }
-    }
+      for (int j = 0; j < C::NLD; ++j)
+        *(u32x4*)(wl + (x * C::TILE + ((j * 64 + lane) / C::LPR) * C::ROW +
+                        (lane % C::LPR) * 16)) = kreg[it][x][j];
     wave_lds_sync();
-
-    // ---- logits S^T[token][head] for both pages
     float s[2][4];
     float mx = kNegBig;
 #pragma unroll
     for (int x = 0; x < 2; ++x) {
       f32x4 sv = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int j = 0; j < C::KC; ++j)
-        sv = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kreg[x][j]), as_bf16x8(qreg[j]), sv,
-                                                     0, 0, 0);
+      for (int j = 0; j < C::KC; ++j) {
+        // A operand: token r16, channels 32*j + 8*kg .. +8 from the K tile
+        const u32x4 a = *(const u32x4*)(wl + (x * C::TILE + r16 * C::ROW + (4 * j + kg) * 16));
+        sv = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), as_bf16x8(qreg[j]), sv, 0, 0, 0);
+      }
       // this lane holds tokens 4*kg + i of page x for head r16
-      const bool pvalid = pg[x] >= 0 && pg[x] < NP;
-      const int t0 = pvalid ? pg[x] * kPage : 0;
+      const int pg = pgs[it][x];
+      const uint32_t t0 = pg < 0 ? 0 : pg * kPage;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const bool tv = pvalid && (t0 + 4 * kg + i < N);
-        s[x][i] = tv ? sv[i] * scale : kNegBig;
+        const bool tv = pg >= 0 && (t0 + 4 * kg + i < (uint32_t)N);
+        s[x][i] = tv ? sv[i] * scale : -INFINITY;  // weight of an absent token is exactly 0
         mx = fmaxf(mx, s[x][i]);
       }
     }
     mx = fmaxf(mx, __shfl_xor(mx, 16));
     mx = fmaxf(mx, __shfl_xor(mx, 32));
     const float m_new = fmaxf(m_run, mx);
-    const float rescale = exp2f(m_run - m_new);
+    const float rescale = __builtin_amdgcn_exp2f(m_run - m_new);
     m_run = m_new;
     float p[8];
     float psum = 0.f;
@@ -192,62 +288,133 @@ __global__ __launch_bounds__(64 * kAttnWaves) void attn_mfma_kernel(
     for (int x = 0; x < 2; ++x)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        p[x * 4 + i] = s[x][i] > 0.5f * kNegBig ? exp2f(s[x][i] - m_new) : 0.f;
+        p[x * 4 + i] = __builtin_amdgcn_exp2f(s[x][i] - m_new);  // m_new is finite
         psum += p[x * 4 + i];
       }
     l_part = l_part * rescale + psum;
+    if (it > 0 && __any(rescale != 1.0f)) {  // wave-uniform: the running maximum moved
 #pragma unroll
-    for (int cb = 0; cb < C::CB; ++cb) acc[cb] *= rescale;
+      for (int cb = 0; cb < C::CB; ++cb) acc[cb] *= rescale;
+    }
     // weights as two bf16 parts; contraction index: (kg, e) e<4 page 0, e>=4 page 1
-    uint4 phi, plo;
-    {
-      uint32_t h[4], l[4];
+    uint32_t h[4], l[4];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        h[r] = pack_bf16(p[2 * r], p[2 * r + 1]);
-        l[r] = pack_bf16(p[2 * r] - bf16_lo(h[r]), p[2 * r + 1] - bf16_hi(h[r]));
-      }
-      phi = make_uint4(h[0], h[1], h[2], h[3]);
-      plo = make_uint4(l[0], l[1], l[2], l[3]);
+    for (int r = 0; r < 4; ++r) {
+      h[r] = pack_bf16(p[2 * r], p[2 * r + 1]);
+      l[r] = pack_bf16(p[2 * r] - bf16_lo(h[r]), p[2 * r + 1] - bf16_hi(h[r]));
     }
-    // ---- O^T += V~^T . P^T per 16-channel block
-#pragma unroll
-    for (int cb = 0; cb < C::CB; ++cb) {
-      uint32_t a[4];
-#pragma unroll
-      for (int x = 0; x < 2; ++x) {
-        const uint32_t* tab = (const uint32_t*)(wl + 2 * C::VBYTES + x * C::TBYTES);
-        const uint4 e = *(const uint4*)(tab + (half * C::CB + cb) * kPage + 4 * kg);
-        const uint32_t v0 = *(const uint16_t*)(wl + e.x + j2);
-        const uint32_t v1 = *(const uint16_t*)(wl + e.y + j2);
-        const uint32_t v2 = *(const uint16_t*)(wl + e.z + j2);
-        const uint32_t v3 = *(const uint16_t*)(wl + e.w + j2);
-        a[2 * x] = v0 | (v1 << 16);
-        a[2 * x + 1] = v2 | (v3 << 16);
-      }
-      const bf16x8 av = as_bf16x8(make_uint4(a[0], a[1], a[2], a[3]));
-      acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(phi), acc[cb], 0, 0, 0);
-      acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(plo), acc[cb], 0, 0, 0);
+    phi = u32x4{h[0], h[1], h[2], h[3]};
+    plo = u32x4{l[0], l[1], l[2], l[3]};
+  };
+
+  // packed runs of a pair -> LDS, then O^T += V~^T . P^T
+#define STC_PV(it, vreg)                                                                       \
+  {                                                                                            \
+    wave_lds_sync(); /* the K tiles have been read */                                          \
+    static_for<0, 2>([&](auto x) {                                                             \
+      static_for<0, C::NLD>([&](auto j) {                                                      \
+        *(u32x4*)(wl + (x * C::TILE + (j * 64 + lane) * 16)) = vreg[x][j];                     \
+      });                                                                                      \
+    });                                                                                        \
+    if (lane < 32) { /* token lane: kept-group mask and offset relative to the run */         \
+      const uint32_t r0 = (lane & 16) ? run0[it][1] : run0[it][0];                             \
+      const uint32_t rel = min(off[it] - r0, 0xffffu);                                         \
+      *(uint32_t*)(wl + C::META + lane * 4) = (mvalid[it] ? mk[it] : 0u) | (rel << 16);        \
+    }                                                                                          \
+    wave_lds_sync();                                                                           \
+    /* t[e]: channels r16*CB .. +CB of token e of this lane's k-group (e < 4: page 0) */       \
+    uint32_t t[8][C::CB / 2];                                                                  \
+    _Pragma("unroll") for (int x = 0; x < 2; ++x) {                                            \
+      const uint32_t rg = run_groups(it, x);                                                   \
+      const u32x4 mt = *(const u32x4*)(wl + C::META + x * 64 + kg * 16);                       \
+      _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                          \
+        const uint32_t m = mt[i] & 0xffffu;                                                    \
+        const uint32_t slot = (mt[i] >> 16) + __popc(m & u_below);                             \
+        const bool kept = ((m >> u_g) & 1u) && slot < rg;                                      \
+        const uint32_t a = kept ? x * C::TILE + slot * gbytes + u_within : (uint32_t)C::ZERO;  \
+        if constexpr (D == 128) {                                                              \
+          const u32x4 v = *(const u32x4*)(wl + a);                                             \
+          t[x * 4 + i][0] = v.x, t[x * 4 + i][1] = v.y, t[x * 4 + i][2] = v.z,                 \
+                       t[x * 4 + i][3] = v.w;                                                  \
+        } else {                                                                               \
+          const u32x2 v = *(const u32x2*)(wl + a);                                             \
+          t[x * 4 + i][0] = v.x, t[x * 4 + i][1] = v.y;                                        \
+        }                                                                                      \
+      }                                                                                        \
+    }                                                                                          \
+    _Pragma("unroll") for (int cb = 0; cb < C::CB; ++cb) {                                     \
+      const uint32_t sel = (cb & 1) ? 0x07060302u : 0x05040100u;                               \
+      uint32_t a[4];                                                                           \
+      _Pragma("unroll") for (int r = 0; r < 4; ++r) a[r] =                                     \
+          __builtin_amdgcn_perm(t[2 * r + 1][cb >> 1], t[2 * r][cb >> 1], sel);                \
+      const bf16x8 av = as_bf16x8(u32x4{a[0], a[1], a[2], a[3]});                              \
+      acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(phi), acc[cb], 0, 0, 0); \
+      acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(plo), acc[cb], 0, 0, 0); \
+    }                                                                                          \
+    wave_lds_sync(); /* the next pair overwrites the tiles */                                  \
+  }
+
+  if (npairs > 0) {
+    STC_MARK(2, mk[0] ^ off[0] ^ run1[0][0] ^ run1[0][1]);
+    // The value requests of a pair are held back until its masks/offsets have arrived:
+    // a wavefront then has one pair of K pages or one pair of V runs plus the next K
+    // pages outstanding, which keeps the chip-wide volume of outstanding requests near
+    // what the memory system sustains.  (Requesting everything at once is slower.)
+    finish_meta(0);
+    uint32_t vgate;
+    asm volatile("v_and_b32 %0, 0, %1" : "=v"(vgate) : "v"(off[0] ^ mk[0]));  // 0, after they arrive
+    u32x4 vregA[2][C::NLD];
+    STC_ISSUE_V(0, vregA);
+    __builtin_amdgcn_sched_barrier(0);
+    u32x4 vregB[2][C::NLD];
+    if constexpr (PAIRS > 1) {
+      issue_k(1);
+      __builtin_amdgcn_sched_barrier(0);
+      finish_meta(1);
+      STC_ISSUE_V(1, vregB);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    wave_lds_sync();  // the next pair overwrites the staging buffers
+    STC_MARK(3, kreg[0][0][0].x ^ kreg[0][1][C::NLD - 1].w);
+    qk_softmax(0);
+    __builtin_amdgcn_sched_barrier(0);
+    STC_MARK(4, phi.x ^ plo.w);
+    STC_MARK(5, vregA[0][0].x ^ vregA[1][C::NLD - 1].w);
+    STC_PV(0, vregA);
+    STC_MARK(6, acc[0][0]);
+    if constexpr (PAIRS > 1) {
+      if (npairs > 1) {
+        STC_MARK(8, kreg[1][0][0].x ^ kreg[1][1][C::NLD - 1].w);
+        qk_softmax(1);
+        STC_MARK(9, phi.x ^ plo.w);
+        STC_MARK(10, vregB[0][0].x ^ vregB[1][C::NLD - 1].w);
+        STC_PV(1, vregB);
+        STC_MARK(11, acc[0][0]);
+      }
+    }
   }
 
   // sum of weights of head r16 over this wavefront's tokens
   float l = l_part + __shfl_xor(l_part, 16);
   l += __shfl_xor(l, 32);
 
-  // ---- merge the 4 wavefronts: each leaves (m, l, acc[R][D]) in its own LDS region
-  float* macc = (float*)wl;                    // [16][D]
-  float* mml = (float*)(wl + 16 * D * 4);      // [16][2]
-  static_assert(16 * D * 4 + 16 * 2 * 4 <= C::WAVE_LDS, "merge buffer fits the staging area");
+  // ---- merge the 4 wavefronts: each leaves (m, l, acc[16][D]) in its own LDS region.
+  // acc[cb][i] of lane (head r16, kg) is channel (4*kg + i)*CB + cb.
+  float* macc = (float*)wl;                // [16][D]
+  float* mml = (float*)(wl + 16 * D * 4);  // [16][2]
 #pragma unroll
-  for (int cb = 0; cb < C::CB; ++cb)
-    *(f32x4*)(macc + r16 * D + cb * 16 + 4 * kg) = acc[cb];  // channels cb*16 + 4*kg + i
+  for (int i = 0; i < 4; ++i) {
+    float* dst = macc + r16 * D + (4 * kg + i) * C::CB;
+#pragma unroll
+    for (int c4 = 0; c4 < C::CB / 4; ++c4)
+      *(f32x4*)(dst + 4 * c4) = f32x4{acc[4 * c4][i], acc[4 * c4 + 1][i], acc[4 * c4 + 2][i],
+                                      acc[4 * c4 + 3][i]};
+  }
   if (kg == 0) {
     mml[r16 * 2] = m_run;
     mml[r16 * 2 + 1] = l;
   }
   __syncthreads();
+  STC_MARK(14, lane);
   for (int i = threadIdx.x; i < R * D; i += 64 * kAttnWaves) {
     const int head = i / D, c = i % D;
     float mw[kAttnWaves], m = kNegBig;
@@ -259,7 +426,7 @@ __global__ __launch_bounds__(64 * kAttnWaves) void attn_mfma_kernel(
     float lsum = 0.f, a = 0.f;
 #pragma unroll
     for (int w = 0; w < kAttnWaves; ++w) {
-      const float wgt = exp2f(mw[w] - m);
+      const float wgt = __builtin_amdgcn_exp2f(mw[w] - m);
       lsum = fmaf(wgt, ((const float*)(lds + w * C::WAVE_LDS + 16 * D * 4))[head * 2 + 1], lsum);
       a = fmaf(wgt, ((const float*)(lds + w * C::WAVE_LDS))[head * D + c], a);
     }
@@ -276,6 +443,9 @@ __global__ __launch_bounds__(64 * kAttnWaves) void attn_mfma_kernel(
     }
   }
 }
+
+#undef STC_ISSUE_V
+#undef STC_PV
 
 // Merge the split partials of one query head in ascending split order.  Each
 // thread owns one channel; partials are fetched 8 splits at a time so the loads
@@ -320,7 +490,10 @@ __global__ __launch_bounds__(D) void attn_combine_kernel(const float* __restrict
 // (4 per CU), and never more than the pages there are.
 static int attention_ppw(const stc_shape_t& s, int k_pages) {
   const int streams = s.B * s.Hkv;
-  int ppw = 8;
+#ifdef STC_TUNE
+  if (const char* e = getenv("STC_ATTN_PPW")) return atoi(e) <= 2 ? 2 : 4;
+#endif
+  int ppw = 4;
   while (ppw > 2 &&
          (long long)streams * ((k_pages + kAttnWaves * ppw - 1) / (kAttnWaves * ppw)) < 1024)
     ppw >>= 1;
@@ -348,16 +521,27 @@ int launch_attention(const stc_shape_t& s, const void* q, const void* K, const v
   const int splits = attention_splits(s, k_pages);
   dim3 grid(splits, streams);
   float* partial = (float*)ws;
-  if (s.D == 128)
-    attn_mfma_kernel<128><<<grid, 64 * kAttnWaves, 0, st>>>(
-        (const uint16_t*)q, (const uint16_t*)K, (const unsigned char*)vpacked, mask, tok_off,
-        page_idx, partial, out, s.Hq, s.Hkv, s.N, NP, s.G, (long long)s.v_cap_groups, k_pages,
-        splits, ppw);
-  else
-    attn_mfma_kernel<64><<<grid, 64 * kAttnWaves, 0, st>>>(
-        (const uint16_t*)q, (const uint16_t*)K, (const unsigned char*)vpacked, mask, tok_off,
-        page_idx, partial, out, s.Hq, s.Hkv, s.N, NP, s.G, (long long)s.v_cap_groups, k_pages,
-        splits, ppw);
+#ifdef STC_TUNE
+  {
+    long long* p = nullptr;
+    if (const char* e = getenv("STC_DBG_PTR")) p = (long long*)strtoull(e, nullptr, 0);
+    static long long* last = (long long*)-1;
+    if (p != last) {
+      (void)hipMemcpyToSymbol(HIP_SYMBOL(stc_dbg_ptr), &p, sizeof(p));
+      last = p;
+    }
+  }
+#endif
+#define STC_ATTN_LAUNCH(DD, PP)                                                                   \
+  attn_mfma_kernel<DD, PP><<<grid, 64 * kAttnWaves, 0, st>>>(                                     \
+      (const uint16_t*)q, (const uint16_t*)K, (const unsigned char*)vpacked, mask, tok_off,       \
+      page_idx, partial, out, s.Hq, s.Hkv, s.N, NP, s.G, (uint32_t)s.v_cap_groups, k_pages, splits)
+  if (s.D == 128) {
+    if (ppw == 2) STC_ATTN_LAUNCH(128, 1); else STC_ATTN_LAUNCH(128, 2);
+  } else {
+    if (ppw == 2) STC_ATTN_LAUNCH(64, 1); else STC_ATTN_LAUNCH(64, 2);
+  }
+#undef STC_ATTN_LAUNCH
   if (hipGetLastError() != hipSuccess) return -1;
   if (splits > 1) {
     if (s.D == 128)

@@ -118,7 +118,12 @@ int stc_decode_attention(const stc_shape_t* shape, const void* q, const void* K,
                          size_t ws_bytes, void* stream) {
   if (!shape || !q || !K || !vpacked || !mask || !tok_off || !page_idx || !out)
     return STC_ERR_NULL;
-  if (!shape_ok(shape) || k_pages < 1 || k_pages > num_pages(shape)) return STC_ERR_SHAPE;
+  if (!shape_ok(shape) || k_pages < 1 || k_pages > num_pages(shape) || shape->v_cap_groups < 1)
+    return STC_ERR_SHAPE;
+  // the kernels address one stream's keys and packed values with 32-bit byte offsets
+  if ((long long)shape->N * shape->D * 2 >= (1ll << 32) ||
+      shape->v_cap_groups * (shape->D / shape->G) * 2 >= (1ll << 32))
+    return STC_ERR_SHAPE;
   if (!aligned16(q) || !aligned16(K) || !aligned16(vpacked) || !aligned16(mask) ||
       !aligned16(tok_off) || !aligned16(page_idx) || !aligned16(out))
     return STC_ERR_ALIGN;

@@ -5,6 +5,22 @@
 
 namespace stc {
 
+// Compile-time loop: f(integral_constant<int, I>) for I in [B, E).  Register arrays
+// indexed through it have constant indices from the start, so they never land in
+// scratch memory.
+template <int I>
+struct IC {
+  static constexpr int value = I;
+  constexpr operator int() const { return I; }
+};
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (B < E) {
+    f(IC<B>{});
+    static_for<B + 1, E>(f);
+  }
+}
+
 constexpr int kWave = 64;
 constexpr int kPage = 16;
 

@@ -81,10 +81,16 @@ def test_null_alignment_and_workspace_errors():
     assert att(8, FAKE, big) == stc.STC_ERR_SHAPE
     assert att(0, FAKE, big) == stc.STC_ERR_SHAPE
     assert att(7, FAKE, big, None) == stc.STC_ERR_NULL
-    need = stc.stc_workspace_bytes(s, stc.STC_WS_ATTENTION, 7)
+    assert stc.stc_workspace_bytes(s, stc.STC_WS_ATTENTION, 7) == 0       # one split: no partials
+    s2 = _shape(N=4096, v_cap_groups=4096 * 8)
+    need = stc.stc_workspace_bytes(s2, stc.STC_WS_ATTENTION, 64)
     assert need > 0
-    assert att(7, FAKE, need - 1) == stc.STC_ERR_WORKSPACE
-    assert att(7, None, big) == stc.STC_ERR_WORKSPACE
+    att2 = lambda ws, wsb: lib.stc_decode_attention(  # noqa: E731
+        ctypes.byref(s2), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 64, FAKE, ws, wsb, None)
+    assert att2(FAKE, need - 1) == stc.STC_ERR_WORKSPACE
+    assert att2(None, big) == stc.STC_ERR_WORKSPACE
+    assert lib.stc_decode_attention(ctypes.byref(_shape(v_cap_groups=0)), FAKE, FAKE, FAKE, FAKE,
+                                    FAKE, FAKE, 7, FAKE, FAKE, big, None) == stc.STC_ERR_SHAPE
     # compact
     assert lib.stc_compact_tokens(FAKE, FAKE, FAKE, 1, 1, 10, 4, 100, None, None) == stc.STC_ERR_SHAPE
     assert lib.stc_compact_tokens(FAKE, None, FAKE, 1, 1, 10, 4, 128, None, None) == stc.STC_ERR_NULL
