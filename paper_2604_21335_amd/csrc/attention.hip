@@ -448,8 +448,8 @@ __global__ __launch_bounds__(64 * kAttnWaves) void attn_mfma_kernel(
 #undef STC_PV
 
 // Merge the split partials of one query head in ascending split order.  Each
-// thread owns one channel; partials are fetched 8 splits at a time so the loads
-// of a batch are in flight together.
+// thread owns one channel; partials are fetched 8 splits at a time (one round of
+// loads for up to 8 splits) and folded in with a running maximum.
 template <int D>
 __global__ __launch_bounds__(D) void attn_combine_kernel(const float* __restrict__ partial,
                                                          float* __restrict__ out, int splits) {
@@ -457,28 +457,22 @@ __global__ __launch_bounds__(D) void attn_combine_kernel(const float* __restrict
   const int head = blockIdx.x;
   const int c = threadIdx.x;
   const float* pr = partial + (size_t)head * splits * ST;
-  float m = kNegBig;
-  for (int s0 = 0; s0 < splits; s0 += 8) {
-    float v[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = s0 + i < splits ? pr[(s0 + i) * ST] : kNegBig;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) m = fmaxf(m, v[i]);
-  }
-  float l = 0.f, a = 0.f;
+  float m = kNegBig, l = 0.f, a = 0.f;
   for (int s0 = 0; s0 < splits; s0 += 8) {
     float ms[8], ls[8], as[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const bool ok = s0 + i < splits;
-      const float* ps = pr + (s0 + i) * ST;
-      ms[i] = ok ? ps[0] : kNegBig;
-      ls[i] = ok ? ps[1] : 0.f;
-      as[i] = ok ? ps[2 + c] : 0.f;
+      const float* ps = pr + min(s0 + i, splits - 1) * ST;
+      ms[i] = ps[0], ls[i] = ps[1], as[i] = ps[2 + c];
     }
+    float mb = m;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) mb = fmaxf(mb, s0 + i < splits ? ms[i] : kNegBig);
+    const float r = __builtin_amdgcn_exp2f(m - mb);
+    l *= r, a *= r, m = mb;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const float w = exp2f(ms[i] - m);
+      const float w = s0 + i < splits ? __builtin_amdgcn_exp2f(ms[i] - mb) : 0.f;
       l = fmaf(w, ls[i], l);
       a = fmaf(w, as[i], a);
     }
@@ -486,8 +480,8 @@ __global__ __launch_bounds__(D) void attn_combine_kernel(const float* __restrict
   out[(size_t)head * D + c] = l > 0.f ? a / l : 0.f;
 }
 
-// Pages per wavefront: as many as keep at least ~1024 workgroups in the grid
-// (4 per CU), and never more than the pages there are.
+// Pages per wavefront: 4 if that still leaves two workgroups per CU (their register
+// budget keeps two resident), else 2; never more than the pages there are.
 static int attention_ppw(const stc_shape_t& s, int k_pages) {
   const int streams = s.B * s.Hkv;
 #ifdef STC_TUNE
@@ -495,7 +489,7 @@ static int attention_ppw(const stc_shape_t& s, int k_pages) {
 #endif
   int ppw = 4;
   while (ppw > 2 &&
-         (long long)streams * ((k_pages + kAttnWaves * ppw - 1) / (kAttnWaves * ppw)) < 1024)
+         (long long)streams * ((k_pages + kAttnWaves * ppw - 1) / (kAttnWaves * ppw)) < 512)
     ppw >>= 1;
   while (ppw > 2 && kAttnWaves * (ppw / 2) >= k_pages) ppw >>= 1;  // no idle wavefronts
   return ppw;

@@ -13,6 +13,11 @@ namespace stc {
 // combined by an xor butterfly, which continues the same tree.  Every product
 // of two bf16 values is exact in float, so fusing a product into the following
 // addition does not change any bit.
+//
+// Because mn <= mx, the larger product is q*mx for q >= 0 and q*mn for q < 0
+// (for q = 0 both are zero).  The choice depends on the query alone, so it is
+// made once per (head, channel): a byte-permute selector that picks the bf16
+// half of the mn or the mx word and widens it to float in the same instruction.
 // ---------------------------------------------------------------------------
 template <int D, int R>
 __global__ __launch_bounds__(256) void score_kernel(const uint4* __restrict__ bounds,
@@ -26,7 +31,11 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* __restrict__ bo
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane % LPP, pw = lane / LPP;
 
+  // v_perm_b32 selectors over the byte pool {mx word: bytes 4..7, mn word: bytes 0..3};
+  // 0x0c yields a zero byte.  Result: the chosen bf16 in the upper half of a float.
+  constexpr uint32_t kSelEvenMn = 0x01000c0cu, kSelOddMn = 0x03020c0cu, kPickMx = 0x04040000u;
   float qf[R][8];
+  uint32_t sel[R][8];
 #pragma unroll
   for (int h = 0; h < R; ++h) {
     const uint4 v = q[((size_t)b * Hq + kvh * R + h) * LPP + sub];
@@ -35,6 +44,8 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* __restrict__ bo
     for (int i = 0; i < 4; ++i) {
       qf[h][2 * i] = bf16_lo(w[i]);
       qf[h][2 * i + 1] = bf16_hi(w[i]);
+      sel[h][2 * i] = kSelEvenMn + ((w[i] & 0x8000u) ? 0u : kPickMx);
+      sel[h][2 * i + 1] = kSelOddMn + ((w[i] & 0x80000000u) ? 0u : kPickMx);
     }
   }
 
@@ -43,37 +54,32 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* __restrict__ bo
   const uint4* base = bounds + (size_t)stream * NP * (2 * LPP);
   float* out = score + (size_t)stream * NP;
 
+  // Two passes of this lane are always in flight behind the one being computed.
+  // Pages past the end of the block's range re-read its last page (never stored).
+  constexpr int STEP = 4 * PPW;
+  const int plast = p1 - 1;
   int p = p0 + wave * PPW + pw;
-  uint4 mnv = make_uint4(0, 0, 0, 0), mxv = mnv;
-  if (p < p1) {
-    mnv = base[(size_t)p * (2 * LPP) + sub];
-    mxv = base[(size_t)p * (2 * LPP) + LPP + sub];
-  }
-  for (; p < p1; p += 4 * PPW) {
-    const uint4 cmn = mnv, cmx = mxv;
-    const int pn = p + 4 * PPW;
-    if (pn < p1) {  // next pass of this lane, in flight during the arithmetic
-      mnv = base[(size_t)pn * (2 * LPP) + sub];
-      mxv = base[(size_t)pn * (2 * LPP) + LPP + sub];
-    }
+  auto load_mn = [&](int pp) { return base[(size_t)min(pp, plast) * (2 * LPP) + sub]; };
+  auto load_mx = [&](int pp) { return base[(size_t)min(pp, plast) * (2 * LPP) + LPP + sub]; };
+  uint4 mn0 = load_mn(p), mx0 = load_mx(p);
+  uint4 mn1 = load_mn(p + STEP), mx1 = load_mx(p + STEP);
+  for (; p < p1; p += STEP) {
+    const uint4 cmn = mn0, cmx = mx0;
+    mn0 = mn1, mx0 = mx1;
+    mn1 = load_mn(p + 2 * STEP), mx1 = load_mx(p + 2 * STEP);
     const uint32_t wn[4] = {cmn.x, cmn.y, cmn.z, cmn.w};
     const uint32_t wx[4] = {cmx.x, cmx.y, cmx.z, cmx.w};
-    float mn[8], mx[8];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      mn[2 * i] = bf16_lo(wn[i]);
-      mn[2 * i + 1] = bf16_hi(wn[i]);
-      mx[2 * i] = bf16_lo(wx[i]);
-      mx[2 * i + 1] = bf16_hi(wx[i]);
-    }
     float best = 0.f;
 #pragma unroll
     for (int h = 0; h < R; ++h) {
-      float t[8];
+      float s2[4];  // sums of adjacent channel pairs
 #pragma unroll
-      for (int c = 0; c < 8; ++c) t[c] = fmaxf(qf[h][c] * mn[c], qf[h][c] * mx[c]);
-      const float s01 = t[0] + t[1], s23 = t[2] + t[3], s45 = t[4] + t[5], s67 = t[6] + t[7];
-      float u = (s01 + s23) + (s45 + s67);
+      for (int i = 0; i < 4; ++i) {
+        const float x0 = __uint_as_float(__builtin_amdgcn_perm(wx[i], wn[i], sel[h][2 * i]));
+        const float x1 = __uint_as_float(__builtin_amdgcn_perm(wx[i], wn[i], sel[h][2 * i + 1]));
+        s2[i] = fmaf(qf[h][2 * i + 1], x1, qf[h][2 * i] * x0);  // both products are exact
+      }
+      float u = (s2[0] + s2[1]) + (s2[2] + s2[3]);
       u = row_tree_sum<LPP>(u);
       best = h == 0 ? u : fmaxf(best, u);
     }
@@ -217,6 +223,146 @@ __global__ __launch_bounds__(kSelThreads) void topk_kernel(const float* __restri
   }
 }
 
+// Same selection with the stream's keys held in registers: 256 threads, thread t owns
+// the IPT adjacent pages t*IPT ..; used whenever NP <= 256*32.  Each radix pass is a
+// shared-memory histogram of one key byte, a block scan over the digits in descending
+// order and a broadcast of the digit that holds the k-th largest key.
+template <int IPT>
+__global__ __launch_bounds__(256) void topk_reg_kernel(const float* __restrict__ score,
+                                                       int32_t* __restrict__ page_idx, int NP,
+                                                       int k) {
+  __shared__ int hist[256];
+  __shared__ int waves[4];
+  __shared__ uint32_t s_prefix;
+  __shared__ int s_remaining, s_cand, s_ncand;
+  __shared__ uint32_t cand[64];
+  const int stream = blockIdx.x;
+  const float* sc = score + (size_t)stream * NP;
+  int32_t* out = page_idx + (size_t)stream * k;
+  const int tid = threadIdx.x;
+  const int i0 = tid * IPT;
+
+  // keys of absent pages (index >= NP) are 0, below the key of any finite float
+  uint32_t key[IPT];
+  if constexpr (IPT >= 4) {
+    if (i0 + IPT <= NP && (NP % 4) == 0) {
+#pragma unroll
+      for (int j = 0; j < IPT; j += 4) {
+        const float4 v = *(const float4*)(sc + i0 + j);
+        key[j] = float_key(v.x), key[j + 1] = float_key(v.y);
+        key[j + 2] = float_key(v.z), key[j + 3] = float_key(v.w);
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < IPT; ++j) key[j] = i0 + j < NP ? float_key(sc[i0 + j]) : 0u;
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) key[j] = i0 + j < NP ? float_key(sc[i0 + j]) : 0u;
+  }
+
+  // Bits above the highest bit in which two keys differ are common to all keys and
+  // need no pass; starting at that bit also spreads the first histogram over many
+  // bins (page scores share their sign and most exponent bits).
+  uint32_t kmin = 0xffffffffu, kmax = 0u;
+#pragma unroll
+  for (int j = 0; j < IPT; ++j)
+    if (i0 + j < NP) kmin = min(kmin, key[j]), kmax = max(kmax, key[j]);
+  for (int d = 32; d >= 1; d >>= 1) {
+    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, d));
+    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, d));
+  }
+  __shared__ uint32_t s_min[4], s_max[4];
+  if ((tid & 63) == 0) s_min[tid >> 6] = kmin, s_max[tid >> 6] = kmax;
+  __syncthreads();
+  kmin = min(min(s_min[0], s_min[1]), min(s_min[2], s_min[3]));
+  kmax = max(max(s_max[0], s_max[1]), max(s_max[2], s_max[3]));
+  const uint32_t diff = kmin ^ kmax;
+  const int top = diff ? 31 - __clz(diff) : 0;  // highest differing bit
+  int shift = max(top - 7, 0);
+  uint32_t decided = shift + 8 < 32 ? ~((1u << (shift + 8)) - 1u) : 0u;  // key bits fixed so far
+  uint32_t prefix = kmax & decided;
+  int remaining = k;  // rank of the k-th largest key among the keys sharing the prefix
+  // The last window may overlap bits that are already fixed; keys are filtered on all
+  // fixed bits, so the digit found repeats them.
+  for (;; shift = max(shift - 8, 0)) {
+    hist[tid] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) {
+      const bool in = (key[j] & decided) == prefix;
+      if (in && i0 + j < NP) atomicAdd(&hist[(key[j] >> shift) & 255u], 1);
+    }
+    __syncthreads();
+    const int cnt = hist[255 - tid];  // digits in descending order
+    int tot;
+    const int above = block_exscan(cnt, waves, &tot);  // keys with a larger digit
+    if (above < remaining && remaining <= above + cnt) {
+      s_prefix = (prefix & ~(255u << shift)) | ((uint32_t)(255 - tid) << shift);
+      s_remaining = remaining - above;
+      s_cand = cnt;  // keys that share the new prefix
+      s_ncand = 0;
+    }
+    __syncthreads();
+    prefix = s_prefix;
+    remaining = s_remaining;
+    decided = ~((1u << shift) - 1u);
+    if (shift == 0) break;
+    if (s_cand <= 64) {
+      // Few keys are left: list them, and let one wavefront rank them directly.
+#pragma unroll
+      for (int j = 0; j < IPT; ++j)
+        if (i0 + j < NP && (key[j] & decided) == prefix) cand[atomicAdd(&s_ncand, 1)] = key[j];
+      __syncthreads();
+      const int c = s_cand;
+      if (tid < c) {
+        const uint32_t mine = cand[tid];
+        int gt = 0, ge = 0;
+        for (int i = 0; i < c; ++i) {
+          const uint32_t o = cand[i];
+          gt += o > mine;
+          ge += o >= mine;
+        }
+        if (gt < remaining && remaining <= ge) {  // equal keys all write the same pair
+          s_prefix = mine;
+          s_remaining = remaining - gt;
+        }
+      }
+      __syncthreads();
+      prefix = s_prefix;
+      remaining = s_remaining;
+      break;
+    }
+  }
+  // prefix = key of the k-th largest score; `remaining` of the pages equal to it are
+  // taken, lowest page index first.
+  int eq = 0;
+#pragma unroll
+  for (int j = 0; j < IPT; ++j) eq += (i0 + j < NP) && key[j] == prefix;
+  int tot;
+  const int eq_before = block_exscan(eq, waves, &tot);
+  int sel = 0;
+  uint32_t take = 0;  // bit j: page i0 + j is selected
+  {
+    int e = eq_before;
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) {
+      if (i0 + j < NP) {
+        bool t = key[j] > prefix;
+        if (key[j] == prefix) t = e++ < remaining;
+        if (t) {
+          take |= 1u << j;
+          ++sel;
+        }
+      }
+    }
+  }
+  int pos = block_exscan(sel, waves, &tot);
+#pragma unroll
+  for (int j = 0; j < IPT; ++j)
+    if (((take >> j) & 1u) && pos < k) out[pos++] = i0 + j;
+}
+
 __global__ void iota_pages_kernel(int32_t* __restrict__ page_idx, int NP, int total) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < total) page_idx[i] = i % NP;
@@ -228,8 +374,9 @@ static void launch_score(const stc_shape_t& s, const void* q, const void* bounds
   constexpr int PPW = 64 / (D / 8);
   const int streams = s.B * s.Hkv;
   const int R = s.Hq / s.Hkv;
-  // aim for a few thousand wavefronts; every block takes at least one pass of its 4 waves
-  const int want_blocks = max(1, 2048 / streams);
+  // about three workgroups per CU (what the register budget keeps resident), so the whole
+  // grid runs as one generation and the per-wave set-up is paid once per ~10 passes
+  const int want_blocks = max(1, 768 / streams);
   int ppb = (NP + want_blocks - 1) / want_blocks;
   ppb = max(4 * PPW, (ppb + 4 * PPW - 1) / (4 * PPW) * (4 * PPW));
   dim3 grid((NP + ppb - 1) / ppb, streams);
@@ -265,7 +412,21 @@ int launch_select(const stc_shape_t& s, const void* q, const void* bounds, int k
   else
     launch_score<64>(s, q, bounds, score, NP, st);
   if (hipGetLastError() != hipSuccess) return -1;
-  topk_kernel<<<streams, kSelThreads, 0, st>>>(score, page_idx, NP, k_pages);
+  const int ipt = (NP + 255) / 256;
+  if (ipt <= 1)
+    topk_reg_kernel<1><<<streams, 256, 0, st>>>(score, page_idx, NP, k_pages);
+  else if (ipt <= 2)
+    topk_reg_kernel<2><<<streams, 256, 0, st>>>(score, page_idx, NP, k_pages);
+  else if (ipt <= 4)
+    topk_reg_kernel<4><<<streams, 256, 0, st>>>(score, page_idx, NP, k_pages);
+  else if (ipt <= 8)
+    topk_reg_kernel<8><<<streams, 256, 0, st>>>(score, page_idx, NP, k_pages);
+  else if (ipt <= 16)
+    topk_reg_kernel<16><<<streams, 256, 0, st>>>(score, page_idx, NP, k_pages);
+  else if (ipt <= 32)
+    topk_reg_kernel<32><<<streams, 256, 0, st>>>(score, page_idx, NP, k_pages);
+  else
+    topk_kernel<<<streams, kSelThreads, 0, st>>>(score, page_idx, NP, k_pages);
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
