@@ -8,7 +8,13 @@ synthetic, resident in HBM before the timed region; the step rotates over
 several independent cache replicas and uses a fresh query every step so that
 no step is served from the 256 MB last-level cache.
 
-Prints ONE JSON line (see README / DESIGN for the fields).
+Prints ONE JSON line:
+  value / ms_per_step  whole step, averaged over --steps back-to-back steps (HIP events)
+  hbm_GBps / hbm_frac  algorithmic bytes of the step / step time, against 8 TB/s
+  calls                the same for stc_select_pages, stc_decode_attention and stc_score_pages
+                       alone (each timed over --steps back-to-back launches)
+  roofline             the dominant kernel (page scoring: it streams every page bound)
+  cpu_baseline         the CPU oracle on a bounded sample of the same workload
 """
 import argparse
 import json
@@ -28,16 +34,23 @@ METRIC = "decode-attention us/step + achieved HBM GB/s (% of peak), Qwen2.5-7B 3
 REPLICAS = {"tiny": 8, "llama2_7b_4k": 4, "qwen25_7b_32k": 6, "llava15_7b_prefix": 4,
             "qwen25_7b_128k": 1}
 
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs of this file
+# (FETCH_SIZE and WRITE_SIZE, scaled by what the same counters read for a copy of known
+# size); see profiles/.  None where it has not been measured.
+MEASURED_TRAFFIC = {}
+
 
 def algorithmic_bytes(w, mean_kept):
     """Bytes the method must move per decode step (one layer's cache)."""
     P, gd = 16, w.D // w.G
     k = min(w.k_pages, w.NP)
-    bounds = w.streams * w.NP * 2 * w.D * 2 if w.k_pages < w.NP else 0
+    selecting = w.k_pages < w.NP
+    bounds = w.streams * w.NP * 2 * w.D * 2 if selecting else 0
     Kb = w.streams * k * P * w.D * 2
     Vb = w.streams * k * P * mean_kept * gd * 2
     meta = w.streams * k * P * 2 + 2 * w.streams * k * 4      # masks, page offsets, page indices
-    return {"select": bounds + w.streams * k * 4, "attention": Kb + Vb + meta,
+    score = bounds + (w.B * w.Hq * w.D * 2 + w.streams * w.NP * 4 if selecting else 0)
+    return {"select": bounds + w.streams * k * 4, "attention": Kb + Vb + meta, "score": score,
             "step": bounds + Kb + Vb + meta,
             "parts": {"bounds": bounds, "K": Kb, "V": Vb, "meta": meta}}
 
@@ -69,8 +82,8 @@ def build_replicas(stc, W, w, n_rep, dev):
 
 
 def timed(fn, n, torch):
-    """Average milliseconds per call of fn(i) over n back-to-back calls (HIP events on
-    the current stream)."""
+    """Average milliseconds per call of fn(i) over n back-to-back calls, from HIP events
+    recorded on the stream the kernels are launched on (torch's current stream)."""
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     a.record()
@@ -87,8 +100,9 @@ def cpu_baseline(W, w, dev, budget_s=12.0):
     import numpy as np
 
     from oracle import stc_oracle as O
-    inp = W.make_cache_inputs(W.shrink(w, B=1), dev, layer=0)     # batch element 0 only
-    q = W.bf16_bits(W.make_query(W.shrink(w, B=1), 0, dev))
+    w1 = W.shrink(w, B=1)
+    inp = W.make_cache_inputs(w1, dev, layer=0)                    # batch element 0 only
+    q = W.bf16_bits(W.make_query(w1, 0, dev))
     R = w.R
     prepared = []
     for h in range(min(w.Hkv, 4)):                                 # oracle-built cache (untimed)
@@ -96,12 +110,10 @@ def cpu_baseline(W, w, dev, budget_s=12.0):
         if w.routing == "vlm":
             ti = inp["token_idx"][0].cpu().numpy()
             K, V = K[ti], V[ti]
-        if inp["logits"] is not None:
-            lg = inp["logits"][0, h].cpu().numpy()
         if inp["mask_in"] is not None:
             m = W.u16_numpy(inp["mask_in"][0, h]) & np.uint16((1 << w.G) - 1)
         else:
-            m = O.route_mask(lg, inp["kcount"][0, h].cpu().numpy())
+            m = O.route_mask(inp["logits"][0, h].cpu().numpy(), inp["kcount"][0, h].cpu().numpy())
         prepared.append((K, V, m, O.page_bounds(K), q[0, h * R:(h + 1) * R]))
     t0 = time.perf_counter()
     done = 0
@@ -114,13 +126,14 @@ def cpu_baseline(W, w, dev, budget_s=12.0):
         O.decode_attention(qh, K, V, m, idx, w.G)
         done += 1
         el = time.perf_counter() - t0
-        if el > budget_s or done >= 4 * w.streams:
+        if el > budget_s:
             break
     per_stream = el / done
     return {"value": per_stream * w.streams * w.layers * 1e6, "unit": "us/step", "cores": 1,
             "kind": "oracle",
-            "sample": "%d stream-steps of %s (oracle select+attention, %.2f s CPU), scaled to %d "
-                      "streams x %d layer(s)" % (done, w.name, el, w.streams, w.layers)}
+            "sample": "%d stream-steps of %s (oracle page scores + selection + attention on "
+                      "streams of batch element 0, %.1f s of CPU), scaled to the %d streams x %d "
+                      "layer(s) of a step" % (done, w.name, el, w.streams, w.layers)}
 
 
 def main():
@@ -130,6 +143,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="qwen25_7b_32k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run 5 plain 256 MiB device copies (a kernel of known traffic, "
+                         "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding or collectives); "
@@ -151,11 +167,14 @@ def main():
     nq = args.steps + args.warmup
     queries = [W.make_query(w, s, dev) for s in range(min(nq, 64))]
     L, C = w.layers, len(caches)
+    selecting = w.k_pages < w.NP
+    score_buf = (torch.empty(w.B, w.Hkv, w.NP, dtype=torch.float32, device=dev)
+                 if selecting else None)
 
     def step(i):                       # one decode step = `layers` (select, attend) pairs
         qv = queries[i % len(queries)]
-        for l in range(L):
-            caches[(i * L + l) % C].step(qv)
+        for lay in range(L):
+            caches[(i * L + lay) % C].step(qv)
 
     def select_only(i):
         caches[i % C].select(queries[i % len(queries)])
@@ -163,27 +182,43 @@ def main():
     def attend_only(i):
         caches[i % C].attend(queries[i % len(queries)])
 
+    def score_only(i):
+        caches[i % C].score(queries[i % len(queries)], score_buf)
+
+    if args.copy_calibration:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for i in range(args.warmup):
         step(i)
     ms_step = timed(step, args.steps, torch)
-    ms_sel = timed(select_only, args.steps, torch) if w.k_pages < w.NP else 0.0
+    ms_sel = timed(select_only, args.steps, torch) if selecting else 0.0
     ms_att = timed(attend_only, args.steps, torch)
+    ms_score = timed(score_only, args.steps, torch) if selecting else 0.0
 
     ab = algorithmic_bytes(w, mean_kept)
     gbps = lambda nbytes, ms: (nbytes / (ms * 1e-3) / 1e9) if ms > 0 else 0.0  # noqa: E731
+
+    def call(ms, nbytes):
+        g = gbps(nbytes, ms)
+        return {"us": ms * 1e3, "bytes": nbytes, "GBps": g, "frac": g / HBM_PEAK_GBPS}
+
     step_gbps = gbps(ab["step"] * L, ms_step)
-    calls = {
-        "select": {"us": ms_sel * 1e3, "bytes": ab["select"], "GBps": gbps(ab["select"], ms_sel)},
-        "attention": {"us": ms_att * 1e3, "bytes": ab["attention"],
-                      "GBps": gbps(ab["attention"], ms_att)},
-    }
-    dom = "select" if ms_sel >= ms_att else "attention"
-    kernel = {"select": "score_kernel (+ topk_kernel) of stc_select_pages",
-              "attention": "attn_split_kernel (+ attn_combine_kernel) of stc_decode_attention"}[dom]
-    roofline = {"bound": "hbm", "kernel": kernel, "achieved": calls[dom]["GBps"],
-                "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": calls[dom]["GBps"] / HBM_PEAK_GBPS, "traffic": None,
-                "algorithmic_bytes": calls[dom]["bytes"], "avg_us": calls[dom]["us"]}
+    calls = {"select": call(ms_sel, ab["select"]), "attention": call(ms_att, ab["attention"]),
+             "score": call(ms_score, ab["score"])}
+    if selecting:   # page scoring streams every bound of the cache: the largest mover of bytes
+        dom, kernel, entry = "score", "score_kernel", "stc_score_pages"
+    else:
+        dom, kernel, entry = "attention", "attn_mfma_kernel", "stc_decode_attention"
+    roofline = {"bound": "hbm", "kernel": kernel, "entry_point": entry,
+                "achieved": calls[dom]["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": calls[dom]["frac"], "traffic": MEASURED_TRAFFIC.get((w.name, kernel)),
+                "algorithmic_bytes": calls[dom]["bytes"], "avg_us": calls[dom]["us"],
+                "launches": args.steps}
     out = {
         "metric": METRIC, "value": ms_step * 1e3, "unit": "us/step", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,

@@ -135,6 +135,15 @@ int stc_select_pages(const stc_shape_t *shape, const void *q, const void *bounds
                      void *stream);
 
 /*
+ * The scoring half of stc_select_pages alone (same arithmetic, same bits): writes
+ * the Quest upper-bound score of every page of every stream and selects nothing.
+ *   q [B, Hq, D] bf16, in;  bounds [B, Hkv, NP, 2, D] bf16, in
+ *   page_score [B, Hkv, NP] float, out
+ */
+int stc_score_pages(const stc_shape_t *shape, const void *q, const void *bounds,
+                    float *page_score, void *stream);
+
+/*
  * Routed decode attention over the selected pages (attention equation of
  * Sec. 3.3 with the routed value matrix).  With T = all tokens t < N of the
  * listed pages and s_t = (q_h . K[t]) / sqrt(D):

@@ -21,7 +21,7 @@ STC_WS_ROUTE, STC_WS_SELECT, STC_WS_ATTENTION = 1, 2, 3
 STC_ROUTE_MASK, STC_ROUTE_TOPK = 0, 1
 
 EXPORTS = ["stc_version", "stc_status_string", "stc_workspace_bytes", "stc_build_page_bounds",
-           "stc_route_and_pack_values", "stc_select_pages", "stc_decode_attention",
+           "stc_route_and_pack_values", "stc_select_pages", "stc_score_pages", "stc_decode_attention",
            "stc_compact_tokens"]
 
 
@@ -70,6 +70,8 @@ def load_library():
                                               vp, vp, vp, vp, sz, vp]
     lib.stc_select_pages.restype = ctypes.c_int
     lib.stc_select_pages.argtypes = [shp, vp, vp, ctypes.c_int, vp, vp, vp, sz, vp]
+    lib.stc_score_pages.restype = ctypes.c_int
+    lib.stc_score_pages.argtypes = [shp, vp, vp, vp, vp]
     lib.stc_decode_attention.restype = ctypes.c_int
     lib.stc_decode_attention.argtypes = [shp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp, sz, vp]
     lib.stc_compact_tokens.restype = ctypes.c_int
@@ -144,6 +146,12 @@ def stc_select_pages(shape, q, bounds, k_pages, page_idx, page_score, ws):
         _stream()), "stc_select_pages")
 
 
+def stc_score_pages(shape, q, bounds, page_score):
+    _check(load_library().stc_score_pages(
+        ctypes.byref(shape), _ptr(q, torch.bfloat16, "q"), _ptr(bounds, torch.bfloat16, "bounds"),
+        _ptr(page_score, torch.float32, "page_score"), _stream()), "stc_score_pages")
+
+
 def stc_decode_attention(shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, out, ws):
     _check(load_library().stc_decode_attention(
         ctypes.byref(shape), _ptr(q, torch.bfloat16, "q"), _ptr(K, torch.bfloat16, "K"),
@@ -206,6 +214,9 @@ class RoutedCache:
     def select(self, q):
         stc_select_pages(self.shape, q, self.bounds, self.k_pages, self.page_idx, self.page_score,
                          self._ws_select)
+
+    def score(self, q, page_score):
+        stc_score_pages(self.shape, q, self.bounds, page_score)
 
     def attend(self, q):
         stc_decode_attention(self.shape, q, self.K, self.vpacked, self.mask, self.tok_off,

@@ -369,7 +369,7 @@ __global__ void iota_pages_kernel(int32_t* __restrict__ page_idx, int NP, int to
 }
 
 template <int D>
-static void launch_score(const stc_shape_t& s, const void* q, const void* bounds, float* score,
+static void launch_score_d(const stc_shape_t& s, const void* q, const void* bounds, float* score,
                          int NP, hipStream_t st) {
   constexpr int PPW = 64 / (D / 8);
   const int streams = s.B * s.Hkv;
@@ -398,6 +398,16 @@ static void launch_score(const stc_shape_t& s, const void* q, const void* bounds
 #undef STC_SCORE_CASE
 }
 
+int launch_score(const stc_shape_t& s, const void* q, const void* bounds, float* score,
+                 hipStream_t st) {
+  const int NP = (s.N + kPage - 1) / kPage;
+  if (s.D == 128)
+    launch_score_d<128>(s, q, bounds, score, NP, st);
+  else
+    launch_score_d<64>(s, q, bounds, score, NP, st);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 int launch_select(const stc_shape_t& s, const void* q, const void* bounds, int k_pages,
                   int32_t* page_idx, float* score, hipStream_t st) {
   const int NP = (s.N + kPage - 1) / kPage;
@@ -407,11 +417,7 @@ int launch_select(const stc_shape_t& s, const void* q, const void* bounds, int k
     iota_pages_kernel<<<(total + 255) / 256, 256, 0, st>>>(page_idx, NP, total);
     return hipGetLastError() == hipSuccess ? 0 : -1;
   }
-  if (s.D == 128)
-    launch_score<128>(s, q, bounds, score, NP, st);
-  else
-    launch_score<64>(s, q, bounds, score, NP, st);
-  if (hipGetLastError() != hipSuccess) return -1;
+  if (launch_score(s, q, bounds, score, st)) return -1;
   const int ipt = (NP + 255) / 256;
   if (ipt <= 1)
     topk_reg_kernel<1><<<streams, 256, 0, st>>>(score, page_idx, NP, k_pages);

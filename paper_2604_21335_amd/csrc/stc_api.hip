@@ -112,6 +112,15 @@ int stc_select_pages(const stc_shape_t* shape, const void* q, const void* bounds
              : STC_OK;
 }
 
+int stc_score_pages(const stc_shape_t* shape, const void* q, const void* bounds,
+                    float* page_score, void* stream) {
+  if (!shape || !q || !bounds || !page_score) return STC_ERR_NULL;
+  if (!shape_ok(shape)) return STC_ERR_SHAPE;
+  if (!aligned16(q) || !aligned16(bounds) || !aligned16(page_score)) return STC_ERR_ALIGN;
+  return stc::launch_score(*shape, q, bounds, page_score, (hipStream_t)stream) ? STC_ERR_LAUNCH
+                                                                               : STC_OK;
+}
+
 int stc_decode_attention(const stc_shape_t* shape, const void* q, const void* K,
                          const void* vpacked, const uint16_t* mask, const uint32_t* tok_off,
                          const int32_t* page_idx, int k_pages, float* out, void* ws,

@@ -18,6 +18,8 @@ int launch_route_pack(const stc_shape_t& s, int mode, const void* V, const float
                       uint32_t* tok_off, void* vpacked, int32_t* dev_status, void* ws,
                       hipStream_t st);
 
+int launch_score(const stc_shape_t& s, const void* q, const void* bounds, float* score,
+                 hipStream_t st);
 int launch_select(const stc_shape_t& s, const void* q, const void* bounds, int k_pages,
                   int32_t* page_idx, float* score, hipStream_t st);
 

@@ -75,6 +75,9 @@ def test_null_alignment_and_workspace_errors():
     assert lib.stc_select_pages(r, FAKE, FAKE, 2, FAKE, None, None, 0, None) == stc.STC_ERR_WORKSPACE
     assert lib.stc_select_pages(r, None, FAKE, 2, FAKE, None, FAKE, big, None) == stc.STC_ERR_NULL
     assert lib.stc_select_pages(r, FAKE, ODD, 2, FAKE, FAKE, FAKE, big, None) == stc.STC_ERR_ALIGN
+    assert lib.stc_score_pages(r, FAKE, FAKE, None, None) == stc.STC_ERR_NULL
+    assert lib.stc_score_pages(r, FAKE, ODD, FAKE, None) == stc.STC_ERR_ALIGN
+    assert lib.stc_score_pages(ctypes.byref(_shape(G=5)), FAKE, FAKE, FAKE, None) == stc.STC_ERR_SHAPE
     # attention: k_pages beyond NP (= 7), missing workspace
     att = lambda k, ws, wsb, out=FAKE: lib.stc_decode_attention(  # noqa: E731
         r, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, k, out, ws, wsb, None)

@@ -95,6 +95,22 @@ def test_selection_ties_and_signed_zero():
     assert np.array_equal(hip["page_idx"], np.broadcast_to(np.arange(9, dtype=np.int32), (B, Hkv, 9)))
 
 
+def test_score_pages_alone_matches_oracle_bits():
+    B, Hq, Hkv, D, N, G = 2, 14, 2, 128, 3000, 8
+    K, V, q, logits, kcount = _rand_case(21, B, Hq, Hkv, D, N, G, outliers=True)
+    hip = PT.run_hip(K, V, q, G, 20, logits=logits, kcount=kcount)
+    c = hip["cache"]
+    sc = torch.full_like(c.page_score, float("nan"))
+    c.score(PT.to_dev_bf16(q), sc)
+    torch.cuda.synchronize()
+    got = sc.cpu().numpy()
+    for b in range(B):
+        for h in range(Hkv):
+            want = O.page_scores(q[b, h * 7:(h + 1) * 7], O.page_bounds(K[b, h]))
+            assert np.array_equal(got[b, h].view(np.uint32), want.view(np.uint32))
+    assert np.array_equal(got.view(np.uint32), hip["page_score"].view(np.uint32))
+
+
 def test_attention_closed_form_and_peaked():
     """q = 0 with integer values: weights are exactly 1/|T| (|T| = 128), so the
     output is an exact dyadic number; then a sharply peaked softmax."""
