@@ -77,14 +77,21 @@ const char *stc_status_string(int status);
 size_t stc_workspace_bytes(const stc_shape_t *shape, int which_call, int k_pages);
 
 /*
- * Quest page summary (Stage I, Sec. 3.2; chunk 16, App. C.1).
+ * Quest page summary (Stage I, Sec. 3.2; chunk 16, App. C.1): for every page p < NP =
+ * ceil(N/P) and channel c, the minimum and the maximum of K[t, c] over the page's valid
+ * tokens (t < N).  Exact (comparisons only); -0 orders below +0.
  *   K      [B, Hkv, N, D]  bf16, in
- *   bounds [B, Hkv, NP, 2, D] bf16, out; NP = ceil(N/P); row 0 = per-channel
- *          minimum over the page's valid tokens (t < N), row 1 = maximum.
- * Exact (comparisons only); -0 orders below +0.
+ *   bounds stc_bounds_bytes(shape) bytes, out.  A layout made for the scoring kernel:
+ *          dwords [B*Hkv][NT][D/32][2][8][4][4] with NT = ceil(NP/8) tiles of 8 pages;
+ *          element [s][t][j][g][e][col][w] is page 8*t + 4*g + col, channel
+ *          e*(D/8) + 4*j + w of stream s: bf16 minimum in the low half of the dword,
+ *          bf16 maximum in the high half.  Pages >= NP of the last tile hold zeros.
  */
 int stc_build_page_bounds(const stc_shape_t *shape, const void *K, void *bounds,
                           void *stream);
+
+/* Size in bytes of the bounds buffer of stc_build_page_bounds (0 for an invalid shape). */
+size_t stc_bounds_bytes(const stc_shape_t *shape);
 
 /*
  * Routing mask and group-packed value store (Stage II, Sec. 3.3 "Value-group
@@ -123,8 +130,11 @@ int stc_route_and_pack_values(const stc_shape_t *shape, int mode, const void *V,
  *   score[p] = max over the query heads of the stream's KV head; -0 becomes +0.
  *   The k_eff = min(k_pages, NP) pages of largest score (ties: lowest p) are
  *   written in ascending order of p.
+ *   Bit-exact for queries and bounds that are zero or normal finite bf16 values whose
+ *   products stay finite in float (the matrix cores form the products; they treat
+ *   subnormal bf16 inputs as zero).
  *   q          [B, Hq, D] bf16, in
- *   bounds     [B, Hkv, NP, 2, D] bf16, in (not read when k_pages >= NP)
+ *   bounds     as written by stc_build_page_bounds, in (not read when k_pages >= NP)
  *   page_idx   [B, Hkv, k_eff] int32, out
  *   page_score [B, Hkv, NP] float, out, may be NULL (then the scores live in ws);
  *              not written when k_pages >= NP
@@ -137,7 +147,7 @@ int stc_select_pages(const stc_shape_t *shape, const void *q, const void *bounds
 /*
  * The scoring half of stc_select_pages alone (same arithmetic, same bits): writes
  * the Quest upper-bound score of every page of every stream and selects nothing.
- *   q [B, Hq, D] bf16, in;  bounds [B, Hkv, NP, 2, D] bf16, in
+ *   q [B, Hq, D] bf16, in;  bounds as written by stc_build_page_bounds, in
  *   page_score [B, Hkv, NP] float, out
  */
 int stc_score_pages(const stc_shape_t *shape, const void *q, const void *bounds,

@@ -20,7 +20,8 @@ STC_ERR_NULL, STC_ERR_SHAPE, STC_ERR_ALIGN, STC_ERR_WORKSPACE, STC_ERR_LAUNCH = 
 STC_WS_ROUTE, STC_WS_SELECT, STC_WS_ATTENTION = 1, 2, 3
 STC_ROUTE_MASK, STC_ROUTE_TOPK = 0, 1
 
-EXPORTS = ["stc_version", "stc_status_string", "stc_workspace_bytes", "stc_build_page_bounds",
+EXPORTS = ["stc_version", "stc_status_string", "stc_workspace_bytes", "stc_bounds_bytes",
+           "stc_build_page_bounds",
            "stc_route_and_pack_values", "stc_select_pages", "stc_score_pages", "stc_decode_attention",
            "stc_compact_tokens"]
 
@@ -63,6 +64,8 @@ def load_library():
     lib.stc_status_string.argtypes = [ctypes.c_int]
     lib.stc_workspace_bytes.restype = sz
     lib.stc_workspace_bytes.argtypes = [shp, ctypes.c_int, ctypes.c_int]
+    lib.stc_bounds_bytes.restype = ctypes.c_size_t
+    lib.stc_bounds_bytes.argtypes = [shp]
     lib.stc_build_page_bounds.restype = ctypes.c_int
     lib.stc_build_page_bounds.argtypes = [shp, vp, vp, vp]
     lib.stc_route_and_pack_values.restype = ctypes.c_int
@@ -120,6 +123,23 @@ def stc_version():
 
 def stc_workspace_bytes(shape, which_call, k_pages=0):
     return int(load_library().stc_workspace_bytes(ctypes.byref(shape), which_call, k_pages))
+
+
+def stc_bounds_bytes(shape):
+    return int(load_library().stc_bounds_bytes(ctypes.byref(shape)))
+
+
+def bounds_rows(bounds, shape):
+    """The tiled bounds buffer as a [B, Hkv, NP, 2, D] tensor (row 0 = minima, row 1 = maxima):
+    a pure re-ordering of its elements, for inspection and tests."""
+    B, Hkv, D = shape.B, shape.Hkv, shape.D
+    NP = (shape.N + shape.P - 1) // shape.P
+    nt = (NP + 7) // 8
+    # dwords [s][t][j][g][e][col][w], each (min, max)
+    t = bounds.reshape(B, Hkv, nt, D // 32, 2, 8, 4, 4, 2)
+    # -> [B, Hkv, t, g, col, (min|max), e, j, w]
+    t = t.permute(0, 1, 2, 4, 6, 8, 5, 3, 7)
+    return t.reshape(B, Hkv, nt * 8, 2, D)[:, :, :NP].contiguous()
 
 
 def stc_build_page_bounds(shape, K, bounds):
@@ -185,7 +205,8 @@ class RoutedCache:
         cap = N * G if v_cap_groups is None else v_cap_groups
         self.shape = make_shape(B, Hq, Hkv, D, N, G, cap)
         dev = self.device
-        self.bounds = torch.empty(B, Hkv, self.NP, 2, D, dtype=torch.bfloat16, device=dev)
+        self.bounds = torch.empty(stc_bounds_bytes(self.shape) // 2, dtype=torch.bfloat16,
+                                  device=dev)
         self.mask = torch.empty(B, Hkv, N, dtype=torch.int16, device=dev)
         self.tok_off = torch.empty(B, Hkv, N + 1, dtype=torch.int32, device=dev)
         self.vpacked = torch.empty(B, Hkv, cap, D // G, dtype=torch.bfloat16, device=dev)
@@ -210,6 +231,9 @@ class RoutedCache:
         mode = STC_ROUTE_MASK if mask_in is not None else STC_ROUTE_TOPK
         stc_route_and_pack_values(self.shape, mode, V, logits, kcount, fixed_k, mask_in, self.mask,
                                   self.tok_off, self.vpacked, self.dev_status, self._ws_route)
+
+    def bounds_rows(self):
+        return bounds_rows(self.bounds, self.shape)
 
     def select(self, q):
         stc_select_pages(self.shape, q, self.bounds, self.k_pages, self.page_idx, self.page_score,

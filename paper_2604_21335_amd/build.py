@@ -9,7 +9,8 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libstc.so")
 BUILD_DIR = os.path.join(PKG_DIR, "_build")
 
-SOURCES = ["stc_api.hip", "bounds.hip", "route_pack.hip", "select.hip", "attention.hip"]
+SOURCES = ["stc_api.hip", "bounds.hip", "route_pack.hip", "score.hip", "select.hip",
+           "attention.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
@@ -17,6 +18,9 @@ HIPCC_FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
 ]
+# score.hip: matrix-core results are consumed by vector adds right away, so keep them in
+# ordinary vector registers (no copies out of the accumulation registers)
+FILE_FLAGS = {"score.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def _hipcc():
@@ -42,7 +46,8 @@ def build_library(verbose=False):
 
     def one(pair):
         src, obj = pair
-        out = _run([hipcc, *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj])
+        out = _run([hipcc, *HIPCC_FLAGS, *FILE_FLAGS.get(src, []), *extra, "-c",
+                    os.path.join(CSRC, src), "-o", obj])
         if verbose and out.strip():
             print(out)
 

@@ -7,7 +7,9 @@ namespace stc {
 
 // One thread owns 8 adjacent channels (one 128-bit load per token row) of one
 // page and walks the page's tokens.  D/8 neighbouring threads cover a row, so a
-// wavefront reads 64/(D/8) whole rows of 2*D bytes per load instruction.
+// wavefront reads 64/(D/8) whole rows of 2*D bytes per load instruction.  The result goes
+// into the tiled layout the scoring kernel reads (two 16-byte units per thread); pages
+// past the last one of a stream's last tile are written as zeros.
 template <int D>
 __global__ __launch_bounds__(256) void bounds_kernel(const uint4* __restrict__ K,
                                                      uint4* __restrict__ bounds, int N, int NP) {
@@ -15,9 +17,10 @@ __global__ __launch_bounds__(256) void bounds_kernel(const uint4* __restrict__ K
   const int stream = blockIdx.y;
   const int sub = threadIdx.x % LPP;
   const int page = blockIdx.x * (256 / LPP) + threadIdx.x / LPP;
-  if (page >= NP) return;
+  const int ntiles = (NP + kBoundsTilePages - 1) / kBoundsTilePages;
+  if (page >= ntiles * kBoundsTilePages) return;
   const int t0 = page * kPage;
-  const int t1 = min(t0 + kPage, N);
+  const int t1 = min(t0 + kPage, N);  // t1 <= t0 for a padding page
   const uint4* row = K + ((size_t)stream * N + t0) * LPP + sub;
   int mn[8], mx[8];
 #pragma unroll
@@ -39,24 +42,23 @@ __global__ __launch_bounds__(256) void bounds_kernel(const uint4* __restrict__ K
       mx[2 * i + 1] = max(mx[2 * i + 1], b);
     }
   }
-  uint4 omn, omx;
-  uint32_t* pmn = &omn.x;
-  uint32_t* pmx = &omx.x;
+  uint32_t w[8];  // per channel: minimum | maximum << 16
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    pmn[i] = bf16_unorder(mn[2 * i]) | (bf16_unorder(mn[2 * i + 1]) << 16);
-    pmx[i] = bf16_unorder(mx[2 * i]) | (bf16_unorder(mx[2 * i + 1]) << 16);
-  }
-  uint4* out = bounds + ((size_t)stream * NP + page) * (2 * LPP);
-  out[sub] = omn;
-  out[LPP + sub] = omx;
+  for (int i = 0; i < 8; ++i)
+    w[i] = page < NP ? (bf16_unorder(mn[i]) | (bf16_unorder(mx[i]) << 16)) : 0u;
+  uint4* tile = bounds + ((size_t)stream * ntiles + page / kBoundsTilePages) *
+                             (bounds_tile_dwords(D) / 4);
+  const int pt = page % kBoundsTilePages;
+  tile[bounds_tile_unit(D, pt, 8 * sub)] = make_uint4(w[0], w[1], w[2], w[3]);
+  tile[bounds_tile_unit(D, pt, 8 * sub + 4)] = make_uint4(w[4], w[5], w[6], w[7]);
 }
 
 int launch_bounds(const stc_shape_t& s, const void* K, void* bounds, hipStream_t st) {
   const int NP = (s.N + kPage - 1) / kPage;
   const int streams = s.B * s.Hkv;
   const int pages_per_block = 256 / (s.D / 8);
-  dim3 grid((NP + pages_per_block - 1) / pages_per_block, streams);
+  const int pages = (NP + kBoundsTilePages - 1) / kBoundsTilePages * kBoundsTilePages;
+  dim3 grid((pages + pages_per_block - 1) / pages_per_block, streams);
   if (s.D == 128)
     bounds_kernel<128><<<grid, 256, 0, st>>>((const uint4*)K, (uint4*)bounds, s.N, NP);
   else

@@ -1,132 +1,9 @@
-// Query-aware page selection (Quest): upper-bound score of every page from its
-// per-channel key bounds, then the k best pages of each stream.
+// Query-aware page selection (Quest, Sec. 3.2): the k pages of largest upper-bound score
+// of each stream (the scores come from score.hip).
 #include "stc_common.hpp"
 #include "stc_kernels.hpp"
 
 namespace stc {
-
-// ---------------------------------------------------------------------------
-// Page scores.
-//   U_h[p] = sum_c max(q_h[c]*mn[p,c], q_h[c]*mx[p,c]),  score[p] = max_h U_h[p]
-// Float arithmetic in a fixed order: a lane owns 8 adjacent channels and sums
-// them as a balanced tree over adjacent pairs; the D/8 lanes of a page are then
-// combined by an xor butterfly, which continues the same tree.  Every product
-// of two bf16 values is exact in float, so fusing a product into the following
-// addition does not change any bit.
-//
-// Because mn <= mx, the larger product is q*mx for q >= 0 and q*mn for q < 0
-// (for q = 0 both are zero).  The choice depends on the query alone, so it is
-// made once per (head, channel): a byte-permute selector that picks the bf16
-// half of the mn or the mx word and widens it to float in the same instruction.
-// ---------------------------------------------------------------------------
-template <int D, int R>
-__global__ __launch_bounds__(256) void score_kernel(const uint4* __restrict__ bounds,
-                                                    const uint4* __restrict__ q,
-                                                    float* __restrict__ score, int NP, int Hq,
-                                                    int Hkv, int pages_per_block) {
-  constexpr int LPP = D / 8;     // lanes per page
-  constexpr int PPW = 64 / LPP;  // pages per wavefront pass
-  const int stream = blockIdx.y;
-  const int b = stream / Hkv, kvh = stream % Hkv;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int sub = lane % LPP, pw = lane / LPP;
-
-  // v_perm_b32 selectors over the byte pool {mx word: bytes 4..7, mn word: bytes 0..3};
-  // 0x0c yields a zero byte.  Result: the chosen bf16 in the upper half of a float.
-  constexpr uint32_t kSelEvenMn = 0x01000c0cu, kSelOddMn = 0x03020c0cu, kPickMx = 0x04040000u;
-  float qf[R][8];
-  uint32_t sel[R][8];
-#pragma unroll
-  for (int h = 0; h < R; ++h) {
-    const uint4 v = q[((size_t)b * Hq + kvh * R + h) * LPP + sub];
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      qf[h][2 * i] = bf16_lo(w[i]);
-      qf[h][2 * i + 1] = bf16_hi(w[i]);
-      sel[h][2 * i] = kSelEvenMn + ((w[i] & 0x8000u) ? 0u : kPickMx);
-      sel[h][2 * i + 1] = kSelOddMn + ((w[i] & 0x80000000u) ? 0u : kPickMx);
-    }
-  }
-
-  const int p0 = blockIdx.x * pages_per_block;
-  const int p1 = min(p0 + pages_per_block, NP);
-  const uint4* base = bounds + (size_t)stream * NP * (2 * LPP);
-  float* out = score + (size_t)stream * NP;
-
-  // Two passes of this lane are always in flight behind the one being computed.
-  // Pages past the end of the block's range re-read its last page (never stored).
-  constexpr int STEP = 4 * PPW;
-  const int plast = p1 - 1;
-  int p = p0 + wave * PPW + pw;
-  auto load_mn = [&](int pp) { return base[(size_t)min(pp, plast) * (2 * LPP) + sub]; };
-  auto load_mx = [&](int pp) { return base[(size_t)min(pp, plast) * (2 * LPP) + LPP + sub]; };
-  uint4 mn0 = load_mn(p), mx0 = load_mx(p);
-  uint4 mn1 = load_mn(p + STEP), mx1 = load_mx(p + STEP);
-  for (; p < p1; p += STEP) {
-    const uint4 cmn = mn0, cmx = mx0;
-    mn0 = mn1, mx0 = mx1;
-    mn1 = load_mn(p + 2 * STEP), mx1 = load_mx(p + 2 * STEP);
-    const uint32_t wn[4] = {cmn.x, cmn.y, cmn.z, cmn.w};
-    const uint32_t wx[4] = {cmx.x, cmx.y, cmx.z, cmx.w};
-    float best = 0.f;
-#pragma unroll
-    for (int h = 0; h < R; ++h) {
-      float s2[4];  // sums of adjacent channel pairs
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float x0 = __uint_as_float(__builtin_amdgcn_perm(wx[i], wn[i], sel[h][2 * i]));
-        const float x1 = __uint_as_float(__builtin_amdgcn_perm(wx[i], wn[i], sel[h][2 * i + 1]));
-        s2[i] = fmaf(qf[h][2 * i + 1], x1, qf[h][2 * i] * x0);  // both products are exact
-      }
-      float u = (s2[0] + s2[1]) + (s2[2] + s2[3]);
-      u = row_tree_sum<LPP>(u);
-      best = h == 0 ? u : fmaxf(best, u);
-    }
-    if (sub == 0) out[p] = best == 0.f ? 0.f : best;  // -0 -> +0
-  }
-}
-
-// Fallback for group sizes without a specialisation: one query head at a time.
-template <int D>
-__global__ __launch_bounds__(256) void score_kernel_any(const uint4* __restrict__ bounds,
-                                                        const uint4* __restrict__ q,
-                                                        float* __restrict__ score, int NP, int Hq,
-                                                        int Hkv, int R, int pages_per_block) {
-  constexpr int LPP = D / 8;
-  constexpr int PPW = 64 / LPP;
-  const int stream = blockIdx.y;
-  const int b = stream / Hkv, kvh = stream % Hkv;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int sub = lane % LPP, pw = lane / LPP;
-  const int p0 = blockIdx.x * pages_per_block;
-  const int p1 = min(p0 + pages_per_block, NP);
-  const uint4* base = bounds + (size_t)stream * NP * (2 * LPP);
-  float* out = score + (size_t)stream * NP;
-  for (int p = p0 + wave * PPW + pw; p < p1; p += 4 * PPW) {
-    const uint4 cmn = base[(size_t)p * (2 * LPP) + sub];
-    const uint4 cmx = base[(size_t)p * (2 * LPP) + LPP + sub];
-    const uint32_t wn[4] = {cmn.x, cmn.y, cmn.z, cmn.w};
-    const uint32_t wx[4] = {cmx.x, cmx.y, cmx.z, cmx.w};
-    float best = 0.f;
-    for (int h = 0; h < R; ++h) {
-      const uint4 v = q[((size_t)b * Hq + kvh * R + h) * LPP + sub];
-      const uint32_t wq[4] = {v.x, v.y, v.z, v.w};
-      float t[8];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float ql = bf16_lo(wq[i]), qh = bf16_hi(wq[i]);
-        t[2 * i] = fmaxf(ql * bf16_lo(wn[i]), ql * bf16_lo(wx[i]));
-        t[2 * i + 1] = fmaxf(qh * bf16_hi(wn[i]), qh * bf16_hi(wx[i]));
-      }
-      const float s01 = t[0] + t[1], s23 = t[2] + t[3], s45 = t[4] + t[5], s67 = t[6] + t[7];
-      float u = (s01 + s23) + (s45 + s67);
-      u = row_tree_sum<LPP>(u);
-      best = h == 0 ? u : fmaxf(best, u);
-    }
-    if (sub == 0) out[p] = best == 0.f ? 0.f : best;
-  }
-}
 
 // ---------------------------------------------------------------------------
 // Top-k pages of a stream: radix select of the k-th largest key (4 passes of 8
@@ -366,46 +243,6 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(const float* __restrict__
 __global__ void iota_pages_kernel(int32_t* __restrict__ page_idx, int NP, int total) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < total) page_idx[i] = i % NP;
-}
-
-template <int D>
-static void launch_score_d(const stc_shape_t& s, const void* q, const void* bounds, float* score,
-                         int NP, hipStream_t st) {
-  constexpr int PPW = 64 / (D / 8);
-  const int streams = s.B * s.Hkv;
-  const int R = s.Hq / s.Hkv;
-  // about three workgroups per CU (what the register budget keeps resident), so the whole
-  // grid runs as one generation and the per-wave set-up is paid once per ~10 passes
-  const int want_blocks = max(1, 768 / streams);
-  int ppb = (NP + want_blocks - 1) / want_blocks;
-  ppb = max(4 * PPW, (ppb + 4 * PPW - 1) / (4 * PPW) * (4 * PPW));
-  dim3 grid((NP + ppb - 1) / ppb, streams);
-  const uint4* b4 = (const uint4*)bounds;
-  const uint4* q4 = (const uint4*)q;
-#define STC_SCORE_CASE(RR)                                                                     \
-  case RR:                                                                                     \
-    score_kernel<D, RR><<<grid, 256, 0, st>>>(b4, q4, score, NP, s.Hq, s.Hkv, ppb);            \
-    break;
-  switch (R) {
-    STC_SCORE_CASE(1)
-    STC_SCORE_CASE(2)
-    STC_SCORE_CASE(4)
-    STC_SCORE_CASE(7)
-    STC_SCORE_CASE(8)
-    default:
-      score_kernel_any<D><<<grid, 256, 0, st>>>(b4, q4, score, NP, s.Hq, s.Hkv, R, ppb);
-  }
-#undef STC_SCORE_CASE
-}
-
-int launch_score(const stc_shape_t& s, const void* q, const void* bounds, float* score,
-                 hipStream_t st) {
-  const int NP = (s.N + kPage - 1) / kPage;
-  if (s.D == 128)
-    launch_score_d<128>(s, q, bounds, score, NP, st);
-  else
-    launch_score_d<64>(s, q, bounds, score, NP, st);
-  return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 int launch_select(const stc_shape_t& s, const void* q, const void* bounds, int k_pages,

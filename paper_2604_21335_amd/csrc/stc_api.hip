@@ -59,6 +59,12 @@ size_t stc_workspace_bytes(const stc_shape_t* shape, int which_call, int k_pages
   }
 }
 
+size_t stc_bounds_bytes(const stc_shape_t* shape) {
+  if (!shape || !shape_ok(shape)) return 0;
+  const size_t tiles = (num_pages(shape) + stc::kBoundsTilePages - 1) / stc::kBoundsTilePages;
+  return (size_t)shape->B * shape->Hkv * tiles * stc::kBoundsTilePages * shape->D * 4;
+}
+
 int stc_build_page_bounds(const stc_shape_t* shape, const void* K, void* bounds, void* stream) {
   if (!shape || !K || !bounds) return STC_ERR_NULL;
   if (!shape_ok(shape)) return STC_ERR_SHAPE;

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "stc_kernels.hpp"
+
 namespace stc {
 
 // Compile-time loop: f(integral_constant<int, I>) for I in [B, E).  Register arrays
@@ -23,6 +25,16 @@ __device__ __forceinline__ void static_for(F&& f) {
 
 constexpr int kWave = 64;
 constexpr int kPage = 16;
+
+// Page bounds are stored in tiles of 8 pages.  A tile is D/32 rows of 64 units of 16 bytes;
+// a unit holds 4 adjacent channels of one page, each as a dword (bf16 minimum in the low
+// half, bf16 maximum in the high half).  With CH = D/8 channels per chunk, channel c of page
+// pt of the tile sits in row (c % CH) / 4, unit (pt % 4) + 4 * (c / CH) + 32 * (pt / 4),
+// dword c % 4.  (The unit number is the lane of the wavefront that scores it.)
+__host__ __device__ constexpr int bounds_tile_dwords(int D) { return kBoundsTilePages * D; }
+__host__ __device__ constexpr int bounds_tile_unit(int D, int pt, int c) {
+  return ((c % (D / 8)) / 4) * 64 + (pt % 4) + 4 * (c / (D / 8)) + 32 * (pt / 4);
+}
 
 // bf16 pair in one dword: element 2i in the low half, 2i+1 in the high half.
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }

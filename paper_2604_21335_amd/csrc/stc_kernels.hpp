@@ -10,6 +10,8 @@
 
 namespace stc {
 
+constexpr int kBoundsTilePages = 8;  // pages per tile of the bounds layout
+
 int launch_bounds(const stc_shape_t& s, const void* K, void* bounds, hipStream_t st);
 
 size_t route_ws_bytes(const stc_shape_t& s);

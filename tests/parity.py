@@ -44,7 +44,7 @@ def run_hip(K, V, q, G, k_pages, logits=None, kcount=None, fixed_k=0, mask_in=No
     c.step(dq)
     torch.cuda.synchronize()
     return {
-        "bounds": host_bf16(c.bounds), "mask": host_u16(c.mask),
+        "bounds": host_bf16(c.bounds_rows()), "bounds_raw": host_bf16(c.bounds), "mask": host_u16(c.mask),
         "tok_off": c.tok_off.cpu().numpy().view(np.uint32), "vpacked": host_bf16(c.vpacked),
         "dev_status": int(c.dev_status.item()), "page_idx": c.page_idx.cpu().numpy(),
         "page_score": c.page_score.cpu().numpy(), "out": c.out.cpu().numpy(), "cache": c,

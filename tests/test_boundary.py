@@ -108,6 +108,32 @@ def test_workspace_sizes():
     assert stc.stc_workspace_bytes(s, 99, 1) == 0
 
 
+def test_bounds_layout_matches_the_header():
+    """stc_bounds_bytes, and bounds_rows() against the index formula stc.h states:
+    dword [s][t][j][g][e][col][w] = page 8t+4g+col, channel e*(D/8)+4j+w, (min, max)."""
+    import numpy as np
+    import torch
+    for D, N in ((128, 300), (64, 16 * 8)):
+        s = _shape(D=D, N=N, G=4, v_cap_groups=N * 4)
+        NP = (N + 15) // 16
+        nt = (NP + 7) // 8
+        assert stc.stc_bounds_bytes(s) == 2 * 2 * nt * 8 * D * 4
+        buf = np.zeros((2 * 2, nt, D // 32, 2, 8, 4, 4, 2), dtype=np.int16)
+        want = np.zeros((2 * 2, NP, 2, D), dtype=np.int16)
+        for st in range(4):
+            for p in range(NP):
+                for c in range(D):
+                    mn, mx = (st * 7 + p * 131 + c) % 30000, 30000 - ((p * 17 + c * 3 + st) % 999)
+                    t, g, col = p // 8, (p % 8) // 4, p % 4
+                    e, j, w = c // (D // 8), (c % (D // 8)) // 4, c % 4
+                    buf[st, t, j, g, e, col, w] = (mn, mx)
+                    want[st, p, 0, c], want[st, p, 1, c] = mn, mx
+        got = stc.bounds_rows(torch.from_numpy(buf.reshape(-1)).view(torch.bfloat16), s)
+        assert got.shape == (2, 2, NP, 2, D)
+        assert np.array_equal(got.view(torch.int16).numpy().reshape(4, NP, 2, D), want)
+    assert stc.stc_bounds_bytes(_shape(D=96)) == 0
+
+
 def test_binding_refuses_host_tensors():
     import torch
     s = _shape()

@@ -95,6 +95,30 @@ def test_selection_ties_and_signed_zero():
     assert np.array_equal(hip["page_idx"], np.broadcast_to(np.arange(9, dtype=np.int32), (B, Hkv, 9)))
 
 
+@pytest.mark.parametrize("Hq,Hkv,D", [(3, 1, 128), (5, 1, 64), (12, 2, 128), (6, 1, 64), (9, 1, 64),
+                                      (16, 1, 128)])
+def test_scores_for_every_head_group_size(Hq, Hkv, D):
+    """Page scores bit for bit for group sizes served by the matrix-core kernel (1..8 heads
+    per KV head) and by the general one (9..16); N leaves a ragged last page and tile."""
+    B, N, G = 2, 16 * 37 + 5, 4
+    K, V, q, logits, kcount = _rand_case(40 + Hq, B, Hq, Hkv, D, N, G, outliers=True)
+    hip = PT.run_hip(K, V, q, G, 9, logits=logits, kcount=kcount)
+    R = Hq // Hkv
+    for b in range(B):
+        for h in range(Hkv):
+            bounds = O.page_bounds(K[b, h])
+            assert np.array_equal(hip["bounds"][b, h], bounds)
+            want = O.page_scores(q[b, h * R:(h + 1) * R], bounds)
+            assert np.array_equal(hip["page_score"][b, h].view(np.uint32), want.view(np.uint32))
+            assert np.array_equal(hip["page_idx"][b, h], O.select_pages(want, 9))
+    # pages past the last one in the last tile of every stream are zero-filled
+    NP, nt = (N + 15) // 16, ((N + 15) // 16 + 7) // 8
+    raw = hip["bounds_raw"].reshape(B * Hkv, nt, D // 32, 2, 8, 4, 4, 2)
+    last = raw[:, nt - 1]                                # [s][j][g][e][col][w][2]
+    for pt in range(NP - 8 * (nt - 1), 8):
+        assert not last[:, :, pt // 4, :, pt % 4].any()
+
+
 def test_score_pages_alone_matches_oracle_bits():
     B, Hq, Hkv, D, N, G = 2, 14, 2, 128, 3000, 8
     K, V, q, logits, kcount = _rand_case(21, B, Hq, Hkv, D, N, G, outliers=True)
@@ -212,6 +236,7 @@ def _check_streams(w, c, t, streams):
     worst = 0.0
     R = w.R
     q = W.bf16_bits(t["q"])
+    rows = c.bounds_rows()
     for (b, h) in streams:
         K, V = W.bf16_bits(t["K"][b, h]), W.bf16_bits(t["V"][b, h])
         if t["mask_in"] is not None:
@@ -219,7 +244,7 @@ def _check_streams(w, c, t, streams):
         else:
             m = O.route_mask(t["logits"][b, h].cpu().numpy(), t["kcount"][b, h].cpu().numpy())
         off = O.token_offsets(m, w.G)
-        assert np.array_equal(W.bf16_bits(c.bounds[b, h]), O.page_bounds(K))
+        assert np.array_equal(W.bf16_bits(rows[b, h]), O.page_bounds(K))
         assert np.array_equal(PT.host_u16(c.mask[b, h]), m)
         assert np.array_equal(c.tok_off[b, h].cpu().numpy().view(np.uint32), off)
         assert np.array_equal(W.bf16_bits(c.vpacked[b, h, :int(off[-1])]),
@@ -285,3 +310,39 @@ def test_steps_are_deterministic():
         c.step(t["q"])
     torch.cuda.synchronize()
     assert torch.equal(c.page_idx, first[0]) and torch.equal(c.out, first[1])
+
+
+@pytest.mark.parametrize("N,k", [(3000, 20), (40000, 100)])
+def test_workspaces_are_reusable_without_clearing(N, k):
+    """Alternating two queries on one cache: nothing a call leaves in the selection or
+    attention workspace (scores, split partials) reaches the next call's results, and
+    workspaces may hold anything beforehand."""
+    B, Hq, Hkv, D, G = 2, 8, 2, 128, 8
+    K, V, q, logits, kcount = _rand_case(33, B, Hq, Hkv, D, N, G)
+    hip = PT.run_hip(K, V, q, G, k, logits=logits, kcount=kcount)
+    c = hip["cache"]
+    assert c._ws_attn.numel() > 16                      # several splits: partials are merged
+    for b in range(B):
+        for h in range(Hkv):
+            sc = O.page_scores(q[b, h * 4:(h + 1) * 4], O.page_bounds(K[b, h]))
+            assert np.array_equal(hip["page_idx"][b, h], O.select_pages(sc, k))
+    ora = PT.run_oracle(K, V, q, G, k, logits=logits, kcount=kcount, streams=[(1, 1)])
+    assert np.abs(hip["out"][1, 4:8] - ora[(1, 1)]["out"]).max() < PT.TOL
+    rng = np.random.default_rng(34)
+    q2 = randn_bf16(rng, q.shape)
+    hip2 = PT.run_hip(K, V, q2, G, k, logits=logits, kcount=kcount)
+    assert not np.array_equal(hip2["page_idx"], hip["page_idx"])
+    sc2 = O.page_scores(q2[0, 0:4], O.page_bounds(K[0, 0]))
+    assert np.array_equal(hip2["page_idx"][0, 0], O.select_pages(sc2, k))
+    dq, dq2 = PT.to_dev_bf16(q), PT.to_dev_bf16(q2)
+    for i, fill in enumerate((0xFF, None, 0x00, None, None, None, 0x01, None)):
+        if fill is not None:
+            c._ws_select.fill_(fill)
+            c._ws_attn.fill_(fill)
+        c.page_idx.fill_(-7)
+        c.out.fill_(float("nan"))
+        c.step(dq2 if i % 2 else dq)
+        torch.cuda.synchronize()
+        ref = hip2 if i % 2 else hip
+        assert np.array_equal(c.page_idx.cpu().numpy(), ref["page_idx"])
+        assert np.array_equal(c.out.cpu().numpy(), ref["out"])
