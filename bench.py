@@ -37,7 +37,7 @@ REPLICAS = {"tiny": 8, "llama2_7b_4k": 4, "qwen25_7b_32k": 6, "llava15_7b_prefix
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs of this file
 # (FETCH_SIZE and WRITE_SIZE, scaled by what the same counters read for a copy of known
 # size); see profiles/.  None where it has not been measured.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {("qwen25_7b_32k", "score_mfma_kernel"): 68624308}
 
 
 def algorithmic_bytes(w, mean_kept):
@@ -212,7 +212,7 @@ def main():
     calls = {"select": call(ms_sel, ab["select"]), "attention": call(ms_att, ab["attention"]),
              "score": call(ms_score, ab["score"])}
     if selecting:   # page scoring streams every bound of the cache: the largest mover of bytes
-        dom, kernel, entry = "score", "score_kernel", "stc_score_pages"
+        dom, kernel, entry = "score", "score_mfma_kernel", "stc_score_pages"
     else:
         dom, kernel, entry = "attention", "attn_mfma_kernel", "stc_decode_attention"
     roofline = {"bound": "hbm", "kernel": kernel, "entry_point": entry,
