@@ -18,9 +18,10 @@ HIPCC_FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
 ]
-# score.hip: matrix-core results are consumed by vector adds right away, so keep them in
+# matrix-core results are consumed by vector instructions right away, so keep them in
 # ordinary vector registers (no copies out of the accumulation registers)
-FILE_FLAGS = {"score.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+_VGPR_MFMA = ["-mllvm", "-amdgpu-mfma-vgpr-form"]
+FILE_FLAGS = {"score.hip": _VGPR_MFMA, "attention.hip": _VGPR_MFMA}
 
 
 def _hipcc():

@@ -31,7 +31,7 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f;  // "no token seen yet" running maximum
-constexpr int kAttnWaves = 4;        // wavefronts per workgroup
+constexpr int kAttnMaxWaves = 8;     // wavefronts per workgroup: 4 or 8
 
 // Partial result of one (query head, split): [0] running max (base-2 logits),
 // [1] sum of weights, [2 .. 2+D) weighted value sum.
@@ -103,8 +103,8 @@ __device__ long long* stc_dbg_ptr = nullptr;
 // next pair's K rows.  All loads are unconditional (addresses of absent pages or
 // tokens collapse to one valid location and the result is discarded) so that they
 // stay in flight across the arithmetic.
-template <int D, int PAIRS>
-__global__ __launch_bounds__(64 * kAttnWaves) void attn_mfma_kernel(
+template <int D, int PAIRS, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K,
     const unsigned char* __restrict__ vpacked, const uint16_t* __restrict__ mask,
     const uint32_t* __restrict__ tok_off, const int32_t* __restrict__ page_idx,
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(64 * kAttnWaves) void attn_mfma_kernel(
     uint32_t cap, int k_pages, int splits) {
   using C = AttnCfg<D>;
   constexpr int ppw = 2 * PAIRS;  // pages per wavefront
-  __shared__ __align__(16) unsigned char lds[kAttnWaves * C::WAVE_LDS];
+  extern __shared__ __align__(16) unsigned char lds[];  // WAVES * C::WAVE_LDS bytes
   const int stream = blockIdx.y, split = blockIdx.x;
   const int b = stream / Hkv, kvh = stream % Hkv;
   const int R = Hq / Hkv;
@@ -137,7 +137,7 @@ __global__ __launch_bounds__(64 * kAttnWaves) void attn_mfma_kernel(
   const unsigned char* vs = vpacked + (size_t)stream * (size_t)cap * gbytes;
 
   // this wavefront's pages: lane i holds page pi0 + i (or -1)
-  const int pi0 = (split * kAttnWaves + wave) * ppw;
+  const int pi0 = (split * WAVES + wave) * ppw;
   const int npages = max(0, min(ppw, k_pages - pi0));
   int my_pg = -1;
   if (lane < npages) {
@@ -415,17 +415,17 @@ __global__ __launch_bounds__(64 * kAttnWaves) void attn_mfma_kernel(
   }
   __syncthreads();
   STC_MARK(14, lane);
-  for (int i = threadIdx.x; i < R * D; i += 64 * kAttnWaves) {
+  for (int i = threadIdx.x; i < R * D; i += 64 * WAVES) {
     const int head = i / D, c = i % D;
-    float mw[kAttnWaves], m = kNegBig;
+    float mw[WAVES], m = kNegBig;
 #pragma unroll
-    for (int w = 0; w < kAttnWaves; ++w) {
+    for (int w = 0; w < WAVES; ++w) {
       mw[w] = ((const float*)(lds + w * C::WAVE_LDS + 16 * D * 4))[head * 2];
       m = fmaxf(m, mw[w]);
     }
     float lsum = 0.f, a = 0.f;
 #pragma unroll
-    for (int w = 0; w < kAttnWaves; ++w) {
+    for (int w = 0; w < WAVES; ++w) {
       const float wgt = __builtin_amdgcn_exp2f(mw[w] - m);
       lsum = fmaf(wgt, ((const float*)(lds + w * C::WAVE_LDS + 16 * D * 4))[head * 2 + 1], lsum);
       a = fmaf(wgt, ((const float*)(lds + w * C::WAVE_LDS))[head * D + c], a);
@@ -480,25 +480,34 @@ __global__ __launch_bounds__(D) void attn_combine_kernel(const float* __restrict
   out[(size_t)head * D + c] = l > 0.f ? a / l : 0.f;
 }
 
-// Pages per wavefront: 4 if that still leaves two workgroups per CU (their register
-// budget keeps two resident), else 2; never more than the pages there are.
-static int attention_ppw(const stc_shape_t& s, int k_pages) {
+// Shape of the launch: wavefronts per workgroup, pages per wavefront, workgroups per stream.
+// Measured on the paper-shaped workloads, one pair of pages per wavefront and 8 wavefronts
+// per workgroup is the fastest shape whenever it still gives every CU a workgroup; with few
+// streams, workgroups of 4 wavefronts (twice as many of them) fill the chip better.  The
+// two-pairs-per-wavefront form of the kernel is kept for tuning builds only.
+struct AttnPlan {
+  int waves, ppw, splits;
+};
+
+static AttnPlan attention_plan(const stc_shape_t& s, int k_pages) {
   const int streams = s.B * s.Hkv;
+  AttnPlan p{8, 2, 0};
 #ifdef STC_TUNE
-  if (const char* e = getenv("STC_ATTN_PPW")) return atoi(e) <= 2 ? 2 : 4;
+  const char* ew = getenv("STC_ATTN_WAVES");
+  const char* ep = getenv("STC_ATTN_PPW");
+  if (ew || ep) {
+    p.waves = ew && atoi(ew) >= 8 ? 8 : 4;
+    p.ppw = ep && atoi(ep) >= 4 ? 4 : 2;
+    p.splits = (k_pages + p.waves * p.ppw - 1) / (p.waves * p.ppw);
+    return p;
+  }
 #endif
-  int ppw = 4;
-  while (ppw > 2 &&
-         (long long)streams * ((k_pages + kAttnWaves * ppw - 1) / (kAttnWaves * ppw)) < 512)
-    ppw >>= 1;
-  while (ppw > 2 && kAttnWaves * (ppw / 2) >= k_pages) ppw >>= 1;  // no idle wavefronts
-  return ppw;
+  if (k_pages <= 8 || (long long)streams * ((k_pages + 15) / 16) < 256) p.waves = 4;
+  p.splits = (k_pages + p.waves * p.ppw - 1) / (p.waves * p.ppw);
+  return p;
 }
 
-int attention_splits(const stc_shape_t& s, int k_pages) {
-  const int per_block = kAttnWaves * attention_ppw(s, k_pages);
-  return (k_pages + per_block - 1) / per_block;
-}
+int attention_splits(const stc_shape_t& s, int k_pages) { return attention_plan(s, k_pages).splits; }
 
 size_t attention_ws_bytes(const stc_shape_t& s, int k_pages) {
   const int splits = attention_splits(s, k_pages);
@@ -511,8 +520,8 @@ int launch_attention(const stc_shape_t& s, const void* q, const void* K, const v
                      int k_pages, float* out, void* ws, hipStream_t st) {
   const int NP = (s.N + kPage - 1) / kPage;
   const int streams = s.B * s.Hkv;
-  const int ppw = attention_ppw(s, k_pages);
-  const int splits = attention_splits(s, k_pages);
+  const AttnPlan plan = attention_plan(s, k_pages);
+  const int splits = plan.splits;
   dim3 grid(splits, streams);
   float* partial = (float*)ws;
 #ifdef STC_TUNE
@@ -526,15 +535,39 @@ int launch_attention(const stc_shape_t& s, const void* q, const void* K, const v
     }
   }
 #endif
-#define STC_ATTN_LAUNCH(DD, PP)                                                                   \
-  attn_mfma_kernel<DD, PP><<<grid, 64 * kAttnWaves, 0, st>>>(                                     \
-      (const uint16_t*)q, (const uint16_t*)K, (const unsigned char*)vpacked, mask, tok_off,       \
-      page_idx, partial, out, s.Hq, s.Hkv, s.N, NP, s.G, (uint32_t)s.v_cap_groups, k_pages, splits)
-  if (s.D == 128) {
-    if (ppw == 2) STC_ATTN_LAUNCH(128, 1); else STC_ATTN_LAUNCH(128, 2);
-  } else {
-    if (ppw == 2) STC_ATTN_LAUNCH(64, 1); else STC_ATTN_LAUNCH(64, 2);
+  // workgroups of 8 wavefronts at D = 128 need more than the default 64 KiB of LDS
+#define STC_ATTN_LAUNCH(DD, PP, WW)                                                               \
+  {                                                                                               \
+    constexpr int lds_bytes = WW * AttnCfg<DD>::WAVE_LDS;                                         \
+    static const hipError_t attr = hipFuncSetAttribute(                                           \
+        (const void*)attn_mfma_kernel<DD, PP, WW>, hipFuncAttributeMaxDynamicSharedMemorySize,    \
+        lds_bytes);                                                                               \
+    if (attr != hipSuccess) return -1;                                                            \
+    attn_mfma_kernel<DD, PP, WW><<<grid, 64 * WW, lds_bytes, st>>>(                               \
+        (const uint16_t*)q, (const uint16_t*)K, (const unsigned char*)vpacked, mask, tok_off,     \
+        page_idx, partial, out, s.Hq, s.Hkv, s.N, NP, s.G, (uint32_t)s.v_cap_groups, k_pages,     \
+        splits);                                                                                  \
   }
+#ifdef STC_TUNE
+#define STC_ATTN_PICK(DD)                                  \
+  if (plan.waves == 8) {                                   \
+    if (plan.ppw == 2) STC_ATTN_LAUNCH(DD, 1, 8)           \
+    else STC_ATTN_LAUNCH(DD, 2, 8)                         \
+  } else {                                                 \
+    if (plan.ppw == 2) STC_ATTN_LAUNCH(DD, 1, 4)           \
+    else STC_ATTN_LAUNCH(DD, 2, 4)                         \
+  }
+#else
+#define STC_ATTN_PICK(DD)                                  \
+  if (plan.waves == 8) STC_ATTN_LAUNCH(DD, 1, 8)           \
+  else STC_ATTN_LAUNCH(DD, 1, 4)
+#endif
+  if (s.D == 128) {
+    STC_ATTN_PICK(128)
+  } else {
+    STC_ATTN_PICK(64)
+  }
+#undef STC_ATTN_PICK
 #undef STC_ATTN_LAUNCH
   if (hipGetLastError() != hipSuccess) return -1;
   if (splits > 1) {
