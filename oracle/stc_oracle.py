@@ -15,6 +15,11 @@ What each routine follows (paper = "Sub-Token Routing for KV Cache Compression")
                     a token give a binary mask m[i,j]; App. B.1 gives the fixed
                     per-token K used for VLMs.  Here the count may differ per
                     token (Sec. 3.4 allows K_i to vary by token).
+  route_mask_global Sec. 3.4 "global token-group budget" and App. B.1: for a
+                    retained sequence of N tokens and nominal budget K the
+                    router keeps the M = N*K token-group pairs of largest logit
+                    over the whole N x S grid, so the kept count varies by
+                    token (0..S).
   token_offsets,    the group-packed store: an encoding of the routed value
   pack_values       vector of Sec. 3.3 (tilde v = m * v per group) that stores
                     kept groups only.
@@ -127,6 +132,27 @@ def route_mask(logits, kcount):
                 wins = wins | (a[:, g2] == a[:, g])
             ahead += wins
         mask |= ((ahead < c).astype(np.uint16) << np.uint16(g))
+    return mask
+
+
+def route_mask_global(logits, budget):
+    """logits[N, G] float32, budget M (0..N*G) -> mask[N] uint16.
+
+    The M token-group pairs of largest logit over the whole grid are kept (paper:
+    M = N*K).  Equal logits (IEEE comparison, so -0 == +0) are ranked by
+    ascending (token, group), i.e. by flat index t*G + g.
+    """
+    a = np.asarray(logits, dtype=np.float32)
+    N, G = a.shape
+    M = int(budget)
+    if not 0 <= M <= N * G:
+        raise ValueError("budget out of range")
+    flat = a.reshape(-1)
+    # primary key: logit descending; secondary: flat index ascending
+    order = np.lexsort((np.arange(N * G), -flat.astype(np.float64)))
+    keep = order[:M]
+    mask = np.zeros(N, dtype=np.uint16)
+    np.bitwise_or.at(mask, keep // G, (1 << (keep % G)).astype(np.uint16))
     return mask
 
 
@@ -253,10 +279,11 @@ def build_page_bounds_all(K_bits, P=16):
     return out
 
 
-def route_and_pack_all(V_bits, G, logits=None, kcount=None, mask_in=None):
+def route_and_pack_all(V_bits, G, logits=None, kcount=None, mask_in=None, global_k=None):
     """V_bits[B, Hkv, N, D] plus either (logits[B,Hkv,N,G], kcount[B,Hkv,N] or
-    scalar) or mask_in[B,Hkv,N] -> (mask, tok_off[B,Hkv,N+1], list of packed
-    arrays per stream in (b, h) order)."""
+    scalar), or (logits, global_k: per-stream budget N*global_k), or
+    mask_in[B,Hkv,N] -> (mask, tok_off[B,Hkv,N+1], list of packed arrays per
+    stream in (b, h) order)."""
     B, Hkv, N, D = V_bits.shape
     mask = np.zeros((B, Hkv, N), dtype=np.uint16)
     off = np.zeros((B, Hkv, N + 1), dtype=np.uint32)
@@ -265,6 +292,8 @@ def route_and_pack_all(V_bits, G, logits=None, kcount=None, mask_in=None):
         for h in range(Hkv):
             if mask_in is not None:
                 m = np.asarray(mask_in[b, h], dtype=np.uint16) & np.uint16((1 << G) - 1)
+            elif global_k is not None:
+                m = route_mask_global(logits[b, h], N * int(global_k))
             else:
                 kc = kcount if np.isscalar(kcount) else kcount[b, h]
                 m = route_mask(logits[b, h], kc)

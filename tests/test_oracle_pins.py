@@ -417,3 +417,79 @@ def test_route_and_pack_all_modes_agree():
     assert np.array_equal(m1, m2) and np.array_equal(o1, o2)
     assert all(np.array_equal(a, b) for a, b in zip(p1, p2))
     assert np.array_equal(o1[..., -1], np.array(kc, dtype=np.int64).sum(axis=-1))
+
+
+# --- global token-group budget (Sec. 3.4; App. B.1: M = N*K of the N x S pairs) -----------
+
+def test_global_budget_brute_force_with_ties():
+    """Plain Python: rank every (token, group) pair by (logit descending, flat index
+    ascending) and keep the first M; logits drawn from few values so ties are everywhere,
+    including -0 against +0."""
+    rng = np.random.default_rng(50)
+    for N, G, M in ((7, 4, 9), (5, 8, 17), (9, 2, 0), (3, 16, 48), (6, 4, 1)):
+        a = rng.choice(np.array([-1.5, -0.0, 0.0, 0.25, 2.0], dtype=np.float32), size=(N, G))
+        pairs = [(t, g) for t in range(N) for g in range(G)]
+        ranked = sorted(pairs, key=lambda tg: (-float(a[tg]), tg[0] * G + tg[1]))
+        want = np.zeros(N, dtype=np.uint16)
+        for (t, g) in ranked[:M]:
+            want[t] |= np.uint16(1 << g)
+        got = O.route_mask_global(a, M)
+        assert np.array_equal(got, want)
+        assert int(O.popcount(got, G).sum()) == M
+
+
+def test_global_budget_keeps_exactly_m_above_a_threshold():
+    rng = np.random.default_rng(51)
+    N, G, K = 500, 8, 3
+    a = rng.standard_normal((N, G)).astype(np.float32)
+    m = O.route_mask_global(a, N * K)
+    bits = (m[:, None] >> np.arange(G)) & 1
+    assert int(bits.sum()) == N * K                       # the budget is met exactly
+    assert a[bits == 1].min() > a[bits == 0].max()         # no ties here: a clean threshold
+    assert np.array_equal(O.route_mask_global(a, 0), np.zeros(N, dtype=np.uint16))
+    assert np.array_equal(O.route_mask_global(a, N * G), np.full(N, (1 << G) - 1, dtype=np.uint16))
+    with pytest.raises(ValueError):
+        O.route_mask_global(a, N * G + 1)
+
+
+def test_global_budget_equals_per_token_topk_when_tokens_share_one_value_set():
+    """Every token's logits are a permutation of the same G distinct values, so the N*K
+    largest pairs of the grid are exactly every token's own top K (App. B.1's fixed-K mode)."""
+    rng = np.random.default_rng(52)
+    N, G = 64, 8
+    vals = np.arange(G, dtype=np.float32) * 0.5 - 1.0
+    a = np.stack([rng.permutation(vals) for _ in range(N)])
+    for K in (1, 3, 8):
+        assert np.array_equal(O.route_mask_global(a, N * K), O.route_mask(a, K))
+
+
+def test_global_budget_all_equal_logits_fill_in_token_order():
+    N, G, M = 10, 4, 14
+    m = O.route_mask_global(np.zeros((N, G), dtype=np.float32), M)
+    assert list(m[:5]) == [15, 15, 15, 3, 0] and not m[5:].any()
+
+
+def test_global_budget_allocation_is_non_uniform_as_in_the_diagnostic_figure():
+    """Fig. 1 caption: S = 4, average budget 1.0 per token; some tokens get no group, some
+    all four, many a partial allocation.  For iid continuous logits the threshold sits at
+    the 3/4 quantile, so P(no group) -> (3/4)^4 and P(all four) -> (1/4)^4."""
+    rng = np.random.default_rng(53)
+    N, S = 40000, 4
+    a = rng.standard_normal((N, S)).astype(np.float32)
+    kept = O.popcount(O.route_mask_global(a, N * 1), S)
+    assert kept.sum() == N and kept.mean() == 1.0
+    assert abs((kept == 0).mean() - 0.75 ** 4) < 0.01
+    assert abs((kept == 4).mean() - 0.25 ** 4) < 0.002
+    assert (kept == 1).any() and (kept == 2).any() and (kept == 3).any()
+
+
+def test_route_and_pack_all_global_mode():
+    rng = np.random.default_rng(54)
+    B, Hkv, N, D, G = 2, 2, 40, 64, 4
+    V = randn_bf16(rng, (B, Hkv, N, D))
+    logits = rng.standard_normal((B, Hkv, N, G)).astype(np.float32)
+    mask, off, packed = O.route_and_pack_all(V, G, logits=logits, global_k=2)
+    for b in range(B):
+        for h in range(Hkv):
+            assert np.array_equal(mask[b, h], O.route_mask_global(logits[b, h], 2 * N))
+            assert int(off[b, h, -1]) == 2 * N == packed[b * Hkv + h].shape[0]
