@@ -65,7 +65,8 @@ enum { STC_WS_ROUTE = 1, STC_WS_SELECT = 2, STC_WS_ATTENTION = 3 };
 /* routing modes of stc_route_and_pack_values */
 enum {
   STC_ROUTE_MASK = 0, /* mask_in gives the kept groups (bits >= G are ignored) */
-  STC_ROUTE_TOPK = 1  /* top-k of `logits` per token; count from kcount[] or fixed_k */
+  STC_ROUTE_TOPK = 1, /* top-k of `logits` per token; count from kcount[] or fixed_k */
+  STC_ROUTE_GLOBAL = 2 /* the N*fixed_k largest of a stream's N*G logits */
 };
 
 int stc_version(void);
@@ -100,8 +101,12 @@ size_t stc_bounds_bytes(const stc_shape_t *shape);
  *        largest of logits[t, 0..G) (equal logits: lower g first), where
  *        c_t = kcount[t] (clamped to G) if kcount != NULL, else fixed_k (0..G).
  *   mode STC_ROUTE_MASK: mask[t] = mask_in[t] & ((1<<G)-1).
+ *   mode STC_ROUTE_GLOBAL (global token-group budget, Sec. 3.4 and App. B.1): per stream the
+ *        M = N*fixed_k token-group pairs of largest logit over the whole [N, G] grid are
+ *        kept (fixed_k in 0..G; equal logits, -0 == +0: lower t*G+g first), so a token keeps
+ *        anything from 0 to G groups.  kcount is ignored.
  *   V       [B, Hkv, N, D] bf16, in
- *   logits  [B, Hkv, N, G] float, in (TOPK only)
+ *   logits  [B, Hkv, N, G] float, in (TOPK and GLOBAL)
  *   kcount  [B, Hkv, N] uint8, in (TOPK, may be NULL)
  *   mask_in [B, Hkv, N] uint16, in (MASK only)
  *   mask    [B, Hkv, N] uint16, out (may alias mask_in)

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libstc.so")
 STC_OK = 0
 STC_ERR_NULL, STC_ERR_SHAPE, STC_ERR_ALIGN, STC_ERR_WORKSPACE, STC_ERR_LAUNCH = -1, -2, -3, -4, -5
 STC_WS_ROUTE, STC_WS_SELECT, STC_WS_ATTENTION = 1, 2, 3
-STC_ROUTE_MASK, STC_ROUTE_TOPK = 0, 1
+STC_ROUTE_MASK, STC_ROUTE_TOPK, STC_ROUTE_GLOBAL = 0, 1, 2
 
 EXPORTS = ["stc_version", "stc_status_string", "stc_workspace_bytes", "stc_bounds_bytes",
            "stc_build_page_bounds",
@@ -224,11 +224,15 @@ class RoutedCache:
         n = stc_workspace_bytes(self.shape, which, k)
         return torch.empty(max(n, 16), dtype=torch.uint8, device=self.device)
 
-    def build(self, K, V, logits=None, kcount=None, fixed_k=0, mask_in=None):
-        """Cache construction: page bounds of K, routing mask + packed store of V."""
+    def build(self, K, V, logits=None, kcount=None, fixed_k=0, mask_in=None, global_k=None):
+        """Cache construction: page bounds of K, routing mask + packed store of V.  The mask
+        comes from mask_in, from a global budget of N*global_k token-group pairs per stream,
+        or from the per-token top kcount[t] / fixed_k of the logits."""
         self.K = K
         stc_build_page_bounds(self.shape, K, self.bounds)
         mode = STC_ROUTE_MASK if mask_in is not None else STC_ROUTE_TOPK
+        if global_k is not None:
+            mode, fixed_k, kcount = STC_ROUTE_GLOBAL, int(global_k), None
         stc_route_and_pack_values(self.shape, mode, V, logits, kcount, fixed_k, mask_in, self.mask,
                                   self.tok_off, self.vpacked, self.dev_status, self._ws_route)
 

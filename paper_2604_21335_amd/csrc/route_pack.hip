@@ -1,6 +1,7 @@
 // Sub-token value-group routing at cache-build time (paper Sec. 3.3): top-k
-// routing mask per token, per-token offsets into the group-packed store, and
-// the packed copy of the kept value groups.
+// routing mask per token (or, for the LLM setting of Sec. 3.4 / App. B.1, the N*K
+// best token-group pairs of the whole stream), per-token offsets into the
+// group-packed store, and the packed copy of the kept value groups.
 #include "stc_common.hpp"
 #include "stc_kernels.hpp"
 
@@ -72,6 +73,123 @@ __global__ __launch_bounds__(kChunk) void route_mask_kernel(
   }
   const int tot = block_sum_256(__popc(m), red);
   if (threadIdx.x == 0) chunk_sum[(size_t)stream * nchunks + blockIdx.x] = (uint32_t)tot;
+}
+
+// ---------------------------------------------------------------------------
+// Global token-group budget (Sec. 3.4; App. B.1: M = N*K of the N x S pairs): one
+// 1024-thread workgroup per stream finds the key of the M-th largest logit by a radix
+// select over the stream's N*G logits (12 + 10 + 10 bits; the wide first digit spreads
+// logits that share sign and exponent over many bins), then walks the tokens in order and
+// keeps every pair above that key plus the first `remaining` pairs equal to it.
+// ---------------------------------------------------------------------------
+constexpr int kGlobalThreads = 1024;
+constexpr int kGlobalBins = 4096;
+
+// Order-preserving key of a finite float with -0 and +0 mapped to one key.
+__device__ __forceinline__ uint32_t logit_key(float f) {
+  uint32_t u = __float_as_uint(f);
+  if (u == 0x80000000u) u = 0u;
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Exclusive prefix sum over a 1024-thread block (thread order); *total = block sum.
+__device__ __forceinline__ uint32_t block_exscan_1024(uint32_t v, uint32_t* lds16,
+                                                      uint32_t* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t inc = v;
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t o = __shfl_up(inc, d);
+    if (lane >= d) inc += o;
+  }
+  if (lane == 63) lds16[wave] = inc;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+  for (int w = 0; w < kGlobalThreads / 64; ++w) {
+    if (w < wave) base += lds16[w];
+    tot += lds16[w];
+  }
+  *total = tot;
+  __syncthreads();
+  return base + inc - v;
+}
+
+__global__ __launch_bounds__(kGlobalThreads) void route_global_kernel(
+    const float* __restrict__ logits, uint16_t* __restrict__ mask, int N, int G,
+    uint32_t budget) {
+  __shared__ uint32_t hist[kGlobalBins];
+  __shared__ uint32_t waves[kGlobalThreads / 64];
+  __shared__ uint32_t s_prefix, s_remaining;
+  const int stream = blockIdx.x;
+  const int tid = threadIdx.x;
+  const uint32_t n = (uint32_t)N * (uint32_t)G;
+  const float* a = logits + (size_t)stream * n;
+  uint16_t* mk = mask + (size_t)stream * N;
+
+  uint32_t prefix = 0, decided = 0, remaining = budget;
+  if (budget > 0) {
+    // digits from the top: bits 31..20, 19..10, 9..0
+    for (int pass = 0; pass < 3; ++pass) {
+      const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
+      const uint32_t bins = pass == 0 ? 4096u : 1024u;
+      for (uint32_t i = tid; i < kGlobalBins; i += kGlobalThreads) hist[i] = 0;
+      __syncthreads();
+      for (uint32_t i = tid; i < n; i += kGlobalThreads) {
+        const uint32_t key = logit_key(a[i]);
+        if ((key & decided) == prefix) atomicAdd(&hist[(key >> shift) & (bins - 1)], 1u);
+      }
+      __syncthreads();
+      // thread t owns the 4 adjacent digits 4095-4t .. 4092-4t (descending order)
+      uint32_t c[4], own = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t d = kGlobalBins - 1 - (4 * tid + j);
+        c[j] = d < bins ? hist[d] : 0u;
+        own += c[j];
+      }
+      uint32_t tot;
+      uint32_t above = block_exscan_1024(own, waves, &tot);  // pairs with a larger digit
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (above < remaining && remaining <= above + c[j]) {
+          s_prefix = prefix | ((uint32_t)(kGlobalBins - 1 - (4 * tid + j)) << shift);
+          s_remaining = remaining - above;
+        }
+        above += c[j];
+      }
+      __syncthreads();
+      prefix = s_prefix;
+      remaining = s_remaining;
+      decided |= (bins - 1) << shift;
+      __syncthreads();
+    }
+  }
+  // prefix = key of the budget-th largest logit; `remaining` of the pairs equal to it are
+  // kept, lowest (token, group) first.  budget == 0 keeps nothing.
+  uint32_t carry = 0;  // pairs equal to the key in earlier tiles
+  for (int t0 = 0; t0 < N; t0 += kGlobalThreads) {
+    const int t = t0 + tid;
+    uint32_t key[16];
+    uint32_t eq = 0;
+#pragma unroll
+    for (int g = 0; g < 16; ++g) {
+      key[g] = (g < G && t < N) ? logit_key(a[(size_t)t * G + g]) : 0u;
+      eq += (g < G && t < N && budget > 0) && key[g] == prefix;
+    }
+    uint32_t tot;
+    uint32_t e = carry + block_exscan_1024(eq, waves, &tot);
+    uint32_t m = 0;
+    if (budget > 0) {
+#pragma unroll
+      for (int g = 0; g < 16; ++g) {
+        if (g < G && t < N) {
+          if (key[g] > prefix) m |= 1u << g;
+          else if (key[g] == prefix && e++ < remaining) m |= 1u << g;
+        }
+      }
+    }
+    if (t < N) mk[t] = (uint16_t)m;
+    carry += tot;
+  }
 }
 
 // Step 2: per stream, exclusive scan of the chunk sums (in place); writes the
@@ -171,6 +289,14 @@ int launch_route_pack(const stc_shape_t& s, int mode, const void* V, const float
   const int nchunks = (s.N + kChunk - 1) / kChunk;
   uint32_t* chunk = (uint32_t*)ws;
   dim3 grid(nchunks, streams);
+  if (mode == STC_ROUTE_GLOBAL) {
+    // the mask of the whole stream first, then the common path with that mask as given
+    route_global_kernel<<<streams, kGlobalThreads, 0, st>>>(
+        logits, mask, s.N, s.G, (uint32_t)((long long)s.N * fixed_k));
+    if (hipGetLastError() != hipSuccess) return -1;
+    mode = STC_ROUTE_MASK;
+    mask_in = mask;
+  }
   route_mask_kernel<<<grid, kChunk, 0, st>>>(mode, logits, kcount, fixed_k, mask_in, mask, chunk,
                                              s.N, s.G, nchunks);
   if (hipGetLastError() != hipSuccess) return -1;

@@ -82,6 +82,9 @@ int stc_route_and_pack_values(const stc_shape_t* shape, int mode, const void* V,
   if (mode == STC_ROUTE_TOPK) {
     if (!logits) return STC_ERR_NULL;
     if (!kcount && (fixed_k < 0 || fixed_k > shape->G)) return STC_ERR_SHAPE;
+  } else if (mode == STC_ROUTE_GLOBAL) {
+    if (!logits) return STC_ERR_NULL;
+    if (fixed_k < 0 || fixed_k > shape->G) return STC_ERR_SHAPE;
   } else if (mode == STC_ROUTE_MASK) {
     if (!mask_in) return STC_ERR_NULL;
   } else {

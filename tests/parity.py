@@ -27,7 +27,7 @@ def host_bf16(t):
 
 
 def run_hip(K, V, q, G, k_pages, logits=None, kcount=None, fixed_k=0, mask_in=None, cap=None,
-            dev="cuda:0"):
+            dev="cuda:0", global_k=None):
     """All inputs are host numpy arrays (bf16 as uint16 bits).  Returns host outputs."""
     B, Hkv, N, D = K.shape
     Hq = q.shape[1]
@@ -39,7 +39,7 @@ def run_hip(K, V, q, G, k_pages, logits=None, kcount=None, fixed_k=0, mask_in=No
             kcount=None if kcount is None or np.isscalar(kcount) else torch.from_numpy(
                 np.ascontiguousarray(kcount, dtype=np.uint8)).to(dev),
             fixed_k=int(kcount) if np.isscalar(kcount) and kcount is not None else fixed_k,
-            mask_in=None if mask_in is None else to_dev_u16(mask_in, dev))
+            mask_in=None if mask_in is None else to_dev_u16(mask_in, dev), global_k=global_k)
     c.page_score.fill_(float("nan"))
     c.step(dq)
     torch.cuda.synchronize()
@@ -51,7 +51,8 @@ def run_hip(K, V, q, G, k_pages, logits=None, kcount=None, fixed_k=0, mask_in=No
     }
 
 
-def run_oracle(K, V, q, G, k_pages, logits=None, kcount=None, mask_in=None, streams=None):
+def run_oracle(K, V, q, G, k_pages, logits=None, kcount=None, mask_in=None, streams=None,
+               global_k=None):
     """Oracle on every stream, or on the listed (b, h) streams only."""
     B, Hkv, N, D = K.shape
     Hq = q.shape[1]
@@ -62,6 +63,8 @@ def run_oracle(K, V, q, G, k_pages, logits=None, kcount=None, mask_in=None, stre
         bounds = O.page_bounds(K[b, h])
         if mask_in is not None:
             m = np.asarray(mask_in[b, h], dtype=np.uint16) & np.uint16((1 << G) - 1)
+        elif global_k is not None:
+            m = O.route_mask_global(logits[b, h], N * int(global_k))
         else:
             kc = kcount if np.isscalar(kcount) else kcount[b, h]
             m = O.route_mask(logits[b, h], kc)

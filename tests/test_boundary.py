@@ -68,6 +68,9 @@ def test_null_alignment_and_workspace_errors():
     assert args(stc.STC_ROUTE_TOPK, FAKE, None, 9, None, FAKE, big) == stc.STC_ERR_SHAPE
     assert args(stc.STC_ROUTE_TOPK, FAKE, None, -1, None, FAKE, big) == stc.STC_ERR_SHAPE
     assert args(7, FAKE, None, 2, FAKE, FAKE, big) == stc.STC_ERR_SHAPE
+    assert args(stc.STC_ROUTE_GLOBAL, None, None, 2, None, FAKE, big) == stc.STC_ERR_NULL
+    assert args(stc.STC_ROUTE_GLOBAL, FAKE, None, 9, None, FAKE, big) == stc.STC_ERR_SHAPE
+    assert args(stc.STC_ROUTE_GLOBAL, FAKE, None, 2, None, FAKE, 0) == stc.STC_ERR_WORKSPACE
     assert args(stc.STC_ROUTE_TOPK, FAKE, None, 2, None, FAKE, 0) == stc.STC_ERR_WORKSPACE
     assert args(stc.STC_ROUTE_TOPK, FAKE, None, 2, None, None, big) == stc.STC_ERR_WORKSPACE
     # select: k out of range, scores need a workspace when page_score is NULL

@@ -119,6 +119,39 @@ def test_scores_for_every_head_group_size(Hq, Hkv, D):
         assert not last[:, :, pt // 4, :, pt % 4].any()
 
 
+@pytest.mark.parametrize("N,G,D,gk", [(1000, 8, 128, 3), (2500, 4, 64, 1), (777, 16, 128, 5),
+                                      (4096, 8, 128, 0), (300, 4, 64, 4), (1024, 1, 64, 1)])
+def test_global_budget_routing(N, G, D, gk):
+    """Global token-group budget: masks (tokens with no group included), offsets and packed
+    values bit for bit; exactly N*K groups kept; attention over the result within the bar."""
+    B, Hq, Hkv = 2, 4, 2
+    K, V, q, logits, _ = _rand_case(60 + N % 7, B, Hq, Hkv, D, N, G)
+    hip = PT.run_hip(K, V, q, G, 12, logits=logits, global_k=gk)
+    ora = PT.run_oracle(K, V, q, G, 12, logits=logits, global_k=gk)
+    assert hip["dev_status"] == 0
+    assert (hip["tok_off"][:, :, -1] == N * gk).all()
+    err = PT.compare(hip, ora, Hq, Hkv)
+    assert err < PT.TIGHT
+    if 0 < gk < G and G > 1:
+        kept = O.popcount(hip["mask"], G)
+        assert kept.min() == 0 or kept.max() > gk          # allocation is not uniform
+
+
+def test_global_budget_routing_with_ties_everywhere():
+    """Logits drawn from five values (with -0 and +0): the cut falls inside a run of equal
+    logits spanning many tokens and several 1024-token tiles."""
+    rng = np.random.default_rng(71)
+    B, Hq, Hkv, D, N, G = 1, 2, 2, 64, 3000, 4
+    K, V, q, _, _ = _rand_case(72, B, Hq, Hkv, D, N, G)
+    logits = rng.choice(np.array([-1.5, -0.0, 0.0, 0.25, 2.0], dtype=np.float32),
+                        size=(B, Hkv, N, G))
+    for gk in (1, 2, 3):
+        hip = PT.run_hip(K, V, q, G, 10, logits=logits, global_k=gk)
+        ora = PT.run_oracle(K, V, q, G, 10, logits=logits, global_k=gk)
+        PT.compare(hip, ora, Hq, Hkv)
+        assert (hip["tok_off"][:, :, -1] == N * gk).all()
+
+
 def test_score_pages_alone_matches_oracle_bits():
     B, Hq, Hkv, D, N, G = 2, 14, 2, 128, 3000, 8
     K, V, q, logits, kcount = _rand_case(21, B, Hq, Hkv, D, N, G, outliers=True)
@@ -300,6 +333,39 @@ def test_workload_full_size_sampled_streams(name):
     streams = sorted({(0, 0), (w.B - 1, w.Hkv - 1), (w.B // 2, w.Hkv // 3)})
     worst = _check_streams(w, c, t, streams)
     assert worst <= PT.TIGHT
+
+
+def test_global_budget_at_full_llm_size():
+    """The LLM-mode routing of the paper (budget N*K over the whole stream, K = 4 of 8) on
+    the headline shape: exact budget on every stream, masks of sampled streams bit for bit,
+    and the decode step over the resulting cache within the bar."""
+    w = W.WORKLOADS["qwen25_7b_32k"]
+    inp = W.make_cache_inputs(w, "cuda:0", 0)
+    c = stc.RoutedCache(w.B, w.Hq, w.Hkv, w.D, w.N, w.G, w.k_pages, device="cuda:0")
+    c.build(inp["K"], inp["V"], logits=inp["logits"], global_k=4)
+    q = W.make_query(w, 0, "cuda:0")
+    c.step(q)
+    torch.cuda.synchronize()
+    assert int(c.dev_status.item()) == 0
+    tot = c.tok_off[..., -1].cpu().numpy().view(np.uint32)
+    assert (tot == w.N * 4).all()
+    qb = W.bf16_bits(q)
+    for (b, h) in [(0, 0), (w.B - 1, w.Hkv - 1)]:
+        m = O.route_mask_global(inp["logits"][b, h].cpu().numpy(), w.N * 4)
+        assert np.array_equal(PT.host_u16(c.mask[b, h]), m)
+        kept = O.popcount(m, w.G)
+        assert kept.min() == 0 and kept.max() == w.G         # non-uniform allocation
+        K, V = W.bf16_bits(inp["K"][b, h]), W.bf16_bits(inp["V"][b, h])
+        off = O.token_offsets(m, w.G)
+        assert np.array_equal(c.tok_off[b, h].cpu().numpy().view(np.uint32), off)
+        assert np.array_equal(W.bf16_bits(c.vpacked[b, h, :int(off[-1])]),
+                              O.pack_values(V, m, off, w.G))
+        qh = qb[b, h * w.R:(h + 1) * w.R]
+        idx = O.select_pages(O.page_scores(qh, O.page_bounds(K)), w.k_pages)
+        assert np.array_equal(c.page_idx[b, h].cpu().numpy(), idx)
+        want = O.decode_attention(qh, K, V, m, idx, w.G)
+        got = c.out[b, h * w.R:(h + 1) * w.R].cpu().numpy()
+        assert np.abs(got - want).max() <= PT.TIGHT
 
 
 def test_steps_are_deterministic():
