@@ -27,7 +27,9 @@ What each routine follows (paper = "Sub-Token Routing for KV Cache Compression")
   select_pages      q_c*max_c) and its top-k pages.
   decode_attention  Sec. 3.3 attention equation: softmax(q K^T / sqrt(d_h))
                     applied to the routed (zero-filled) value matrix; softmax
-                    uses q and K only, dropped groups contribute nothing.
+                    uses q and K only, dropped groups contribute nothing.  An
+                    optional tail of recent tokens is attended uncompressed
+                    (Sec. 3.4: query-region tokens are not compressed).
   rho_total         Sec. 3.3 "Compression ratio" and App. C.2:
                     rho_total = r * (1 + K/S) / 2.
 
@@ -235,10 +237,13 @@ def select_pages(score, k):
 # --------------------------------------------------------------------------- #
 # Routed attention (Sec. 3.3 attention equation)
 # --------------------------------------------------------------------------- #
-def decode_attention(q_bits, K_bits, V_bits, mask, page_idx, G, P=16):
+def decode_attention(q_bits, K_bits, V_bits, mask, page_idx, G, P=16, K_tail=None, V_tail=None):
     """q_bits[R, D]; K_bits, V_bits [N, D]; mask[N]; page_idx ascending or not.
 
-    Tokens attended: every t < N of every listed page.  Returns float32 [R, D].
+    Tokens attended: every t < N of every listed page, and, when a tail is given
+    (K_tail, V_tail [n_tail, D]), every tail token with its full value vector: the
+    recent tokens that the paper leaves uncompressed (Sec. 3.4: query-region tokens are
+    not compressed).  One softmax runs over both sets.  Returns float32 [R, D].
     """
     q = bf16_to_f32(q_bits).astype(np.float64)
     N, D = np.asarray(K_bits).shape
@@ -251,8 +256,12 @@ def decode_attention(q_bits, K_bits, V_bits, mask, page_idx, G, P=16):
     Kt = bf16_to_f32(np.asarray(K_bits)[toks]).astype(np.float64)      # [T, D]
     Vt = bf16_to_f32(np.asarray(V_bits)[toks]).astype(np.float64)      # [T, D]
     mt = np.asarray(mask)[toks].astype(np.int64)
+    if K_tail is not None and len(K_tail):
+        Kt = np.concatenate([Kt, bf16_to_f32(np.asarray(K_tail)).astype(np.float64)])
+        Vt = np.concatenate([Vt, bf16_to_f32(np.asarray(V_tail)).astype(np.float64)])
+        mt = np.concatenate([mt, np.full(len(K_tail), (1 << G) - 1, dtype=np.int64)])
     # routed (zero-filled) values: tilde v = m * v per group
-    keep = np.zeros((len(toks), D), dtype=np.float64)
+    keep = np.zeros((len(mt), D), dtype=np.float64)
     for g in range(G):
         keep[:, g * gd:(g + 1) * gd] = ((mt >> g) & 1)[:, None]
     Vr = Vt * keep
@@ -319,8 +328,10 @@ def select_pages_all(q_bits, bounds_bits, k):
     return idx, score
 
 
-def decode_attention_all(q_bits, K_bits, V_bits, mask, page_idx, G, P=16):
-    """-> out[B, Hq, D] float32; query head j belongs to KV head j // (Hq/Hkv)."""
+def decode_attention_all(q_bits, K_bits, V_bits, mask, page_idx, G, P=16, K_tail=None,
+                         V_tail=None):
+    """-> out[B, Hq, D] float32; query head j belongs to KV head j // (Hq/Hkv).
+    K_tail, V_tail [B, Hkv, n_tail, D]: uncompressed recent tokens, always attended."""
     B, Hq, D = q_bits.shape
     Hkv = K_bits.shape[1]
     R = Hq // Hkv
@@ -329,5 +340,6 @@ def decode_attention_all(q_bits, K_bits, V_bits, mask, page_idx, G, P=16):
         for h in range(Hkv):
             out[b, h * R:(h + 1) * R] = decode_attention(
                 q_bits[b, h * R:(h + 1) * R], K_bits[b, h], V_bits[b, h],
-                mask[b, h], page_idx[b, h], G, P)
+                mask[b, h], page_idx[b, h], G, P,
+                None if K_tail is None else K_tail[b, h], None if V_tail is None else V_tail[b, h])
     return out

@@ -493,3 +493,57 @@ def test_route_and_pack_all_global_mode():
         for h in range(Hkv):
             assert np.array_equal(mask[b, h], O.route_mask_global(logits[b, h], 2 * N))
             assert int(off[b, h, -1]) == 2 * N == packed[b * Hkv + h].shape[0]
+
+
+# --- uncompressed recent tail (Sec. 3.4: query-region tokens are not compressed) ----------
+
+def test_attention_with_tail_is_dense_attention_over_both_sets():
+    """Definition written out: one softmax over the selected cached tokens (routed values)
+    and every tail token (full values), against numpy float64 and torch SDPA float64."""
+    import torch
+    rng = np.random.default_rng(60)
+    N, D, G, R, nt = 96, 64, 4, 3, 21
+    gd = D // G
+    K, V = randn_bf16(rng, (N, D)), randn_bf16(rng, (N, D))
+    Kt, Vt = randn_bf16(rng, (nt, D)), randn_bf16(rng, (nt, D))
+    q = randn_bf16(rng, (R, D))
+    mask = rng.integers(0, 1 << G, size=N).astype(np.uint16)
+    pages = [1, 4, 5]
+    got = O.decode_attention(q, K, V, mask, pages, G, K_tail=Kt, V_tail=Vt)
+    toks = np.concatenate([np.arange(p * 16, p * 16 + 16) for p in pages])
+    keep = np.repeat((mask[toks, None] >> np.arange(G)) & 1, gd, axis=1)
+    Kall = np.concatenate([bits_to_f64(K)[toks], bits_to_f64(Kt)])
+    Vall = np.concatenate([bits_to_f64(V)[toks] * keep, bits_to_f64(Vt)])
+    s = bits_to_f64(q) @ Kall.T / math.sqrt(D)
+    w = np.exp(s - s.max(axis=1, keepdims=True))
+    want = (w / w.sum(axis=1, keepdims=True)) @ Vall
+    assert np.abs(got - want).max() < 1e-6
+    sd = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(bits_to_f64(q))[None], torch.from_numpy(Kall)[None],
+        torch.from_numpy(Vall)[None]).numpy()[0]
+    assert np.abs(got - sd).max() < 1e-6
+
+
+def test_attention_tail_special_cases():
+    rng = np.random.default_rng(61)
+    N, D, G, R = 64, 64, 4, 2
+    K, V = randn_bf16(rng, (N, D)), randn_bf16(rng, (N, D))
+    q = randn_bf16(rng, (R, D))
+    mask = rng.integers(0, 1 << G, size=N).astype(np.uint16)
+    base = O.decode_attention(q, K, V, mask, [0, 2], G)
+    # an empty tail changes nothing
+    empty = np.zeros((0, D), dtype=np.uint16)
+    assert np.array_equal(O.decode_attention(q, K, V, mask, [0, 2], G, K_tail=empty, V_tail=empty),
+                          base)
+    # moving a fully kept page from the cache into the tail gives the same output
+    full = mask.copy()
+    full[48:64] = (1 << G) - 1
+    a = O.decode_attention(q, K, V, full, [0, 2, 3], G)
+    b = O.decode_attention(q, K, V, full, [0, 2], G, K_tail=K[48:64], V_tail=V[48:64])
+    assert np.abs(a - b).max() < 1e-6
+    # a tail token whose key matches the query dominates: the output is its full value row
+    Kt = f32_to_bf16_bits(bits_to_f64(q[:1]).astype(np.float32) * 6.0)
+    Vt = ints_bf16(rng, (1, D), -8, 9)
+    o = O.decode_attention(q[:1], K, V, np.zeros(N, dtype=np.uint16), [0, 1, 2, 3], G,
+                           K_tail=Kt, V_tail=Vt)
+    assert np.abs(o[0] - bits_to_f64(Vt)[0]).max() < 1e-3
