@@ -60,7 +60,7 @@ enum {
 };
 
 /* which_call values for stc_workspace_bytes */
-enum { STC_WS_ROUTE = 1, STC_WS_SELECT = 2, STC_WS_ATTENTION = 3 };
+enum { STC_WS_ROUTE = 1, STC_WS_SELECT = 2, STC_WS_ATTENTION = 3, STC_WS_ATTENTION_TAIL = 4 };
 
 /* routing modes of stc_route_and_pack_values */
 enum {
@@ -73,7 +73,8 @@ int stc_version(void);
 const char *stc_status_string(int status);
 
 /* Bytes of device workspace the given call needs for this shape (0 = none).
- * k_pages is only used by STC_WS_SELECT / STC_WS_ATTENTION.  Returns 0 for an
+ * k_pages is only used by STC_WS_SELECT / STC_WS_ATTENTION / STC_WS_ATTENTION_TAIL (for the
+ * last one it is the number of selected pages plus ceil(n_tail / P), at their largest).  Returns 0 for an
  * invalid shape (the call itself then reports the error). */
 size_t stc_workspace_bytes(const stc_shape_t *shape, int which_call, int k_pages);
 
@@ -178,6 +179,32 @@ int stc_decode_attention(const stc_shape_t *shape, const void *q, const void *K,
                          const void *vpacked, const uint16_t *mask, const uint32_t *tok_off,
                          const int32_t *page_idx, int k_pages, float *out, void *ws,
                          size_t ws_bytes, void *stream);
+
+/*
+ * Routed decode attention with an uncompressed tail of recent tokens: the tokens generated
+ * since the cache was built (the paper leaves query-region tokens uncompressed, Sec. 3.4)
+ * are kept with full-width values in a small dense store and are always attended, next to
+ * the selected pages of the compressed cache, under one softmax.  Everything else as
+ * stc_decode_attention.
+ *   K_tail, V_tail [B, Hkv, tail_cap, D] bf16, in: rows 0 .. n_tail-1 of every stream are
+ *            attended (0 <= n_tail <= tail_cap; may be NULL when n_tail == 0);
+ *            tail_cap*D*2 bytes must stay below 4 GiB
+ *   ws       stc_workspace_bytes(shape, STC_WS_ATTENTION_TAIL, k_pages + ceil(n_tail/P))
+ */
+int stc_decode_attention_tail(const stc_shape_t *shape, const void *q, const void *K,
+                              const void *vpacked, const uint16_t *mask, const uint32_t *tok_off,
+                              const int32_t *page_idx, int k_pages, const void *K_tail,
+                              const void *V_tail, int n_tail, int tail_cap, float *out, void *ws,
+                              size_t ws_bytes, void *stream);
+
+/*
+ * Per-step append: writes the new token's key and value of every stream (k_new, v_new
+ * [B, Hkv, D] bf16) to row n_tail of K_tail / V_tail (n_tail < tail_cap); the caller then
+ * attends n_tail + 1 tail tokens.  Moving old tail tokens into the compressed cache (routing
+ * and packing them) is a cache-construction step and not done here.
+ */
+int stc_append_tail(const stc_shape_t *shape, const void *k_new, const void *v_new, void *K_tail,
+                    void *V_tail, int n_tail, int tail_cap, void *stream);
 
 /*
  * Token-level compaction helper for caches reduced by a visual-token method

@@ -17,12 +17,12 @@ LIB_PATH = os.path.join(_PKG_DIR, "libstc.so")
 
 STC_OK = 0
 STC_ERR_NULL, STC_ERR_SHAPE, STC_ERR_ALIGN, STC_ERR_WORKSPACE, STC_ERR_LAUNCH = -1, -2, -3, -4, -5
-STC_WS_ROUTE, STC_WS_SELECT, STC_WS_ATTENTION = 1, 2, 3
+STC_WS_ROUTE, STC_WS_SELECT, STC_WS_ATTENTION, STC_WS_ATTENTION_TAIL = 1, 2, 3, 4
 STC_ROUTE_MASK, STC_ROUTE_TOPK, STC_ROUTE_GLOBAL = 0, 1, 2
 
 EXPORTS = ["stc_version", "stc_status_string", "stc_workspace_bytes", "stc_bounds_bytes",
            "stc_build_page_bounds",
-           "stc_route_and_pack_values", "stc_select_pages", "stc_score_pages", "stc_decode_attention",
+           "stc_route_and_pack_values", "stc_select_pages", "stc_score_pages", "stc_decode_attention", "stc_decode_attention_tail", "stc_append_tail",
            "stc_compact_tokens"]
 
 
@@ -77,6 +77,11 @@ def load_library():
     lib.stc_score_pages.argtypes = [shp, vp, vp, vp, vp]
     lib.stc_decode_attention.restype = ctypes.c_int
     lib.stc_decode_attention.argtypes = [shp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp, sz, vp]
+    lib.stc_decode_attention_tail.restype = ctypes.c_int
+    lib.stc_decode_attention_tail.argtypes = [shp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp,
+                                              ctypes.c_int, ctypes.c_int, vp, vp, sz, vp]
+    lib.stc_append_tail.restype = ctypes.c_int
+    lib.stc_append_tail.argtypes = [shp, vp, vp, vp, vp, ctypes.c_int, ctypes.c_int, vp]
     lib.stc_compact_tokens.restype = ctypes.c_int
     lib.stc_compact_tokens.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
     _lib = lib
@@ -181,6 +186,25 @@ def stc_decode_attention(shape, q, K, vpacked, mask, tok_off, page_idx, k_pages,
         "stc_decode_attention")
 
 
+def stc_decode_attention_tail(shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, K_tail,
+                              V_tail, n_tail, tail_cap, out, ws):
+    _check(load_library().stc_decode_attention_tail(
+        ctypes.byref(shape), _ptr(q, torch.bfloat16, "q"), _ptr(K, torch.bfloat16, "K"),
+        _ptr(vpacked, torch.bfloat16, "vpacked"), _ptr(mask, _U16, "mask"),
+        _ptr(tok_off, _U32, "tok_off"), _ptr(page_idx, torch.int32, "page_idx"), int(k_pages),
+        _ptr(K_tail, torch.bfloat16, "K_tail"), _ptr(V_tail, torch.bfloat16, "V_tail"),
+        int(n_tail), int(tail_cap), _ptr(out, torch.float32, "out"), _ptr(ws, None, "ws"),
+        _nbytes(ws), _stream()), "stc_decode_attention_tail")
+
+
+def stc_append_tail(shape, k_new, v_new, K_tail, V_tail, n_tail, tail_cap):
+    _check(load_library().stc_append_tail(
+        ctypes.byref(shape), _ptr(k_new, torch.bfloat16, "k_new"),
+        _ptr(v_new, torch.bfloat16, "v_new"), _ptr(K_tail, torch.bfloat16, "K_tail"),
+        _ptr(V_tail, torch.bfloat16, "V_tail"), int(n_tail), int(tail_cap), _stream()),
+        "stc_append_tail")
+
+
 def stc_compact_tokens(src, token_idx, dst, B, Hkv, N_src, n_keep, D, dev_status=None):
     _check(load_library().stc_compact_tokens(
         _ptr(src, torch.bfloat16, "src"), _ptr(token_idx, torch.int32, "token_idx"),
@@ -196,7 +220,7 @@ class RoutedCache:
     """
 
     def __init__(self, B, Hq, Hkv, D, N, G, k_pages, v_cap_groups=None, device="cuda:0",
-                 keep_scores=True):
+                 keep_scores=True, tail_cap=0):
         self.device = torch.device(device)
         self.B, self.Hq, self.Hkv, self.D, self.N, self.G = B, Hq, Hkv, D, N, G
         self.NP = (N + 15) // 16
@@ -219,6 +243,12 @@ class RoutedCache:
         self._ws_select = self._ws(STC_WS_SELECT, k_pages)
         self._ws_attn = self._ws(STC_WS_ATTENTION, self.k_eff)
         self.K = None
+        # uncompressed tail of recent tokens (tail_cap = 0: none)
+        self.tail_cap, self.n_tail = tail_cap, 0
+        if tail_cap:
+            self.K_tail = torch.empty(B, Hkv, tail_cap, D, dtype=torch.bfloat16, device=dev)
+            self.V_tail = torch.empty_like(self.K_tail)
+            self._ws_attn = self._ws(STC_WS_ATTENTION_TAIL, self.k_eff + (tail_cap + 15) // 16)
 
     def _ws(self, which, k):
         n = stc_workspace_bytes(self.shape, which, k)
@@ -246,7 +276,18 @@ class RoutedCache:
     def score(self, q, page_score):
         stc_score_pages(self.shape, q, self.bounds, page_score)
 
+    def append(self, k_new, v_new):
+        """New token of every stream ([B, Hkv, D] each) into the uncompressed tail."""
+        stc_append_tail(self.shape, k_new, v_new, self.K_tail, self.V_tail, self.n_tail,
+                        self.tail_cap)
+        self.n_tail += 1
+
     def attend(self, q):
+        if self.tail_cap:
+            stc_decode_attention_tail(self.shape, q, self.K, self.vpacked, self.mask, self.tok_off,
+                                      self.page_idx, self.k_eff, self.K_tail, self.V_tail,
+                                      self.n_tail, self.tail_cap, self.out, self._ws_attn)
+            return
         stc_decode_attention(self.shape, q, self.K, self.vpacked, self.mask, self.tok_off,
                              self.page_idx, self.k_eff, self.out, self._ws_attn)
 

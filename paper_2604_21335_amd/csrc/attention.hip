@@ -32,6 +32,7 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f;  // "no token seen yet" running maximum
 constexpr int kAttnMaxWaves = 8;     // wavefronts per workgroup: 4 or 8
+constexpr int kTailPage = 1 << 30;   // flag of a page slot that lies in the uncompressed tail
 
 // Partial result of one (query head, split): [0] running max (base-2 logits),
 // [1] sum of weights, [2 .. 2+D) weighted value sum.
@@ -103,13 +104,14 @@ __device__ long long* stc_dbg_ptr = nullptr;
 // next pair's K rows.  All loads are unconditional (addresses of absent pages or
 // tokens collapse to one valid location and the result is discarded) so that they
 // stay in flight across the arithmetic.
-template <int D, int PAIRS, int WAVES>
+template <int D, int PAIRS, int WAVES, bool TAIL>
 __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K,
     const unsigned char* __restrict__ vpacked, const uint16_t* __restrict__ mask,
     const uint32_t* __restrict__ tok_off, const int32_t* __restrict__ page_idx,
     float* __restrict__ partial, float* __restrict__ out, int Hq, int Hkv, int N, int NP, int G,
-    uint32_t cap, int k_pages, int splits) {
+    uint32_t cap, int k_pages, int splits, const uint16_t* __restrict__ K_tail,
+    const uint16_t* __restrict__ V_tail, int n_tail, int tail_cap) {
   using C = AttnCfg<D>;
   constexpr int ppw = 2 * PAIRS;  // pages per wavefront
   extern __shared__ __align__(16) unsigned char lds[];  // WAVES * C::WAVE_LDS bytes
@@ -135,14 +137,25 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
   const unsigned char* mask_s = (const unsigned char*)mask + (size_t)stream * N * 2;
   const unsigned char* off_s = (const unsigned char*)tok_off + (size_t)stream * (N + 1) * 4;
   const unsigned char* vs = vpacked + (size_t)stream * (size_t)cap * gbytes;
+  // the uncompressed tail: dense K and V rows, i.e. a packed store in which every token kept
+  // every group; its pages follow the selected ones in the list of page slots
+  const unsigned char* Kts = (const unsigned char*)K_tail + (size_t)stream * tail_cap * D * 2;
+  const unsigned char* vts = (const unsigned char*)V_tail + (size_t)stream * tail_cap * D * 2;
+  const int tail_pages = TAIL ? (n_tail + kPage - 1) / kPage : 0;
+  const uint32_t full_mask = (1u << G) - 1u;
 
-  // this wavefront's pages: lane i holds page pi0 + i (or -1)
+  // this wavefront's pages: lane i holds page slot pi0 + i (-1: none; kTailPage | p: tail page)
   const int pi0 = (split * WAVES + wave) * ppw;
-  const int npages = max(0, min(ppw, k_pages - pi0));
+  const int npages = max(0, min(ppw, k_pages + tail_pages - pi0));
   int my_pg = -1;
   if (lane < npages) {
-    my_pg = page_idx[(size_t)stream * k_pages + pi0 + lane];
-    if (my_pg < 0 || my_pg >= NP) my_pg = -1;
+    const int slot = pi0 + lane;
+    if (slot < k_pages) {
+      my_pg = page_idx[(size_t)stream * k_pages + slot];
+      if (my_pg < 0 || my_pg >= NP) my_pg = -1;
+    } else {
+      my_pg = kTailPage | (slot - k_pages);
+    }
   }
   const int npairs = (npages + 1) / 2;
 
@@ -162,21 +175,37 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
   // 16..31 of its second page; lanes 32 and 33 fetch the offset just past each page
   // (the end of its packed run).  Vector loads on purpose: scalar loads of these
   // scattered words queue up in the scalar cache for several microseconds.
+  // Page slot -> page number, token limit of its store, and whether it is a tail page.
+  auto is_tail = [&](int pg) { return TAIL && pg >= kTailPage; };  // never, if no tail is given
+  auto page_no = [&](int pg) { return pg & (kTailPage - 1); };
+  auto tok_lim = [&](int pg) { return (uint32_t)(is_tail(pg) ? n_tail : N); };
+  uint32_t moi[PAIRS];   // token index behind off[] (tail pages derive their offsets from it)
+  bool mtail[PAIRS];     // this lane's meta words belong to a tail page
   auto issue_meta = [&](int it) {
 #pragma unroll
     for (int x = 0; x < 2; ++x) pgs[it][x] = __builtin_amdgcn_readlane(my_pg, 2 * it + x);
     const int pg = (lane & 1) ? pgs[it][1] : pgs[it][0];          // lanes 32, 33
     const int pgt = (lane & 16) ? pgs[it][1] : pgs[it][0];        // token lanes
-    const uint32_t t = (pgt < 0 ? 0 : pgt * kPage) + r16;
-    const bool tv = lane < 32 && pgt >= 0 && t < (uint32_t)N;
-    const uint32_t tend = pg < 0 ? 0u : min((uint32_t)pg * kPage + kPage, (uint32_t)N);
+    const uint32_t t = (pgt < 0 ? 0 : page_no(pgt) * kPage) + r16;
+    const bool tv = lane < 32 && pgt >= 0 && t < tok_lim(pgt);
+    const uint32_t tend =
+        pg < 0 ? 0u : min((uint32_t)page_no(pg) * kPage + kPage, tok_lim(pg));
     const uint32_t oi = tv ? t : ((lane == 32 || lane == 33) ? tend : 0u);
+    const bool tl = lane < 32 ? (pgt >= 0 && is_tail(pgt)) : (pg >= 0 && is_tail(pg));
     mvalid[it] = tv;
-    mk[it] = *(const uint16_t*)(mask_s + (tv ? t : 0u) * 2);  // discarded later if !tv
-    off[it] = *(const uint32_t*)(off_s + oi * 4);
+    moi[it] = oi;
+    mtail[it] = tl;
+    // tail lanes read word 0 of the stream's arrays and replace the result later
+    mk[it] = *(const uint16_t*)(mask_s + ((tv && !tl) ? t : 0u) * 2);  // discarded if !tv
+    off[it] = *(const uint32_t*)(off_s + (tl ? 0u : oi) * 4);
   };
-  // start and end of the packed runs of a pair (wave-uniform), once the offsets are there
+  // start and end of the packed runs of a pair (wave-uniform), once the offsets are there.
+  // A tail token keeps every group and its G groups sit at token index * G.
   auto finish_meta = [&](int it) {
+    if (mtail[it]) {
+      mk[it] = full_mask;
+      off[it] = moi[it] * G;
+    }
 #pragma unroll
     for (int x = 0; x < 2; ++x) {
       run0[it][x] = __builtin_amdgcn_readlane(off[it], 16 * x);  // token 0 of a page is valid
@@ -187,21 +216,24 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
 #pragma unroll
     for (int x = 0; x < 2; ++x) {
       const int pg = pgs[it][x];
-      const uint32_t t0 = pg < 0 ? 0 : pg * kPage;
+      const uint32_t t0 = pg < 0 ? 0 : page_no(pg) * kPage;
+      const uint32_t lim = tok_lim(pg);
+      const unsigned char* kb = (pg >= 0 && is_tail(pg)) ? Kts : Ks;  // wave-uniform
 #pragma unroll
       for (int j = 0; j < C::NLD; ++j) {
         const uint32_t tok = (j * 64 + lane) / C::LPR;
-        const bool tv = pg >= 0 && (t0 + tok < (uint32_t)N);
-        // rows of absent tokens read the stream's first bytes: their logits are discarded
+        const bool tv = pg >= 0 && (t0 + tok < lim);
+        // rows of absent tokens read the store's first bytes: their logits are discarded
         const uint32_t ko = tv ? t0 * (D * 2) + (j * 64 + lane) * 16 : 0;
-        kreg[it][x][j] = *(const u32x4*)(Ks + ko);
+        kreg[it][x][j] = *(const u32x4*)(kb + ko);
       }
     }
   };
   // Groups of a page present in the store (wave-uniform).
   auto run_groups = [&](int it, int x) -> uint32_t {
     const uint32_t r0 = run0[it][x];
-    const uint32_t r1 = pgs[it][x] < 0 ? 0u : min(run1[it][x], cap);
+    const uint32_t store = is_tail(pgs[it][x]) ? (uint32_t)tail_cap * G : cap;
+    const uint32_t r1 = pgs[it][x] < 0 ? 0u : min(run1[it][x], store);
     const uint32_t rg = r1 > r0 ? r1 - r0 : 0u;
     return min(rg, (uint32_t)(kPage * G));
   };
@@ -209,7 +241,8 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
 #define STC_ISSUE_V(it, vreg)                                                                  \
   static_for<0, 2>([&](auto x) {                                                               \
     const uint32_t rbytes = run_groups(it, x) * gbytes + vgate;                                \
-    const unsigned char* vrun = vs + (size_t)run0[it][x] * gbytes;                             \
+    const unsigned char* vrun =                                                                \
+        ((pgs[it][x] >= 0 && is_tail(pgs[it][x])) ? vts : vs) + (size_t)run0[it][x] * gbytes;  \
     static_for<0, C::NLD>([&](auto j) {                                                        \
       const uint32_t bo = (j * 64 + lane) * 16;                                                \
       /* one address computed with integer selects, so that it stays a single request */      \
@@ -269,10 +302,11 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
       }
       // this lane holds tokens 4*kg + i of page x for head r16
       const int pg = pgs[it][x];
-      const uint32_t t0 = pg < 0 ? 0 : pg * kPage;
+      const uint32_t t0 = pg < 0 ? 0 : page_no(pg) * kPage;
+      const uint32_t lim = tok_lim(pg);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const bool tv = pg >= 0 && (t0 + 4 * kg + i < (uint32_t)N);
+        const bool tv = pg >= 0 && (t0 + 4 * kg + i < lim);
         s[x][i] = tv ? sv[i] * scale : -INFINITY;  // weight of an absent token is exactly 0
         mx = fmaxf(mx, s[x][i]);
       }
@@ -517,10 +551,13 @@ size_t attention_ws_bytes(const stc_shape_t& s, int k_pages) {
 
 int launch_attention(const stc_shape_t& s, const void* q, const void* K, const void* vpacked,
                      const uint16_t* mask, const uint32_t* tok_off, const int32_t* page_idx,
-                     int k_pages, float* out, void* ws, hipStream_t st) {
+                     int k_pages, const void* K_tail, const void* V_tail, int n_tail, int tail_cap,
+                     float* out, void* ws, hipStream_t st) {
   const int NP = (s.N + kPage - 1) / kPage;
   const int streams = s.B * s.Hkv;
-  const AttnPlan plan = attention_plan(s, k_pages);
+  const int tail_pages = (n_tail + kPage - 1) / kPage;
+  if (tail_pages == 0) K_tail = V_tail = K;  // any valid address: never read
+  const AttnPlan plan = attention_plan(s, k_pages + tail_pages);
   const int splits = plan.splits;
   dim3 grid(splits, streams);
   float* partial = (float*)ws;
@@ -536,17 +573,22 @@ int launch_attention(const stc_shape_t& s, const void* q, const void* K, const v
   }
 #endif
   // workgroups of 8 wavefronts at D = 128 need more than the default 64 KiB of LDS
-#define STC_ATTN_LAUNCH(DD, PP, WW)                                                               \
+#define STC_ATTN_LAUNCH(DD, PP, WW)                                    \
+  {                                                                    \
+    if (tail_pages > 0) STC_ATTN_LAUNCH_T(DD, PP, WW, true)            \
+    else STC_ATTN_LAUNCH_T(DD, PP, WW, false)                          \
+  }
+#define STC_ATTN_LAUNCH_T(DD, PP, WW, TT)                                                         \
   {                                                                                               \
     constexpr int lds_bytes = WW * AttnCfg<DD>::WAVE_LDS;                                         \
     static const hipError_t attr = hipFuncSetAttribute(                                           \
-        (const void*)attn_mfma_kernel<DD, PP, WW>, hipFuncAttributeMaxDynamicSharedMemorySize,    \
-        lds_bytes);                                                                               \
+        (const void*)attn_mfma_kernel<DD, PP, WW, TT>,                                            \
+        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);                                   \
     if (attr != hipSuccess) return -1;                                                            \
-    attn_mfma_kernel<DD, PP, WW><<<grid, 64 * WW, lds_bytes, st>>>(                               \
+    attn_mfma_kernel<DD, PP, WW, TT><<<grid, 64 * WW, lds_bytes, st>>>(                           \
         (const uint16_t*)q, (const uint16_t*)K, (const unsigned char*)vpacked, mask, tok_off,     \
         page_idx, partial, out, s.Hq, s.Hkv, s.N, NP, s.G, (uint32_t)s.v_cap_groups, k_pages,     \
-        splits);                                                                                  \
+        splits, (const uint16_t*)K_tail, (const uint16_t*)V_tail, n_tail, tail_cap);              \
   }
 #ifdef STC_TUNE
 #define STC_ATTN_PICK(DD)                                  \
@@ -568,6 +610,7 @@ int launch_attention(const stc_shape_t& s, const void* q, const void* K, const v
     STC_ATTN_PICK(64)
   }
 #undef STC_ATTN_PICK
+#undef STC_ATTN_LAUNCH_T
 #undef STC_ATTN_LAUNCH
   if (hipGetLastError() != hipSuccess) return -1;
   if (splits > 1) {
@@ -578,6 +621,37 @@ int launch_attention(const stc_shape_t& s, const void* q, const void* K, const v
     if (hipGetLastError() != hipSuccess) return -1;
   }
   return 0;
+}
+
+// New token of every stream -> row n_tail of the stream's uncompressed tail (K and V).
+template <int D>
+__global__ __launch_bounds__(256) void append_tail_kernel(const uint4* __restrict__ k_new,
+                                                          const uint4* __restrict__ v_new,
+                                                          uint4* __restrict__ K_tail,
+                                                          uint4* __restrict__ V_tail, int streams,
+                                                          int n_tail, int tail_cap) {
+  constexpr int LPR = D / 8;  // 16-byte pieces per row
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= streams * LPR) return;
+  const int stream = i / LPR, piece = i % LPR;
+  const size_t dst = ((size_t)stream * tail_cap + n_tail) * LPR + piece;
+  K_tail[dst] = k_new[i];
+  V_tail[dst] = v_new[i];
+}
+
+int launch_append_tail(const stc_shape_t& s, const void* k_new, const void* v_new, void* K_tail,
+                       void* V_tail, int n_tail, int tail_cap, hipStream_t st) {
+  const int streams = s.B * s.Hkv;
+  const int n = streams * (s.D / 8);
+  if (s.D == 128)
+    append_tail_kernel<128><<<(n + 255) / 256, 256, 0, st>>>(
+        (const uint4*)k_new, (const uint4*)v_new, (uint4*)K_tail, (uint4*)V_tail, streams, n_tail,
+        tail_cap);
+  else
+    append_tail_kernel<64><<<(n + 255) / 256, 256, 0, st>>>(
+        (const uint4*)k_new, (const uint4*)v_new, (uint4*)K_tail, (uint4*)V_tail, streams, n_tail,
+        tail_cap);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 }  // namespace stc

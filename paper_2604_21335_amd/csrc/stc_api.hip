@@ -55,6 +55,9 @@ size_t stc_workspace_bytes(const stc_shape_t* shape, int which_call, int k_pages
     case STC_WS_ATTENTION:
       if (k_pages < 1 || k_pages > num_pages(shape)) return 0;
       return stc::attention_ws_bytes(*shape, k_pages);
+    case STC_WS_ATTENTION_TAIL:  // k_pages counts the tail's pages too
+      if (k_pages < 1) return 0;
+      return stc::attention_ws_bytes(*shape, k_pages);
     default: return 0;
   }
 }
@@ -130,10 +133,13 @@ int stc_score_pages(const stc_shape_t* shape, const void* q, const void* bounds,
                                                                                : STC_OK;
 }
 
-int stc_decode_attention(const stc_shape_t* shape, const void* q, const void* K,
-                         const void* vpacked, const uint16_t* mask, const uint32_t* tok_off,
-                         const int32_t* page_idx, int k_pages, float* out, void* ws,
-                         size_t ws_bytes, void* stream) {
+namespace {
+
+int decode_attention_impl(const stc_shape_t* shape, const void* q, const void* K,
+                          const void* vpacked, const uint16_t* mask, const uint32_t* tok_off,
+                          const int32_t* page_idx, int k_pages, const void* K_tail,
+                          const void* V_tail, int n_tail, int tail_cap, float* out, void* ws,
+                          size_t ws_bytes, void* stream) {
   if (!shape || !q || !K || !vpacked || !mask || !tok_off || !page_idx || !out)
     return STC_ERR_NULL;
   if (!shape_ok(shape) || k_pages < 1 || k_pages > num_pages(shape) || shape->v_cap_groups < 1)
@@ -142,13 +148,50 @@ int stc_decode_attention(const stc_shape_t* shape, const void* q, const void* K,
   if ((long long)shape->N * shape->D * 2 >= (1ll << 32) ||
       shape->v_cap_groups * (shape->D / shape->G) * 2 >= (1ll << 32))
     return STC_ERR_SHAPE;
+  if (n_tail < 0 || tail_cap < 0 || n_tail > tail_cap ||
+      (long long)tail_cap * shape->D * 2 >= (1ll << 32))
+    return STC_ERR_SHAPE;
+  if (n_tail > 0 && (!K_tail || !V_tail)) return STC_ERR_NULL;
   if (!aligned16(q) || !aligned16(K) || !aligned16(vpacked) || !aligned16(mask) ||
-      !aligned16(tok_off) || !aligned16(page_idx) || !aligned16(out))
+      !aligned16(tok_off) || !aligned16(page_idx) || !aligned16(out) ||
+      (n_tail > 0 && (!aligned16(K_tail) || !aligned16(V_tail))))
     return STC_ERR_ALIGN;
-  const size_t need = stc::attention_ws_bytes(*shape, k_pages);
+  const int slots = k_pages + (n_tail + shape->P - 1) / shape->P;
+  const size_t need = stc::attention_ws_bytes(*shape, slots);
   if (need && (!ws || ws_bytes < need || !aligned16(ws))) return STC_ERR_WORKSPACE;
-  return stc::launch_attention(*shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, out, ws,
-                               (hipStream_t)stream)
+  return stc::launch_attention(*shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, K_tail,
+                               V_tail, n_tail, tail_cap, out, ws, (hipStream_t)stream)
+             ? STC_ERR_LAUNCH
+             : STC_OK;
+}
+
+}  // namespace
+
+int stc_decode_attention(const stc_shape_t* shape, const void* q, const void* K,
+                         const void* vpacked, const uint16_t* mask, const uint32_t* tok_off,
+                         const int32_t* page_idx, int k_pages, float* out, void* ws,
+                         size_t ws_bytes, void* stream) {
+  return decode_attention_impl(shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, nullptr,
+                               nullptr, 0, 0, out, ws, ws_bytes, stream);
+}
+
+int stc_decode_attention_tail(const stc_shape_t* shape, const void* q, const void* K,
+                              const void* vpacked, const uint16_t* mask, const uint32_t* tok_off,
+                              const int32_t* page_idx, int k_pages, const void* K_tail,
+                              const void* V_tail, int n_tail, int tail_cap, float* out, void* ws,
+                              size_t ws_bytes, void* stream) {
+  return decode_attention_impl(shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, K_tail,
+                               V_tail, n_tail, tail_cap, out, ws, ws_bytes, stream);
+}
+
+int stc_append_tail(const stc_shape_t* shape, const void* k_new, const void* v_new, void* K_tail,
+                    void* V_tail, int n_tail, int tail_cap, void* stream) {
+  if (!shape || !k_new || !v_new || !K_tail || !V_tail) return STC_ERR_NULL;
+  if (!shape_ok(shape) || n_tail < 0 || n_tail >= tail_cap) return STC_ERR_SHAPE;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(K_tail) || !aligned16(V_tail))
+    return STC_ERR_ALIGN;
+  return stc::launch_append_tail(*shape, k_new, v_new, K_tail, V_tail, n_tail, tail_cap,
+                                 (hipStream_t)stream)
              ? STC_ERR_LAUNCH
              : STC_OK;
 }

@@ -29,7 +29,10 @@ int attention_splits(const stc_shape_t& s, int k_pages);
 size_t attention_ws_bytes(const stc_shape_t& s, int k_pages);
 int launch_attention(const stc_shape_t& s, const void* q, const void* K, const void* vpacked,
                      const uint16_t* mask, const uint32_t* tok_off, const int32_t* page_idx,
-                     int k_pages, float* out, void* ws, hipStream_t st);
+                     int k_pages, const void* K_tail, const void* V_tail, int n_tail, int tail_cap,
+                     float* out, void* ws, hipStream_t st);
+int launch_append_tail(const stc_shape_t& s, const void* k_new, const void* v_new, void* K_tail,
+                       void* V_tail, int n_tail, int tail_cap, hipStream_t st);
 
 int launch_compact(const void* src, const int32_t* token_idx, void* dst, int B, int Hkv, int N_src,
                    int n_keep, int D, int32_t* dev_status, hipStream_t st);

@@ -97,6 +97,20 @@ def test_null_alignment_and_workspace_errors():
     assert att2(None, big) == stc.STC_ERR_WORKSPACE
     assert lib.stc_decode_attention(ctypes.byref(_shape(v_cap_groups=0)), FAKE, FAKE, FAKE, FAKE,
                                     FAKE, FAKE, 7, FAKE, FAKE, big, None) == stc.STC_ERR_SHAPE
+    # attention with a tail: tail arguments
+    tail = lambda kt, vt, n, capt: lib.stc_decode_attention_tail(  # noqa: E731
+        r, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 7, kt, vt, n, capt, FAKE, FAKE, big, None)
+    assert tail(None, None, 3, 8) == stc.STC_ERR_NULL
+    assert tail(FAKE, FAKE, 9, 8) == stc.STC_ERR_SHAPE
+    assert tail(FAKE, FAKE, -1, 8) == stc.STC_ERR_SHAPE
+    assert tail(ODD, FAKE, 3, 8) == stc.STC_ERR_ALIGN
+    assert stc.stc_workspace_bytes(s, stc.STC_WS_ATTENTION_TAIL, 7 + 1) == 0     # still one split
+    assert stc.stc_workspace_bytes(s, stc.STC_WS_ATTENTION_TAIL, 7 + 40) > 0
+    assert lib.stc_decode_attention_tail(r, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 7, FAKE, FAKE, 600,
+                                         640, FAKE, None, 0, None) == stc.STC_ERR_WORKSPACE
+    assert lib.stc_append_tail(r, FAKE, FAKE, FAKE, FAKE, 8, 8, None) == stc.STC_ERR_SHAPE
+    assert lib.stc_append_tail(r, FAKE, None, FAKE, FAKE, 0, 8, None) == stc.STC_ERR_NULL
+    assert lib.stc_append_tail(r, ODD, FAKE, FAKE, FAKE, 0, 8, None) == stc.STC_ERR_ALIGN
     # compact
     assert lib.stc_compact_tokens(FAKE, FAKE, FAKE, 1, 1, 10, 4, 100, None, None) == stc.STC_ERR_SHAPE
     assert lib.stc_compact_tokens(FAKE, None, FAKE, 1, 1, 10, 4, 128, None, None) == stc.STC_ERR_NULL

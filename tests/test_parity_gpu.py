@@ -152,6 +152,76 @@ def test_global_budget_routing_with_ties_everywhere():
         assert (hip["tok_off"][:, :, -1] == N * gk).all()
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,D,N,G,k,ntail", [
+    (1, 4, 1, 128, 700, 8, 9, 1), (2, 14, 2, 128, 1500, 8, 20, 37), (1, 8, 8, 64, 333, 4, 21, 16),
+    (2, 2, 2, 64, 100, 4, 3, 15), (1, 16, 1, 128, 2048, 16, 128, 64), (1, 3, 1, 64, 64, 2, 4, 17)])
+def test_attention_with_uncompressed_tail(B, Hq, Hkv, D, N, G, k, ntail):
+    """Selected pages of the compressed cache plus an always-attended dense tail of recent
+    tokens (ragged last tail page included), against the oracle; an empty tail gives the bits
+    of the plain entry point."""
+    K, V, q, logits, kcount = _rand_case(80 + ntail, B, Hq, Hkv, D, N, G)
+    rng = np.random.default_rng(81 + ntail)
+    cap_t = ntail + 5
+    Kt, Vt = randn_bf16(rng, (B, Hkv, cap_t, D)), randn_bf16(rng, (B, Hkv, cap_t, D))
+    hip = PT.run_hip(K, V, q, G, k, logits=logits, kcount=kcount)
+    c = hip["cache"]
+    shp = c.shape
+    dq, dKt, dVt = PT.to_dev_bf16(q), PT.to_dev_bf16(Kt), PT.to_dev_bf16(Vt)
+    slots = c.k_eff + (ntail + 15) // 16
+    ws = torch.zeros(max(16, stc.stc_workspace_bytes(shp, stc.STC_WS_ATTENTION_TAIL, slots)),
+                     dtype=torch.uint8, device="cuda:0")
+    out = torch.full_like(c.out, float("nan"))
+    stc.stc_decode_attention_tail(shp, dq, c.K, c.vpacked, c.mask, c.tok_off, c.page_idx, c.k_eff,
+                                  dKt, dVt, ntail, cap_t, out, ws)
+    out0 = torch.full_like(c.out, float("nan"))
+    stc.stc_decode_attention_tail(shp, dq, c.K, c.vpacked, c.mask, c.tok_off, c.page_idx, c.k_eff,
+                                  None, None, 0, 0, out0, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(out0.cpu().numpy(), hip["out"])
+    got = out.cpu().numpy()
+    R = Hq // Hkv
+    worst = 0.0
+    for b in range(B):
+        for h in range(Hkv):
+            want = O.decode_attention(q[b, h * R:(h + 1) * R], K[b, h], V[b, h], hip["mask"][b, h],
+                                      hip["page_idx"][b, h], G, K_tail=Kt[b, h, :ntail],
+                                      V_tail=Vt[b, h, :ntail])
+            worst = max(worst, float(np.abs(got[b, h * R:(h + 1) * R] - want).max()))
+    assert worst < PT.TIGHT
+
+
+def test_append_then_attend_step_by_step():
+    """Twenty decode steps: each appends the new token's key and value to the tail and attends
+    cache + tail; checked against the oracle at every step (tail lengths 1..20, crossing a page)."""
+    B, Hq, Hkv, D, N, G, k, steps = 2, 8, 2, 128, 600, 8, 10, 20
+    K, V, q, logits, kcount = _rand_case(90, B, Hq, Hkv, D, N, G)
+    rng = np.random.default_rng(91)
+    c = stc.RoutedCache(B, Hq, Hkv, D, N, G, k, device="cuda:0", tail_cap=24)
+    c.K_tail.view(torch.int16).fill_(0x7FC0)               # NaN: rows not yet appended
+    c.V_tail.view(torch.int16).fill_(0x7FC0)
+    c.build(PT.to_dev_bf16(K), PT.to_dev_bf16(V), logits=torch.from_numpy(logits).cuda(),
+            kcount=torch.from_numpy(kcount).cuda())
+    mask = O.route_and_pack_all(V, G, logits=logits, kcount=kcount)[0]
+    new_k, new_v = randn_bf16(rng, (steps, B, Hkv, D)), randn_bf16(rng, (steps, B, Hkv, D))
+    R = Hq // Hkv
+    for s_ in range(steps):
+        qs = randn_bf16(rng, (B, Hq, D))
+        c.append(PT.to_dev_bf16(new_k[s_]), PT.to_dev_bf16(new_v[s_]))
+        c.step(PT.to_dev_bf16(qs))
+        torch.cuda.synchronize()
+        assert c.n_tail == s_ + 1
+        got, idx = c.out.cpu().numpy(), c.page_idx.cpu().numpy()
+        for (b, h) in ((0, 0), (1, 1)):
+            sc = O.page_scores(qs[b, h * R:(h + 1) * R], O.page_bounds(K[b, h]))
+            assert np.array_equal(idx[b, h], O.select_pages(sc, k))
+            want = O.decode_attention(qs[b, h * R:(h + 1) * R], K[b, h], V[b, h], mask[b, h],
+                                      idx[b, h], G, K_tail=new_k[:s_ + 1, b, h],
+                                      V_tail=new_v[:s_ + 1, b, h])
+            assert np.abs(got[b, h * R:(h + 1) * R] - want).max() < PT.TIGHT
+    assert np.array_equal(PT.host_bf16(c.K_tail)[:, :, :steps], new_k.transpose(1, 2, 0, 3))
+    assert np.array_equal(PT.host_bf16(c.V_tail)[:, :, :steps], new_v.transpose(1, 2, 0, 3))
+
+
 def test_score_pages_alone_matches_oracle_bits():
     B, Hq, Hkv, D, N, G = 2, 14, 2, 128, 3000, 8
     K, V, q, logits, kcount = _rand_case(21, B, Hq, Hkv, D, N, G, outliers=True)
