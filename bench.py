@@ -10,6 +10,7 @@ no step is served from the 256 MB last-level cache.
 
 Prints ONE JSON line:
   value / ms_per_step  whole step, averaged over --steps back-to-back steps (HIP events)
+  step_us_per_step_events  median / p10 / p90 of the same steps timed one by one
   hbm_GBps / hbm_frac  algorithmic bytes of the step / step time, against 8 TB/s
   calls                the same for stc_select_pages, stc_decode_attention and stc_score_pages
                        alone (each timed over --steps back-to-back launches)
@@ -92,6 +93,19 @@ def timed(fn, n, torch):
     b.record()
     torch.cuda.synchronize()
     return a.elapsed_time(b) / n
+
+
+def per_step_times(fn, n, torch):
+    """Microseconds of each of n steps, one HIP event pair per step (the event records add a
+    little to every step, so these sit slightly above the back-to-back mean)."""
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+    torch.cuda.synchronize()
+    ev[0].record()
+    for i in range(n):
+        fn(i)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    return sorted(ev[i].elapsed_time(ev[i + 1]) * 1e3 for i in range(n))
 
 
 def cpu_baseline(W, w, dev, budget_s=12.0):
@@ -200,6 +214,8 @@ def main():
     ms_sel = timed(select_only, args.steps, torch) if selecting else 0.0
     ms_att = timed(attend_only, args.steps, torch)
     ms_score = timed(score_only, args.steps, torch) if selecting else 0.0
+    per = per_step_times(step, args.steps, torch)
+    pct = lambda f: per[min(len(per) - 1, int(f * len(per)))]  # noqa: E731
 
     ab = algorithmic_bytes(w, mean_kept)
     gbps = lambda nbytes, ms: (nbytes / (ms * 1e-3) / 1e9) if ms > 0 else 0.0  # noqa: E731
@@ -228,6 +244,7 @@ def main():
         "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "N": w.N,
                    "page": 16, "k_pages": min(w.k_pages, w.NP), "G": w.G,
                    "mean_kept_groups": mean_kept, "layers_per_step": L, "cache_replicas": n_rep},
+        "step_us_per_step_events": {"median": pct(0.5), "p10": pct(0.1), "p90": pct(0.9)},
         "hbm_GBps": step_gbps, "hbm_frac": step_gbps / HBM_PEAK_GBPS,
         "algorithmic_bytes_per_step": ab["step"] * L, "bytes_parts": ab["parts"],
         "calls": calls, "roofline": roofline,
