@@ -104,12 +104,12 @@ __global__ __launch_bounds__(kSelThreads) void topk_kernel(const float* __restri
 // the IPT adjacent pages t*IPT ..; used whenever NP <= 256*32.  Each radix pass is a
 // shared-memory histogram of one key byte, a block scan over the digits in descending
 // order and a broadcast of the digit that holds the k-th largest key.
-template <int IPT>
-__global__ __launch_bounds__(256) void topk_reg_kernel(const float* __restrict__ score,
+template <int IPT, int THREADS>
+__global__ __launch_bounds__(THREADS) void topk_reg_kernel(const float* __restrict__ score,
                                                        int32_t* __restrict__ page_idx, int NP,
                                                        int k) {
   __shared__ int hist[256];
-  __shared__ int waves[4];
+  __shared__ int waves[THREADS / 64];
   __shared__ uint32_t s_prefix;
   __shared__ int s_remaining, s_cand, s_ncand;
   __shared__ uint32_t cand[64];
@@ -149,11 +149,11 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(const float* __restrict__
     kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, d));
     kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, d));
   }
-  __shared__ uint32_t s_min[4], s_max[4];
+  __shared__ uint32_t s_min[THREADS / 64], s_max[THREADS / 64];
   if ((tid & 63) == 0) s_min[tid >> 6] = kmin, s_max[tid >> 6] = kmax;
   __syncthreads();
-  kmin = min(min(s_min[0], s_min[1]), min(s_min[2], s_min[3]));
-  kmax = max(max(s_max[0], s_max[1]), max(s_max[2], s_max[3]));
+#pragma unroll
+  for (int w = 0; w < THREADS / 64; ++w) kmin = min(kmin, s_min[w]), kmax = max(kmax, s_max[w]);
   const uint32_t diff = kmin ^ kmax;
   const int top = diff ? 31 - __clz(diff) : 0;  // highest differing bit
   int shift = max(top - 7, 0);
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(const float* __restrict__
   // The last window may overlap bits that are already fixed; keys are filtered on all
   // fixed bits, so the digit found repeats them.
   for (;; shift = max(shift - 8, 0)) {
-    hist[tid] = 0;
+    if (tid < 256) hist[tid] = 0;
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < IPT; ++j) {
@@ -171,10 +171,10 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(const float* __restrict__
       if (in && i0 + j < NP) atomicAdd(&hist[(key[j] >> shift) & 255u], 1);
     }
     __syncthreads();
-    const int cnt = hist[255 - tid];  // digits in descending order
+    const int cnt = tid < 256 ? hist[255 - tid] : 0;  // digits in descending order
     int tot;
     const int above = block_exscan(cnt, waves, &tot);  // keys with a larger digit
-    if (above < remaining && remaining <= above + cnt) {
+    if (tid < 256 && above < remaining && remaining <= above + cnt) {
       s_prefix = (prefix & ~(255u << shift)) | ((uint32_t)(255 - tid) << shift);
       s_remaining = remaining - above;
       s_cand = cnt;  // keys that share the new prefix
@@ -255,21 +255,18 @@ int launch_select(const stc_shape_t& s, const void* q, const void* bounds, int k
     return hipGetLastError() == hipSuccess ? 0 : -1;
   }
   if (launch_score(s, q, bounds, score, st)) return -1;
-  const int ipt = (NP + 255) / 256;
-  if (ipt <= 1)
-    topk_reg_kernel<1><<<streams, 256, 0, st>>>(score, page_idx, NP, k_pages);
-  else if (ipt <= 2)
-    topk_reg_kernel<2><<<streams, 256, 0, st>>>(score, page_idx, NP, k_pages);
-  else if (ipt <= 4)
-    topk_reg_kernel<4><<<streams, 256, 0, st>>>(score, page_idx, NP, k_pages);
-  else if (ipt <= 8)
-    topk_reg_kernel<8><<<streams, 256, 0, st>>>(score, page_idx, NP, k_pages);
-  else if (ipt <= 16)
-    topk_reg_kernel<16><<<streams, 256, 0, st>>>(score, page_idx, NP, k_pages);
-  else if (ipt <= 32)
-    topk_reg_kernel<32><<<streams, 256, 0, st>>>(score, page_idx, NP, k_pages);
-  else
-    topk_kernel<<<streams, kSelThreads, 0, st>>>(score, page_idx, NP, k_pages);
+  // keys per thread; streams of more than 1024 pages use 512 threads (measured: faster than
+  // both 256 threads with more keys each and 1024 threads with longer barriers)
+#define STC_TOPK(IPT, TH) \
+  topk_reg_kernel<IPT, TH><<<streams, TH, 0, st>>>(score, page_idx, NP, k_pages)
+  if (NP <= 256) STC_TOPK(1, 256);
+  else if (NP <= 512) STC_TOPK(2, 256);
+  else if (NP <= 1024) STC_TOPK(4, 256);
+  else if (NP <= 2048) STC_TOPK(4, 512);
+  else if (NP <= 4096) STC_TOPK(8, 512);
+  else if (NP <= 8192) STC_TOPK(16, 512);
+  else topk_kernel<<<streams, kSelThreads, 0, st>>>(score, page_idx, NP, k_pages);
+#undef STC_TOPK
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
