@@ -328,6 +328,39 @@ def select_pages_all(q_bits, bounds_bits, k):
     return idx, score
 
 
+def select_pages_per_head_all(q_bits, bounds_bits, k):
+    """The other reading of Quest under GQA: every query head selects its own pages from its
+    own upper-bound score (no maximum over the group).
+    q_bits[B, Hq, D], bounds[B, Hkv, NP, 2, D] ->
+    (page_idx[B, Hq, min(k,NP)] int32, page_score[B, Hq, NP] float32)."""
+    B, Hq, D = q_bits.shape
+    _, Hkv, NP = bounds_bits.shape[:3]
+    R = Hq // Hkv
+    k_eff = min(int(k), NP)
+    idx = np.zeros((B, Hq, k_eff), dtype=np.int32)
+    score = np.zeros((B, Hq, NP), dtype=np.float32)
+    for b in range(B):
+        for j in range(Hq):
+            score[b, j] = page_scores(q_bits[b, j:j + 1], bounds_bits[b, j // R])
+            idx[b, j] = select_pages(score[b, j], k_eff)
+    return idx, score
+
+
+def decode_attention_per_head_all(q_bits, K_bits, V_bits, mask, page_idx, G, P=16):
+    """page_idx[B, Hq, k]: query head j attends its own pages of KV head j // (Hq/Hkv).
+    -> out[B, Hq, D] float32."""
+    B, Hq, D = q_bits.shape
+    Hkv = K_bits.shape[1]
+    R = Hq // Hkv
+    out = np.zeros((B, Hq, D), dtype=np.float32)
+    for b in range(B):
+        for j in range(Hq):
+            out[b, j:j + 1] = decode_attention(q_bits[b, j:j + 1], K_bits[b, j // R],
+                                               V_bits[b, j // R], mask[b, j // R],
+                                               page_idx[b, j], G, P)
+    return out
+
+
 def decode_attention_all(q_bits, K_bits, V_bits, mask, page_idx, G, P=16, K_tail=None,
                          V_tail=None):
     """-> out[B, Hq, D] float32; query head j belongs to KV head j // (Hq/Hkv).

@@ -547,3 +547,53 @@ def test_attention_tail_special_cases():
     o = O.decode_attention(q[:1], K, V, np.zeros(N, dtype=np.uint16), [0, 1, 2, 3], G,
                            K_tail=Kt, V_tail=Vt)
     assert np.abs(o[0] - bits_to_f64(Vt)[0]).max() < 1e-3
+
+
+# --- per-query-head page selection (the other reading of Quest under GQA) -----------------
+
+def test_per_head_selection_is_each_heads_own_topk():
+    """Constant pages: bounds collapse (min = max), a head's page score is exactly its logit
+    with any token of the page, so each head's selection is the textbook top-k of ITS logits,
+    and heads of one group choose different pages."""
+    rng = np.random.default_rng(70)
+    B, Hq, Hkv, D, NP, k = 1, 4, 2, 64, 12, 4
+    page_rows = ints_bf16(rng, (B, Hkv, NP, D), -3, 3)
+    K = np.repeat(page_rows, 16, axis=2)                     # [B, Hkv, NP*16, D]
+    q = ints_bf16(rng, (B, Hq, D), -3, 3)
+    bounds = O.build_page_bounds_all(K)
+    idx, score = O.select_pages_per_head_all(q, bounds, k)
+    assert idx.shape == (B, Hq, k) and score.shape == (B, Hq, NP)
+    for j in range(Hq):
+        logit = bits_to_f64(page_rows[0, j // 2]) @ bits_to_f64(q[0, j])
+        assert np.array_equal(score[0, j].astype(np.float64), logit)
+        want = sorted(sorted(range(NP), key=lambda p: (-logit[p], p))[:k])
+        assert list(idx[0, j]) == want
+    assert not np.array_equal(idx[0, 0], idx[0, 1])          # same KV head, different pages
+
+
+def test_per_head_equals_shared_selection_for_mha_and_for_identical_heads():
+    rng = np.random.default_rng(71)
+    B, Hkv, D, N, k = 2, 2, 64, 160, 3
+    K = randn_bf16(rng, (B, Hkv, N, D))
+    bounds = O.build_page_bounds_all(K)
+    q = randn_bf16(rng, (B, Hkv, D))                          # MHA: one head per KV head
+    a, sa = O.select_pages_per_head_all(q, bounds, k)
+    b_, sb = O.select_pages_all(q, bounds, k)
+    assert np.array_equal(a, b_) and np.array_equal(sa.view(np.uint32), sb.view(np.uint32))
+    q3 = np.repeat(q, 3, axis=1)                              # 3 identical heads per KV head
+    c, _ = O.select_pages_per_head_all(q3, bounds, k)
+    assert np.array_equal(c, np.repeat(b_, 3, axis=1))
+
+
+def test_per_head_attention_wrapper_uses_each_heads_pages():
+    rng = np.random.default_rng(72)
+    B, Hq, Hkv, D, N, G, k = 1, 4, 2, 64, 96, 4, 2
+    K, V = randn_bf16(rng, (B, Hkv, N, D)), randn_bf16(rng, (B, Hkv, N, D))
+    q = randn_bf16(rng, (B, Hq, D))
+    mask = rng.integers(0, 1 << G, size=(B, Hkv, N)).astype(np.uint16)
+    idx, _ = O.select_pages_per_head_all(q, O.build_page_bounds_all(K), k)
+    out = O.decode_attention_per_head_all(q, K, V, mask, idx, G)
+    for j in range(Hq):
+        want = O.decode_attention(q[0, j:j + 1], K[0, j // 2], V[0, j // 2], mask[0, j // 2],
+                                  idx[0, j], G)
+        assert np.array_equal(out[0, j:j + 1], want)
