@@ -60,7 +60,14 @@ enum {
 };
 
 /* which_call values for stc_workspace_bytes */
-enum { STC_WS_ROUTE = 1, STC_WS_SELECT = 2, STC_WS_ATTENTION = 3, STC_WS_ATTENTION_TAIL = 4 };
+enum {
+  STC_WS_ROUTE = 1,
+  STC_WS_SELECT = 2,
+  STC_WS_ATTENTION = 3,
+  STC_WS_ATTENTION_TAIL = 4,
+  STC_WS_SELECT_PER_HEAD = 5,
+  STC_WS_ATTENTION_PER_HEAD = 6
+};
 
 /* routing modes of stc_route_and_pack_values */
 enum {
@@ -205,6 +212,25 @@ int stc_decode_attention_tail(const stc_shape_t *shape, const void *q, const voi
  */
 int stc_append_tail(const stc_shape_t *shape, const void *k_new, const void *v_new, void *K_tail,
                     void *V_tail, int n_tail, int tail_cap, void *stream);
+
+/*
+ * Per-query-head page selection and attention: the other reading of Quest under grouped-query
+ * attention.  Every query head scores the pages with its own upper bound U_h[p] (no maximum
+ * over the heads of its KV head), keeps its own k pages, and attends them; heads of one KV
+ * head then read that head's cache independently (pages chosen by several heads are read
+ * once per head).  For Hq == Hkv both calls equal stc_select_pages / stc_decode_attention.
+ *   page_idx   [B, Hq, k_eff] int32;  page_score [B, Hq, NP] float (may be NULL)
+ *   ws         stc_workspace_bytes(shape, STC_WS_SELECT_PER_HEAD / STC_WS_ATTENTION_PER_HEAD,
+ *              k_pages); B*Hq must not exceed 65535 for the attention call.
+ * Everything else as in the calls they mirror.
+ */
+int stc_select_pages_per_head(const stc_shape_t *shape, const void *q, const void *bounds,
+                              int k_pages, int32_t *page_idx, float *page_score, void *ws,
+                              size_t ws_bytes, void *stream);
+int stc_decode_attention_per_head(const stc_shape_t *shape, const void *q, const void *K,
+                                  const void *vpacked, const uint16_t *mask,
+                                  const uint32_t *tok_off, const int32_t *page_idx, int k_pages,
+                                  float *out, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Token-level compaction helper for caches reduced by a visual-token method

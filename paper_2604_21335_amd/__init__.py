@@ -18,11 +18,13 @@ LIB_PATH = os.path.join(_PKG_DIR, "libstc.so")
 STC_OK = 0
 STC_ERR_NULL, STC_ERR_SHAPE, STC_ERR_ALIGN, STC_ERR_WORKSPACE, STC_ERR_LAUNCH = -1, -2, -3, -4, -5
 STC_WS_ROUTE, STC_WS_SELECT, STC_WS_ATTENTION, STC_WS_ATTENTION_TAIL = 1, 2, 3, 4
+STC_WS_SELECT_PER_HEAD, STC_WS_ATTENTION_PER_HEAD = 5, 6
 STC_ROUTE_MASK, STC_ROUTE_TOPK, STC_ROUTE_GLOBAL = 0, 1, 2
 
 EXPORTS = ["stc_version", "stc_status_string", "stc_workspace_bytes", "stc_bounds_bytes",
            "stc_build_page_bounds",
            "stc_route_and_pack_values", "stc_select_pages", "stc_score_pages", "stc_decode_attention", "stc_decode_attention_tail", "stc_append_tail",
+           "stc_select_pages_per_head", "stc_decode_attention_per_head",
            "stc_compact_tokens"]
 
 
@@ -77,6 +79,10 @@ def load_library():
     lib.stc_score_pages.argtypes = [shp, vp, vp, vp, vp]
     lib.stc_decode_attention.restype = ctypes.c_int
     lib.stc_decode_attention.argtypes = [shp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp, sz, vp]
+    lib.stc_select_pages_per_head.restype = ctypes.c_int
+    lib.stc_select_pages_per_head.argtypes = lib.stc_select_pages.argtypes
+    lib.stc_decode_attention_per_head.restype = ctypes.c_int
+    lib.stc_decode_attention_per_head.argtypes = lib.stc_decode_attention.argtypes
     lib.stc_decode_attention_tail.restype = ctypes.c_int
     lib.stc_decode_attention_tail.argtypes = [shp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp,
                                               ctypes.c_int, ctypes.c_int, vp, vp, sz, vp]
@@ -184,6 +190,23 @@ def stc_decode_attention(shape, q, K, vpacked, mask, tok_off, page_idx, k_pages,
         _ptr(tok_off, _U32, "tok_off"), _ptr(page_idx, torch.int32, "page_idx"), int(k_pages),
         _ptr(out, torch.float32, "out"), _ptr(ws, None, "ws"), _nbytes(ws), _stream()),
         "stc_decode_attention")
+
+
+def stc_select_pages_per_head(shape, q, bounds, k_pages, page_idx, page_score, ws):
+    _check(load_library().stc_select_pages_per_head(
+        ctypes.byref(shape), _ptr(q, torch.bfloat16, "q"), _ptr(bounds, torch.bfloat16, "bounds"),
+        int(k_pages), _ptr(page_idx, torch.int32, "page_idx"),
+        _ptr(page_score, torch.float32, "page_score"), _ptr(ws, None, "ws"), _nbytes(ws),
+        _stream()), "stc_select_pages_per_head")
+
+
+def stc_decode_attention_per_head(shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, out, ws):
+    _check(load_library().stc_decode_attention_per_head(
+        ctypes.byref(shape), _ptr(q, torch.bfloat16, "q"), _ptr(K, torch.bfloat16, "K"),
+        _ptr(vpacked, torch.bfloat16, "vpacked"), _ptr(mask, _U16, "mask"),
+        _ptr(tok_off, _U32, "tok_off"), _ptr(page_idx, torch.int32, "page_idx"), int(k_pages),
+        _ptr(out, torch.float32, "out"), _ptr(ws, None, "ws"), _nbytes(ws), _stream()),
+        "stc_decode_attention_per_head")
 
 
 def stc_decode_attention_tail(shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, K_tail,

@@ -111,7 +111,7 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
     const uint32_t* __restrict__ tok_off, const int32_t* __restrict__ page_idx,
     float* __restrict__ partial, float* __restrict__ out, int Hq, int Hkv, int N, int NP, int G,
     uint32_t cap, int k_pages, int splits, const uint16_t* __restrict__ K_tail,
-    const uint16_t* __restrict__ V_tail, int n_tail, int tail_cap) {
+    const uint16_t* __restrict__ V_tail, int n_tail, int tail_cap, int kv_div) {
   using C = AttnCfg<D>;
   constexpr int ppw = 2 * PAIRS;  // pages per wavefront
   extern __shared__ __align__(16) unsigned char lds[];  // WAVES * C::WAVE_LDS bytes
@@ -132,15 +132,18 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
   STC_MARK(0, lane);
   if (lane < 4) *(uint32_t*)(wl + C::ZERO + lane * 4) = 0;
 
-  // per-stream bases (wave-uniform); everything below is addressed with 32-bit byte offsets
-  const unsigned char* Ks = (const unsigned char*)K + (size_t)stream * N * D * 2;
-  const unsigned char* mask_s = (const unsigned char*)mask + (size_t)stream * N * 2;
-  const unsigned char* off_s = (const unsigned char*)tok_off + (size_t)stream * (N + 1) * 4;
-  const unsigned char* vs = vpacked + (size_t)stream * (size_t)cap * gbytes;
+  // per-stream bases (wave-uniform); everything below is addressed with 32-bit byte offsets.
+  // kv_div > 1: the launch has one "stream" (page list, query, output) per query head and
+  // kv_div of them share the cache of one KV head.
+  const int kvs = stream / kv_div;
+  const unsigned char* Ks = (const unsigned char*)K + (size_t)kvs * N * D * 2;
+  const unsigned char* mask_s = (const unsigned char*)mask + (size_t)kvs * N * 2;
+  const unsigned char* off_s = (const unsigned char*)tok_off + (size_t)kvs * (N + 1) * 4;
+  const unsigned char* vs = vpacked + (size_t)kvs * (size_t)cap * gbytes;
   // the uncompressed tail: dense K and V rows, i.e. a packed store in which every token kept
   // every group; its pages follow the selected ones in the list of page slots
-  const unsigned char* Kts = (const unsigned char*)K_tail + (size_t)stream * tail_cap * D * 2;
-  const unsigned char* vts = (const unsigned char*)V_tail + (size_t)stream * tail_cap * D * 2;
+  const unsigned char* Kts = (const unsigned char*)K_tail + (size_t)kvs * tail_cap * D * 2;
+  const unsigned char* vts = (const unsigned char*)V_tail + (size_t)kvs * tail_cap * D * 2;
   const int tail_pages = TAIL ? (n_tail + kPage - 1) / kPage : 0;
   const uint32_t full_mask = (1u << G) - 1u;
 
@@ -543,16 +546,27 @@ static AttnPlan attention_plan(const stc_shape_t& s, int k_pages) {
 
 int attention_splits(const stc_shape_t& s, int k_pages) { return attention_plan(s, k_pages).splits; }
 
-size_t attention_ws_bytes(const stc_shape_t& s, int k_pages) {
+// The per-query-head form is the ordinary launch on a shape with one KV head per query head
+// (the kernel then maps kv_div of those onto one cache).
+static stc_shape_t launch_shape(const stc_shape_t& s, bool per_head) {
+  stc_shape_t t = s;
+  if (per_head) t.Hkv = s.Hq;
+  return t;
+}
+
+size_t attention_ws_bytes(const stc_shape_t& s0, int k_pages, bool per_head) {
+  const stc_shape_t s = launch_shape(s0, per_head);
   const int splits = attention_splits(s, k_pages);
   if (splits <= 1) return 0;
   return (size_t)s.B * s.Hq * splits * partial_stride(s.D) * sizeof(float);
 }
 
-int launch_attention(const stc_shape_t& s, const void* q, const void* K, const void* vpacked,
+int launch_attention(const stc_shape_t& s0, const void* q, const void* K, const void* vpacked,
                      const uint16_t* mask, const uint32_t* tok_off, const int32_t* page_idx,
                      int k_pages, const void* K_tail, const void* V_tail, int n_tail, int tail_cap,
-                     float* out, void* ws, hipStream_t st) {
+                     bool per_head, float* out, void* ws, hipStream_t st) {
+  const stc_shape_t s = launch_shape(s0, per_head);
+  const int kv_div = per_head ? s0.Hq / s0.Hkv : 1;
   const int NP = (s.N + kPage - 1) / kPage;
   const int streams = s.B * s.Hkv;
   const int tail_pages = (n_tail + kPage - 1) / kPage;
@@ -588,7 +602,7 @@ int launch_attention(const stc_shape_t& s, const void* q, const void* K, const v
     attn_mfma_kernel<DD, PP, WW, TT><<<grid, 64 * WW, lds_bytes, st>>>(                           \
         (const uint16_t*)q, (const uint16_t*)K, (const unsigned char*)vpacked, mask, tok_off,     \
         page_idx, partial, out, s.Hq, s.Hkv, s.N, NP, s.G, (uint32_t)s.v_cap_groups, k_pages,     \
-        splits, (const uint16_t*)K_tail, (const uint16_t*)V_tail, n_tail, tail_cap);              \
+        splits, (const uint16_t*)K_tail, (const uint16_t*)V_tail, n_tail, tail_cap, kv_div);      \
   }
 #ifdef STC_TUNE
 #define STC_ATTN_PICK(DD)                                  \

@@ -56,7 +56,9 @@ __device__ __forceinline__ bf16x4 as_bf16x4(uint32_t w0, uint32_t w1) {
 #define STC_SCORE_WAVES_PER_SIMD \
   amdgpu_waves_per_eu((D == 128 && R > 4) ? 3 : 4, (D == 128 && R > 4) ? 3 : 8)
 
-template <int D, int R>
+// PER_HEAD: every query head's own score is written ([B, Hq, NP]) instead of the maximum
+// over the heads of the KV head ([B, Hkv, NP]).
+template <int D, int R, bool PER_HEAD>
 __global__ __launch_bounds__(256) __attribute__((STC_SCORE_WAVES_PER_SIMD))
 void score_mfma_kernel(const u32x4* __restrict__ tiles, const uint16_t* __restrict__ q,
                        float* __restrict__ score, int NP, int Hq, int Hkv, int tiles_per_block) {
@@ -88,7 +90,7 @@ void score_mfma_kernel(const u32x4* __restrict__ tiles, const uint16_t* __restri
 
   const int t0 = blockIdx.x * tiles_per_block, t1 = min(t0 + tiles_per_block, ntiles);
   const u32x4* base = tiles + (size_t)stream * ntiles * T16 + lane;
-  float* out = score + (size_t)stream * NP;
+  float* out = score + (size_t)stream * (PER_HEAD ? R : 1) * NP;
   const int tlast = t1 - 1;
 
   // tile index past the block's range: its last tile is fetched again (never stored)
@@ -121,11 +123,19 @@ void score_mfma_kernel(const u32x4* __restrict__ tiles, const uint16_t* __restri
         _Pragma("unroll") for (int w = 1; w < CH; w *= 2)                                        \
           _Pragma("unroll") for (int c = 0; c < CH; c += 2 * w) v[c] += v[c + w];                \
         const float u = chunk_tree_sum(v[0]);                                                    \
-        best = (g == 0 && i == 0) ? u : fmaxf(best, u);                                          \
+        if (PER_HEAD) {                                                                          \
+          const int page = (tt) * kBoundsTilePages + 4 * (lane >> 5) + (lane & 3);               \
+          if ((lane & 0x1c) == kChunkSumLanes && page < NP)                                      \
+            out[(size_t)(4 * g + i) * NP + page] = u == 0.f ? 0.f : u;                           \
+        } else {                                                                                 \
+          best = (g == 0 && i == 0) ? u : fmaxf(best, u);                                        \
+        }                                                                                        \
       }                                                                                          \
     }                                                                                            \
-    const int page = (tt) * kBoundsTilePages + 4 * (lane >> 5) + (lane & 3);                     \
-    if ((lane & 0x1c) == kChunkSumLanes && page < NP) out[page] = best == 0.f ? 0.f : best;      \
+    if (!PER_HEAD) {                                                                             \
+      const int page = (tt) * kBoundsTilePages + 4 * (lane >> 5) + (lane & 3);                   \
+      if ((lane & 0x1c) == kChunkSumLanes && page < NP) out[page] = best == 0.f ? 0.f : best;    \
+    }                                                                                            \
   }
 
   // two tiles of this wavefront are always in flight behind the one being computed
@@ -151,7 +161,8 @@ template <int D>
 __global__ __launch_bounds__(256) void score_any_kernel(const u32x4* __restrict__ tiles,
                                                         const uint16_t* __restrict__ q,
                                                         float* __restrict__ score, int NP, int Hq,
-                                                        int Hkv, int R, int tiles_per_block) {
+                                                        int Hkv, int R, int tiles_per_block,
+                                                        int per_head) {
   constexpr int CH = D / 8, NJ = CH / 4, T16 = NJ * 64;
   const int stream = blockIdx.y;
   const int b = stream / Hkv, kvh = stream % Hkv;
@@ -160,7 +171,7 @@ __global__ __launch_bounds__(256) void score_any_kernel(const u32x4* __restrict_
   const int ntiles = (NP + kBoundsTilePages - 1) / kBoundsTilePages;
   const int t0 = blockIdx.x * tiles_per_block, t1 = min(t0 + tiles_per_block, ntiles);
   const u32x4* base = tiles + (size_t)stream * ntiles * T16 + lane;
-  float* out = score + (size_t)stream * NP;
+  float* out = score + (size_t)stream * (per_head ? R : 1) * NP;
   for (int t = t0 + wave; t < t1; t += 4) {
     uint32_t w[CH];
 #pragma unroll
@@ -169,6 +180,8 @@ __global__ __launch_bounds__(256) void score_any_kernel(const u32x4* __restrict_
       w[4 * j] = v.x, w[4 * j + 1] = v.y, w[4 * j + 2] = v.z, w[4 * j + 3] = v.w;
     }
     float best = 0.f;
+    const int page = t * kBoundsTilePages + 4 * (lane >> 5) + (lane & 3);
+    const bool writer = (lane & 0x1c) == kChunkSumLanes && page < NP;
     for (int h = 0; h < R; ++h) {
       const uint16_t* qp = q + ((size_t)b * Hq + kvh * R + h) * D + e * CH;
       float v[CH];
@@ -182,16 +195,16 @@ __global__ __launch_bounds__(256) void score_any_kernel(const u32x4* __restrict_
 #pragma unroll
         for (int c = 0; c < CH; c += 2 * s) v[c] += v[c + s];
       const float u = chunk_tree_sum(v[0]);
+      if (per_head && writer) out[(size_t)h * NP + page] = u == 0.f ? 0.f : u;
       best = h == 0 ? u : fmaxf(best, u);
     }
-    const int page = t * kBoundsTilePages + 4 * (lane >> 5) + (lane & 3);
-    if ((lane & 0x1c) == kChunkSumLanes && page < NP) out[page] = best == 0.f ? 0.f : best;
+    if (!per_head && writer) out[page] = best == 0.f ? 0.f : best;
   }
 }
 
 template <int D>
 static void launch_score_d(const stc_shape_t& s, const void* q, const void* bounds, float* score,
-                           int NP, hipStream_t st) {
+                           int NP, bool per_head, hipStream_t st) {
   const int streams = s.B * s.Hkv;
   const int R = s.Hq / s.Hkv;
   const int ntiles = (NP + kBoundsTilePages - 1) / kBoundsTilePages;
@@ -205,7 +218,12 @@ static void launch_score_d(const stc_shape_t& s, const void* q, const void* boun
   const uint16_t* q16 = (const uint16_t*)q;
 #define STC_SCORE_CASE(RR)                                                                  \
   case RR:                                                                                  \
-    score_mfma_kernel<D, RR><<<grid, 256, 0, st>>>(t4, q16, score, NP, s.Hq, s.Hkv, tpb);   \
+    if (per_head)                                                                           \
+      score_mfma_kernel<D, RR, true><<<grid, 256, 0, st>>>(t4, q16, score, NP, s.Hq, s.Hkv, \
+                                                           tpb);                            \
+    else                                                                                    \
+      score_mfma_kernel<D, RR, false><<<grid, 256, 0, st>>>(t4, q16, score, NP, s.Hq,       \
+                                                            s.Hkv, tpb);                    \
     break;
   switch (R) {
     STC_SCORE_CASE(1)
@@ -217,18 +235,19 @@ static void launch_score_d(const stc_shape_t& s, const void* q, const void* boun
     STC_SCORE_CASE(7)
     STC_SCORE_CASE(8)
     default:
-      score_any_kernel<D><<<grid, 256, 0, st>>>(t4, q16, score, NP, s.Hq, s.Hkv, R, tpb);
+      score_any_kernel<D><<<grid, 256, 0, st>>>(t4, q16, score, NP, s.Hq, s.Hkv, R, tpb,
+                                                per_head ? 1 : 0);
   }
 #undef STC_SCORE_CASE
 }
 
 int launch_score(const stc_shape_t& s, const void* q, const void* bounds, float* score,
-                 hipStream_t st) {
+                 bool per_head, hipStream_t st) {
   const int NP = (s.N + kPage - 1) / kPage;
   if (s.D == 128)
-    launch_score_d<128>(s, q, bounds, score, NP, st);
+    launch_score_d<128>(s, q, bounds, score, NP, per_head, st);
   else
-    launch_score_d<64>(s, q, bounds, score, NP, st);
+    launch_score_d<64>(s, q, bounds, score, NP, per_head, st);
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

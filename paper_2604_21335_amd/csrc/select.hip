@@ -246,15 +246,15 @@ __global__ void iota_pages_kernel(int32_t* __restrict__ page_idx, int NP, int to
 }
 
 int launch_select(const stc_shape_t& s, const void* q, const void* bounds, int k_pages,
-                  int32_t* page_idx, float* score, hipStream_t st) {
+                  int32_t* page_idx, float* score, bool per_head, hipStream_t st) {
   const int NP = (s.N + kPage - 1) / kPage;
-  const int streams = s.B * s.Hkv;
+  const int streams = s.B * (per_head ? s.Hq : s.Hkv);  // page lists to produce
   if (k_pages >= NP) {
     const int total = streams * NP;
     iota_pages_kernel<<<(total + 255) / 256, 256, 0, st>>>(page_idx, NP, total);
     return hipGetLastError() == hipSuccess ? 0 : -1;
   }
-  if (launch_score(s, q, bounds, score, st)) return -1;
+  if (launch_score(s, q, bounds, score, per_head, st)) return -1;
   // keys per thread; streams of more than 1024 pages use 512 threads (measured: faster than
   // both 256 threads with more keys each and 1024 threads with longer barriers)
 #define STC_TOPK(IPT, TH) \

@@ -25,8 +25,8 @@ bool shape_ok(const stc_shape_t* s) {
 
 int num_pages(const stc_shape_t* s) { return (s->N + s->P - 1) / s->P; }
 
-size_t select_ws_bytes(const stc_shape_t* s) {
-  return (size_t)s->B * s->Hkv * num_pages(s) * sizeof(float);
+size_t select_ws_bytes(const stc_shape_t* s, bool per_head = false) {
+  return (size_t)s->B * (per_head ? s->Hq : s->Hkv) * num_pages(s) * sizeof(float);
 }
 
 }  // namespace
@@ -58,6 +58,11 @@ size_t stc_workspace_bytes(const stc_shape_t* shape, int which_call, int k_pages
     case STC_WS_ATTENTION_TAIL:  // k_pages counts the tail's pages too
       if (k_pages < 1) return 0;
       return stc::attention_ws_bytes(*shape, k_pages);
+    case STC_WS_SELECT_PER_HEAD:
+      return k_pages >= num_pages(shape) ? 0 : select_ws_bytes(shape, true);
+    case STC_WS_ATTENTION_PER_HEAD:
+      if (k_pages < 1 || k_pages > num_pages(shape)) return 0;
+      return stc::attention_ws_bytes(*shape, k_pages, true);
     default: return 0;
   }
 }
@@ -103,9 +108,11 @@ int stc_route_and_pack_values(const stc_shape_t* shape, int mode, const void* V,
              : STC_OK;
 }
 
-int stc_select_pages(const stc_shape_t* shape, const void* q, const void* bounds, int k_pages,
-                     int32_t* page_idx, float* page_score, void* ws, size_t ws_bytes,
-                     void* stream) {
+namespace {
+
+int select_pages_impl(const stc_shape_t* shape, const void* q, const void* bounds, int k_pages,
+                      int32_t* page_idx, float* page_score, void* ws, size_t ws_bytes,
+                      bool per_head, void* stream) {
   if (!shape || !page_idx) return STC_ERR_NULL;
   if (!shape_ok(shape) || k_pages < 1) return STC_ERR_SHAPE;
   if (!aligned16(page_idx)) return STC_ERR_ALIGN;
@@ -115,13 +122,31 @@ int stc_select_pages(const stc_shape_t* shape, const void* q, const void* bounds
     if (!aligned16(q) || !aligned16(bounds) || (page_score && !aligned16(page_score)))
       return STC_ERR_ALIGN;
     if (!score) {
-      if (!ws || ws_bytes < select_ws_bytes(shape) || !aligned16(ws)) return STC_ERR_WORKSPACE;
+      if (!ws || ws_bytes < select_ws_bytes(shape, per_head) || !aligned16(ws))
+        return STC_ERR_WORKSPACE;
       score = (float*)ws;
     }
   }
-  return stc::launch_select(*shape, q, bounds, k_pages, page_idx, score, (hipStream_t)stream)
+  return stc::launch_select(*shape, q, bounds, k_pages, page_idx, score, per_head,
+                            (hipStream_t)stream)
              ? STC_ERR_LAUNCH
              : STC_OK;
+}
+
+}  // namespace
+
+int stc_select_pages(const stc_shape_t* shape, const void* q, const void* bounds, int k_pages,
+                     int32_t* page_idx, float* page_score, void* ws, size_t ws_bytes,
+                     void* stream) {
+  return select_pages_impl(shape, q, bounds, k_pages, page_idx, page_score, ws, ws_bytes, false,
+                           stream);
+}
+
+int stc_select_pages_per_head(const stc_shape_t* shape, const void* q, const void* bounds,
+                              int k_pages, int32_t* page_idx, float* page_score, void* ws,
+                              size_t ws_bytes, void* stream) {
+  return select_pages_impl(shape, q, bounds, k_pages, page_idx, page_score, ws, ws_bytes, true,
+                           stream);
 }
 
 int stc_score_pages(const stc_shape_t* shape, const void* q, const void* bounds,
@@ -129,7 +154,7 @@ int stc_score_pages(const stc_shape_t* shape, const void* q, const void* bounds,
   if (!shape || !q || !bounds || !page_score) return STC_ERR_NULL;
   if (!shape_ok(shape)) return STC_ERR_SHAPE;
   if (!aligned16(q) || !aligned16(bounds) || !aligned16(page_score)) return STC_ERR_ALIGN;
-  return stc::launch_score(*shape, q, bounds, page_score, (hipStream_t)stream) ? STC_ERR_LAUNCH
+  return stc::launch_score(*shape, q, bounds, page_score, false, (hipStream_t)stream) ? STC_ERR_LAUNCH
                                                                                : STC_OK;
 }
 
@@ -138,8 +163,8 @@ namespace {
 int decode_attention_impl(const stc_shape_t* shape, const void* q, const void* K,
                           const void* vpacked, const uint16_t* mask, const uint32_t* tok_off,
                           const int32_t* page_idx, int k_pages, const void* K_tail,
-                          const void* V_tail, int n_tail, int tail_cap, float* out, void* ws,
-                          size_t ws_bytes, void* stream) {
+                          const void* V_tail, int n_tail, int tail_cap, bool per_head, float* out,
+                          void* ws, size_t ws_bytes, void* stream) {
   if (!shape || !q || !K || !vpacked || !mask || !tok_off || !page_idx || !out)
     return STC_ERR_NULL;
   if (!shape_ok(shape) || k_pages < 1 || k_pages > num_pages(shape) || shape->v_cap_groups < 1)
@@ -157,10 +182,11 @@ int decode_attention_impl(const stc_shape_t* shape, const void* q, const void* K
       (n_tail > 0 && (!aligned16(K_tail) || !aligned16(V_tail))))
     return STC_ERR_ALIGN;
   const int slots = k_pages + (n_tail + shape->P - 1) / shape->P;
-  const size_t need = stc::attention_ws_bytes(*shape, slots);
+  if (per_head && (long long)shape->B * shape->Hq > kMaxGridY) return STC_ERR_SHAPE;
+  const size_t need = stc::attention_ws_bytes(*shape, slots, per_head);
   if (need && (!ws || ws_bytes < need || !aligned16(ws))) return STC_ERR_WORKSPACE;
   return stc::launch_attention(*shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, K_tail,
-                               V_tail, n_tail, tail_cap, out, ws, (hipStream_t)stream)
+                               V_tail, n_tail, tail_cap, per_head, out, ws, (hipStream_t)stream)
              ? STC_ERR_LAUNCH
              : STC_OK;
 }
@@ -172,7 +198,15 @@ int stc_decode_attention(const stc_shape_t* shape, const void* q, const void* K,
                          const int32_t* page_idx, int k_pages, float* out, void* ws,
                          size_t ws_bytes, void* stream) {
   return decode_attention_impl(shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, nullptr,
-                               nullptr, 0, 0, out, ws, ws_bytes, stream);
+                               nullptr, 0, 0, false, out, ws, ws_bytes, stream);
+}
+
+int stc_decode_attention_per_head(const stc_shape_t* shape, const void* q, const void* K,
+                                  const void* vpacked, const uint16_t* mask,
+                                  const uint32_t* tok_off, const int32_t* page_idx, int k_pages,
+                                  float* out, void* ws, size_t ws_bytes, void* stream) {
+  return decode_attention_impl(shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, nullptr,
+                               nullptr, 0, 0, true, out, ws, ws_bytes, stream);
 }
 
 int stc_decode_attention_tail(const stc_shape_t* shape, const void* q, const void* K,
@@ -181,7 +215,7 @@ int stc_decode_attention_tail(const stc_shape_t* shape, const void* q, const voi
                               const void* V_tail, int n_tail, int tail_cap, float* out, void* ws,
                               size_t ws_bytes, void* stream) {
   return decode_attention_impl(shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, K_tail,
-                               V_tail, n_tail, tail_cap, out, ws, ws_bytes, stream);
+                               V_tail, n_tail, tail_cap, false, out, ws, ws_bytes, stream);
 }
 
 int stc_append_tail(const stc_shape_t* shape, const void* k_new, const void* v_new, void* K_tail,

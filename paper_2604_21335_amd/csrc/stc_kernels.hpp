@@ -20,17 +20,18 @@ int launch_route_pack(const stc_shape_t& s, int mode, const void* V, const float
                       uint32_t* tok_off, void* vpacked, int32_t* dev_status, void* ws,
                       hipStream_t st);
 
+// per_head: one score row per query head ([B, Hq, NP]) instead of one per KV head
 int launch_score(const stc_shape_t& s, const void* q, const void* bounds, float* score,
-                 hipStream_t st);
+                 bool per_head, hipStream_t st);
 int launch_select(const stc_shape_t& s, const void* q, const void* bounds, int k_pages,
-                  int32_t* page_idx, float* score, hipStream_t st);
+                  int32_t* page_idx, float* score, bool per_head, hipStream_t st);
 
 int attention_splits(const stc_shape_t& s, int k_pages);
-size_t attention_ws_bytes(const stc_shape_t& s, int k_pages);
+size_t attention_ws_bytes(const stc_shape_t& s, int k_pages, bool per_head = false);
 int launch_attention(const stc_shape_t& s, const void* q, const void* K, const void* vpacked,
                      const uint16_t* mask, const uint32_t* tok_off, const int32_t* page_idx,
                      int k_pages, const void* K_tail, const void* V_tail, int n_tail, int tail_cap,
-                     float* out, void* ws, hipStream_t st);
+                     bool per_head, float* out, void* ws, hipStream_t st);
 int launch_append_tail(const stc_shape_t& s, const void* k_new, const void* v_new, void* K_tail,
                        void* V_tail, int n_tail, int tail_cap, hipStream_t st);
 

@@ -111,6 +111,17 @@ def test_null_alignment_and_workspace_errors():
     assert lib.stc_append_tail(r, FAKE, FAKE, FAKE, FAKE, 8, 8, None) == stc.STC_ERR_SHAPE
     assert lib.stc_append_tail(r, FAKE, None, FAKE, FAKE, 0, 8, None) == stc.STC_ERR_NULL
     assert lib.stc_append_tail(r, ODD, FAKE, FAKE, FAKE, 0, 8, None) == stc.STC_ERR_ALIGN
+    # per-head calls: same checks, their own workspace sizes
+    assert lib.stc_select_pages_per_head(r, FAKE, FAKE, 2, FAKE, None, None, 0,
+                                         None) == stc.STC_ERR_WORKSPACE
+    assert lib.stc_select_pages_per_head(r, None, FAKE, 2, FAKE, None, FAKE, big,
+                                         None) == stc.STC_ERR_NULL
+    assert stc.stc_workspace_bytes(s, stc.STC_WS_SELECT_PER_HEAD, 2) == 2 * 8 * 7 * 4
+    assert stc.stc_workspace_bytes(s, stc.STC_WS_SELECT, 2) == 2 * 2 * 7 * 4
+    assert lib.stc_decode_attention_per_head(r, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 8, FAKE, FAKE,
+                                             big, None) == stc.STC_ERR_SHAPE
+    assert lib.stc_decode_attention_per_head(r, FAKE, FAKE, FAKE, FAKE, FAKE, ODD, 7, FAKE, FAKE,
+                                             big, None) == stc.STC_ERR_ALIGN
     # compact
     assert lib.stc_compact_tokens(FAKE, FAKE, FAKE, 1, 1, 10, 4, 100, None, None) == stc.STC_ERR_SHAPE
     assert lib.stc_compact_tokens(FAKE, None, FAKE, 1, 1, 10, 4, 128, None, None) == stc.STC_ERR_NULL

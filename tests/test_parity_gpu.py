@@ -222,6 +222,45 @@ def test_append_then_attend_step_by_step():
     assert np.array_equal(PT.host_bf16(c.V_tail)[:, :, :steps], new_v.transpose(1, 2, 0, 3))
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,D,N,G,k", [
+    (2, 14, 2, 128, 3000, 8, 20), (1, 8, 2, 64, 1000, 4, 9), (2, 4, 4, 128, 700, 8, 5),
+    (1, 12, 1, 128, 2048, 8, 100), (1, 16, 1, 64, 500, 2, 30)])
+def test_per_head_selection_and_attention(B, Hq, Hkv, D, N, G, k):
+    """Every query head selects and attends its own pages: scores and indices bit for bit per
+    head, output within the bar; for MHA the calls equal the shared ones bit for bit."""
+    K, V, q, logits, kcount = _rand_case(100 + Hq, B, Hq, Hkv, D, N, G, outliers=True)
+    hip = PT.run_hip(K, V, q, G, k, logits=logits, kcount=kcount)
+    c = hip["cache"]
+    NP = (N + 15) // 16
+    dq = PT.to_dev_bf16(q)
+    dev = "cuda:0"
+    idx = torch.full((B, Hq, k), -9, dtype=torch.int32, device=dev)
+    score = torch.full((B, Hq, NP), float("nan"), dtype=torch.float32, device=dev)
+    ws_s = torch.empty(max(16, stc.stc_workspace_bytes(c.shape, stc.STC_WS_SELECT_PER_HEAD, k)),
+                       dtype=torch.uint8, device=dev)
+    ws_a = torch.empty(max(16, stc.stc_workspace_bytes(c.shape, stc.STC_WS_ATTENTION_PER_HEAD, k)),
+                       dtype=torch.uint8, device=dev)
+    out = torch.full((B, Hq, D), float("nan"), dtype=torch.float32, device=dev)
+    stc.stc_select_pages_per_head(c.shape, dq, c.bounds, k, idx, score, ws_s)
+    stc.stc_decode_attention_per_head(c.shape, dq, c.K, c.vpacked, c.mask, c.tok_off, idx, k, out,
+                                      ws_a)
+    idx2 = torch.full_like(idx, -9)
+    stc.stc_select_pages_per_head(c.shape, dq, c.bounds, k, idx2, None, ws_s)  # scores in ws
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx2)
+    bounds = O.build_page_bounds_all(K)
+    want_idx, want_score = O.select_pages_per_head_all(q, bounds, k)
+    assert np.array_equal(score.cpu().numpy().view(np.uint32), want_score.view(np.uint32))
+    assert np.array_equal(idx.cpu().numpy(), want_idx)
+    want = O.decode_attention_per_head_all(q, K, V, hip["mask"], want_idx, G)
+    assert np.abs(out.cpu().numpy() - want).max() < PT.TIGHT
+    if Hq == Hkv:
+        assert np.array_equal(idx.cpu().numpy(), hip["page_idx"])
+        assert np.array_equal(out.cpu().numpy(), hip["out"])
+    else:
+        assert not np.array_equal(want_idx[:, 0], want_idx[:, 1])   # heads really differ
+
+
 def test_score_pages_alone_matches_oracle_bits():
     B, Hq, Hkv, D, N, G = 2, 14, 2, 128, 3000, 8
     K, V, q, logits, kcount = _rand_case(21, B, Hq, Hkv, D, N, G, outliers=True)
