@@ -12,6 +12,16 @@
  * queries and keys are never compressed, dropped groups contribute nothing and
  * the softmax is not renormalised over kept groups.
  *
+ * Calls
+ *   cache construction   stc_build_page_bounds, stc_route_and_pack_values (per-token top-K,
+ *                        given masks, or the global token-group budget of the LLM setting),
+ *                        stc_compact_tokens (token-level compaction helper)
+ *   decode step          stc_select_pages (+ stc_score_pages: its scoring half alone),
+ *                        stc_decode_attention
+ *   recent tokens        stc_append_tail, stc_decode_attention_tail (uncompressed tail)
+ *   per-query-head form  stc_select_pages_per_head, stc_decode_attention_per_head
+ *   helpers              stc_workspace_bytes, stc_bounds_bytes, stc_status_string, stc_version
+ *
  * Conventions shared by every call
  *   - "stream" = one (batch b, KV head h) pair; streams are independent.
  *     Query head j belongs to KV head j / (Hq/Hkv).
