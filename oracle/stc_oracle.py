@@ -11,6 +11,8 @@ What each routine follows (paper = "Sub-Token Routing for KV Cache Compression")
                     reduction to Quest with chunk size 16 (App. C.1, LLM
                     training-config table).  Quest's page summary is the
                     per-page, per-channel min and max of the cached keys.
+  router_logits     App. B.1 "Value-Group Router": a single linear projection from
+                    the layer-input hidden state of a token to its S group logits.
   route_mask        Sec. 3.3 "Routing mask": the top-K of the S group logits of
                     a token give a binary mask m[i,j]; App. B.1 gives the fixed
                     per-token K used for VLMs.  Here the count may differ per
@@ -40,6 +42,11 @@ Readings where the paper is silent (also listed in the design notes):
   * page score arithmetic: every product is formed in float32 (exact for two
     bf16 factors), the D terms are summed in float32 by a balanced tree over
     adjacent channels (c0+c1), (c2+c3), ... repeated until one value is left.
+  * router logits: float32; products of two bf16 factors are exact; the d_model
+    terms are summed in chunks of 128 adjacent channels, each chunk by the
+    balanced adjacent-pair tree, the chunk sums accumulated left to right; an
+    optional float32 bias is added last.  (Masks are integer decisions taken on
+    these logits, so the order is part of the definition.)
   * GQA: one page set per KV head; its score is the max over the query heads of
     that group.  Ties in every top-k go to the lowest index.  A zero score is +0.
   * the selected pages are listed in ascending page order.
@@ -113,6 +120,27 @@ def page_bounds(K_bits, P=16):
 # --------------------------------------------------------------------------- #
 # Routing mask, offsets, packing (Sec. 3.3)
 # --------------------------------------------------------------------------- #
+def router_logits(h_bits, W_bits, bias=None):
+    """h_bits[N, d_model], W_bits[G, d_model] (bf16 bits), bias[G] float32 or None
+    -> logits[N, G] float32 = h W^T (+ bias), in the order stated in the header."""
+    h = bf16_to_f32(h_bits)                                   # [N, dm]
+    W = bf16_to_f32(W_bits)                                   # [G, dm]
+    N, dm = h.shape
+    G = W.shape[0]
+    assert dm % 128 == 0, "d_model must be a multiple of 128"
+    nc = dm // 128
+    acc = np.zeros((N, G), dtype=np.float32)
+    for c in range(nc):
+        sl = slice(c * 128, (c + 1) * 128)
+        term = (h[:, None, sl] * W[None, :, sl]).astype(np.float32)   # exact products
+        while term.shape[-1] > 1:
+            term = (term[..., 0::2] + term[..., 1::2]).astype(np.float32)
+        acc = (acc + term[..., 0]).astype(np.float32)
+    if bias is not None:
+        acc = (acc + np.asarray(bias, dtype=np.float32)[None, :]).astype(np.float32)
+    return acc
+
+
 def route_mask(logits, kcount):
     """logits[N, G] float32, kcount[N] -> mask[N] uint16.
 

@@ -597,3 +597,59 @@ def test_per_head_attention_wrapper_uses_each_heads_pages():
         want = O.decode_attention(q[0, j:j + 1], K[0, j // 2], V[0, j // 2], mask[0, j // 2],
                                   idx[0, j], G)
         assert np.array_equal(out[0, j:j + 1], want)
+
+
+# --- router logits (App. B.1: one linear projection from the hidden state to S logits) -----
+
+def test_router_logits_exact_on_small_integers_and_close_to_float64():
+    rng = np.random.default_rng(80)
+    N, dm, G = 37, 384, 8
+    h, W = ints_bf16(rng, (N, dm), -4, 4), ints_bf16(rng, (G, dm), -4, 4)
+    bias = rng.integers(-5, 6, size=G).astype(np.float32)
+    got = O.router_logits(h, W, bias)
+    want = bits_to_f64(h) @ bits_to_f64(W).T + bias            # integers: exact in any order
+    assert got.dtype == np.float32 and np.array_equal(got.astype(np.float64), want)
+    h, W = randn_bf16(rng, (N, dm)), randn_bf16(rng, (G, dm))
+    got = O.router_logits(h, W)
+    want = bits_to_f64(h) @ bits_to_f64(W).T
+    assert np.abs(got - want).max() < 1e-4 * np.abs(want).max()
+    # transposed operands or a dropped chunk would not survive this
+    assert np.abs(O.router_logits(h[:, :128], W[:, :128]) - want).max() > 1.0
+
+
+def test_router_logits_summation_order():
+    """Within a chunk of 128 channels: balanced adjacent-pair tree.  Across chunks: left to
+    right.  With e = 2^-24 (half an ulp of 1.0f) the two orders round differently."""
+    e = 2.0 ** -24
+    one = f32_to_bf16_bits(np.float32(1.0))
+    def row(vals, dm):
+        r = np.zeros(dm, dtype=np.float32)
+        for i, v in vals.items():
+            r[i] = v
+        return f32_to_bf16_bits(r)
+    W = np.full((1, 256), one, dtype=np.uint16)
+    # chunk sums 1, e... : terms (1, 1.5e, e, 3e) at channels 0..3 of chunk 0, as in the page
+    # score pin: tree gives (1 + 1.5e) + (e + 3e) = (1 + 2e) + 4e = 1 + 6e -> 1 + 3u (u = 2e)
+    h = row({0: 1.0, 1: 1.5 * e, 2: e, 3: 3 * e}, 256)[None]
+    assert float(O.router_logits(h, W)[0, 0]) == 1.0 + 6 * e
+    # left to right over the four terms would give ((1 + 1.5e) + e) + 3e = (1+2e) + e -> 1+2e, +3e
+    assert float(np.float32(np.float32(np.float32(np.float32(1.0) + np.float32(1.5 * e))
+                                       + np.float32(e)) + np.float32(3 * e))) != 1.0 + 6 * e
+    # across chunks: chunk sums (1, e, e): left to right (1 + e) + e = 1 (ties to even, twice);
+    # a tree over the chunks would give 1 + (e + e) = 1 + 2e
+    W3 = np.full((1, 384), one, dtype=np.uint16)
+    h3 = row({0: 1.0, 128: e, 256: e}, 384)[None]
+    assert float(O.router_logits(h3, W3)[0, 0]) == 1.0
+    # the bias is added after the last chunk
+    assert float(O.router_logits(h3, W3, np.array([2 * e], dtype=np.float32))[0, 0]) == 1.0 + 2 * e
+
+
+def test_router_then_routing_pipeline():
+    rng = np.random.default_rng(81)
+    N, dm, G = 50, 256, 4
+    h, W = randn_bf16(rng, (N, dm)), randn_bf16(rng, (G, dm))
+    a = O.router_logits(h, W)
+    m = O.route_mask(a, 2)
+    top2 = np.argsort(-a, axis=1, kind="stable")[:, :2]
+    want = (1 << top2[:, 0]) | (1 << top2[:, 1])
+    assert np.array_equal(m, want.astype(np.uint16))
