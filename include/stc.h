@@ -15,7 +15,8 @@
  * Calls
  *   cache construction   stc_build_page_bounds, stc_route_and_pack_values (per-token top-K,
  *                        given masks, or the global token-group budget of the LLM setting),
- *                        stc_compact_tokens (token-level compaction helper)
+ *                        stc_router_logits (the router's projection), stc_compact_tokens
+ *                        (token-level compaction helper)
  *   decode step          stc_select_pages (+ stc_score_pages: its scoring half alone),
  *                        stc_decode_attention
  *   recent tokens        stc_append_tail, stc_decode_attention_tail (uncompressed tail)
@@ -241,6 +242,23 @@ int stc_decode_attention_per_head(const stc_shape_t *shape, const void *q, const
                                   const void *vpacked, const uint16_t *mask,
                                   const uint32_t *tok_off, const int32_t *page_idx, int k_pages,
                                   float *out, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Value-group router (App. B.1: a single linear projection from the layer-input hidden state
+ * to the S group logits), for feeding stc_route_and_pack_values:
+ *   logits[b, kvh, t, g] = sum_c h[b, t, c] * W[g, c] (+ bias[g]), the same for every kvh
+ *   (the router gives one mask per token and layer).
+ * Float arithmetic in a fixed order, because masks are decided on these numbers: chunks of
+ * 128 adjacent channels are summed as a balanced tree over adjacent channels, chunk sums are
+ * accumulated left to right, the bias is added last.
+ *   h      [B, N, d_model] bf16, in; d_model a multiple of 128
+ *   W      [G, d_model] bf16, in; G in {1, 2, 4, 8, 16}
+ *   bias   [G] float, in, may be NULL
+ *   logits [B, Hkv, N, G] float, out
+ */
+int stc_router_logits(int32_t B, int32_t Hkv, int32_t N, int32_t d_model, int32_t G,
+                      const void *h, const void *W, const float *bias, float *logits,
+                      void *stream);
 
 /*
  * Token-level compaction helper for caches reduced by a visual-token method

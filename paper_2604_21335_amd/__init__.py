@@ -24,7 +24,7 @@ STC_ROUTE_MASK, STC_ROUTE_TOPK, STC_ROUTE_GLOBAL = 0, 1, 2
 EXPORTS = ["stc_version", "stc_status_string", "stc_workspace_bytes", "stc_bounds_bytes",
            "stc_build_page_bounds",
            "stc_route_and_pack_values", "stc_select_pages", "stc_score_pages", "stc_decode_attention", "stc_decode_attention_tail", "stc_append_tail",
-           "stc_select_pages_per_head", "stc_decode_attention_per_head",
+           "stc_select_pages_per_head", "stc_decode_attention_per_head", "stc_router_logits",
            "stc_compact_tokens"]
 
 
@@ -88,6 +88,8 @@ def load_library():
                                               ctypes.c_int, ctypes.c_int, vp, vp, sz, vp]
     lib.stc_append_tail.restype = ctypes.c_int
     lib.stc_append_tail.argtypes = [shp, vp, vp, vp, vp, ctypes.c_int, ctypes.c_int, vp]
+    lib.stc_router_logits.restype = ctypes.c_int
+    lib.stc_router_logits.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
     lib.stc_compact_tokens.restype = ctypes.c_int
     lib.stc_compact_tokens.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
     _lib = lib
@@ -226,6 +228,17 @@ def stc_append_tail(shape, k_new, v_new, K_tail, V_tail, n_tail, tail_cap):
         _ptr(v_new, torch.bfloat16, "v_new"), _ptr(K_tail, torch.bfloat16, "K_tail"),
         _ptr(V_tail, torch.bfloat16, "V_tail"), int(n_tail), int(tail_cap), _stream()),
         "stc_append_tail")
+
+
+def stc_router_logits(h, W, bias, logits, Hkv):
+    """h [B, N, d_model] bf16, W [G, d_model] bf16, bias [G] float32 or None ->
+    logits [B, Hkv, N, G] float32 (the same for every KV head)."""
+    B, N, dm = h.shape
+    G = W.shape[0]
+    _check(load_library().stc_router_logits(
+        B, Hkv, N, dm, G, _ptr(h, torch.bfloat16, "h"), _ptr(W, torch.bfloat16, "W"),
+        _ptr(bias, torch.float32, "bias"), _ptr(logits, torch.float32, "logits"), _stream()),
+        "stc_router_logits")
 
 
 def stc_compact_tokens(src, token_idx, dst, B, Hkv, N_src, n_keep, D, dev_status=None):

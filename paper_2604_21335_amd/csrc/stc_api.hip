@@ -230,6 +230,21 @@ int stc_append_tail(const stc_shape_t* shape, const void* k_new, const void* v_n
              : STC_OK;
 }
 
+int stc_router_logits(int32_t B, int32_t Hkv, int32_t N, int32_t d_model, int32_t G,
+                      const void* h, const void* W, const float* bias, float* logits,
+                      void* stream) {
+  if (!h || !W || !logits) return STC_ERR_NULL;
+  if (B < 1 || Hkv < 1 || N < 1 || d_model < 128 || d_model % 128 != 0 || B > kMaxGridY ||
+      !(G == 1 || G == 2 || G == 4 || G == 8 || G == 16))
+    return STC_ERR_SHAPE;
+  if (!aligned16(h) || !aligned16(W) || !aligned16(logits) || (bias && ((uintptr_t)bias & 3)))
+    return STC_ERR_ALIGN;
+  return stc::launch_router_logits(h, W, bias, logits, B, Hkv, N, d_model, G,
+                                   (hipStream_t)stream)
+             ? STC_ERR_LAUNCH
+             : STC_OK;
+}
+
 int stc_compact_tokens(const void* src, const int32_t* token_idx, void* dst, int32_t B,
                        int32_t Hkv, int32_t N_src, int32_t n_keep, int32_t D,
                        int32_t* dev_status, void* stream) {

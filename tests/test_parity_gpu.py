@@ -261,6 +261,35 @@ def test_per_head_selection_and_attention(B, Hq, Hkv, D, N, G, k):
         assert not np.array_equal(want_idx[:, 0], want_idx[:, 1])   # heads really differ
 
 
+@pytest.mark.parametrize("B,Hkv,N,dm,G,with_bias", [(2, 2, 301, 512, 8, True), (1, 3, 64, 128, 4, False),
+                                                     (1, 1, 1000, 3584, 8, True),
+                                                     (2, 1, 77, 256, 16, False), (1, 2, 50, 384, 1, True)])
+def test_router_logits_bits_and_routing(B, Hkv, N, dm, G, with_bias):
+    """The router's projection bit for bit (the order of its float additions is part of the
+    definition), replicated over the KV heads; masks routed from it equal the oracle's."""
+    rng = np.random.default_rng(110 + dm)
+    h, Wr = randn_bf16(rng, (B, N, dm)), randn_bf16(rng, (G, dm))
+    bias = rng.standard_normal(G).astype(np.float32) if with_bias else None
+    dev = "cuda:0"
+    logits = torch.full((B, Hkv, N, G), float("nan"), dtype=torch.float32, device=dev)
+    stc.stc_router_logits(PT.to_dev_bf16(h), PT.to_dev_bf16(Wr),
+                          None if bias is None else torch.from_numpy(bias).to(dev), logits, Hkv)
+    torch.cuda.synchronize()
+    got = logits.cpu().numpy()
+    for b in range(B):
+        want = O.router_logits(h[b], Wr, bias)
+        for kvh in range(Hkv):
+            assert np.array_equal(got[b, kvh].view(np.uint32), want.view(np.uint32))
+    if G >= 4:                                      # logits -> global-budget masks, end to end
+        D = 128
+        K, V, q, _, _ = _rand_case(111, B, Hkv, Hkv, D, N, G)
+        hip = PT.run_hip(K, V, q, G, 3, logits=got, global_k=2)
+        for b in range(B):
+            m = O.route_mask_global(O.router_logits(h[b], Wr, bias), 2 * N)
+            for kvh in range(Hkv):
+                assert np.array_equal(hip["mask"][b, kvh], m)
+
+
 def test_score_pages_alone_matches_oracle_bits():
     B, Hq, Hkv, D, N, G = 2, 14, 2, 128, 3000, 8
     K, V, q, logits, kcount = _rand_case(21, B, Hq, Hkv, D, N, G, outliers=True)
