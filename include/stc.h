@@ -244,8 +244,8 @@ int stc_decode_attention_per_head(const stc_shape_t *shape, const void *q, const
                                   float *out, void *ws, size_t ws_bytes, void *stream);
 
 /*
- * Value-group router (App. B.1: a single linear projection from the layer-input hidden state
- * to the S group logits), for feeding stc_route_and_pack_values:
+ * Value-group router (App. B.1: the S group logits of a token are one learned linear map of
+ * its hidden state at the layer input), for feeding stc_route_and_pack_values:
  *   logits[b, kvh, t, g] = sum_c h[b, t, c] * W[g, c] (+ bias[g]), the same for every kvh
  *   (the router gives one mask per token and layer).
  * Float arithmetic in a fixed order, because masks are decided on these numbers: chunks of

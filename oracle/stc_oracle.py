@@ -11,8 +11,9 @@ What each routine follows (paper = "Sub-Token Routing for KV Cache Compression")
                     reduction to Quest with chunk size 16 (App. C.1, LLM
                     training-config table).  Quest's page summary is the
                     per-page, per-channel min and max of the cached keys.
-  router_logits     App. B.1 "Value-Group Router": a single linear projection from
-                    the layer-input hidden state of a token to its S group logits.
+  router_logits     App. B.1 (the router's architecture): the S group logits of a
+                    token are one matrix-vector product of a learned S x d_model
+                    matrix with the token's hidden state at the layer input.
   route_mask        Sec. 3.3 "Routing mask": the top-K of the S group logits of
                     a token give a binary mask m[i,j]; App. B.1 gives the fixed
                     per-token K used for VLMs.  Here the count may differ per
@@ -31,7 +32,7 @@ What each routine follows (paper = "Sub-Token Routing for KV Cache Compression")
                     applied to the routed (zero-filled) value matrix; softmax
                     uses q and K only, dropped groups contribute nothing.  An
                     optional tail of recent tokens is attended uncompressed
-                    (Sec. 3.4: query-region tokens are not compressed).
+                    (Sec. 3.4 exempts the tokens of the query region from compression).
   rho_total         Sec. 3.3 "Compression ratio" and App. C.2:
                     rho_total = r * (1 + K/S) / 2.
 
@@ -270,8 +271,8 @@ def decode_attention(q_bits, K_bits, V_bits, mask, page_idx, G, P=16, K_tail=Non
 
     Tokens attended: every t < N of every listed page, and, when a tail is given
     (K_tail, V_tail [n_tail, D]), every tail token with its full value vector: the
-    recent tokens that the paper leaves uncompressed (Sec. 3.4: query-region tokens are
-    not compressed).  One softmax runs over both sets.  Returns float32 [R, D].
+    recent tokens, which the paper exempts from compression (Sec. 3.4, end of the LLM routing
+    subsection).  One softmax runs over both sets.  Returns float32 [R, D].
     """
     q = bf16_to_f32(q_bits).astype(np.float64)
     N, D = np.asarray(K_bits).shape

@@ -495,7 +495,7 @@ def test_route_and_pack_all_global_mode():
             assert int(off[b, h, -1]) == 2 * N == packed[b * Hkv + h].shape[0]
 
 
-# --- uncompressed recent tail (Sec. 3.4: query-region tokens are not compressed) ----------
+# --- uncompressed recent tail (Sec. 3.4 exempts the query region from compression) --------
 
 def test_attention_with_tail_is_dense_attention_over_both_sets():
     """Definition written out: one softmax over the selected cached tokens (routed values)
