@@ -31,7 +31,6 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f;  // "no token seen yet" running maximum
-constexpr int kAttnMaxWaves = 8;     // wavefronts per workgroup: 4 or 8
 constexpr int kTailPage = 1 << 30;   // flag of a page slot that lies in the uncompressed tail
 
 // Partial result of one (query head, split): [0] running max (base-2 logits),
@@ -83,8 +82,10 @@ __device__ long long* stc_dbg_ptr = nullptr;
 #define STC_MARK(slot, dep) do {} while (0)
 #endif
 
-// One wavefront walks 2*PAIRS pages of one stream, two at a time; the 4 wavefronts
-// of a workgroup then merge their partial results in LDS.
+// One wavefront walks 2*PAIRS page slots of one stream, two at a time (PAIRS = 1 in regular
+// builds); the WAVES wavefronts of a workgroup then merge their partial results in LDS.
+// Page slots are the selected pages of the compressed cache followed, with TAIL, by the pages
+// of the uncompressed tail; kv_div query-head streams may share one KV head's cache.
 //
 // Per pair of pages:
 //   1. K pages and packed V runs are read flat (every request is 1 KiB of adjacent
@@ -434,7 +435,7 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
   float l = l_part + __shfl_xor(l_part, 16);
   l += __shfl_xor(l, 32);
 
-  // ---- merge the 4 wavefronts: each leaves (m, l, acc[16][D]) in its own LDS region.
+  // ---- merge the workgroup's wavefronts: each leaves (m, l, acc[16][D]) in its own LDS region.
   // acc[cb][i] of lane (head r16, kg) is channel (4*kg + i)*CB + cb.
   float* macc = (float*)wl;                // [16][D]
   float* mml = (float*)(wl + 16 * D * 4);  // [16][2]
