@@ -54,6 +54,17 @@ def test_parity_topk_routing(case):
     assert worst <= PT.TIGHT
 
 
+def test_parity_very_long_stream():
+    """More than 8192 pages per stream (the selection kernel that re-reads its keys from
+    memory) and an attention over 300 pages split over many workgroups."""
+    B, Hq, Hkv, D, N, G, k = 1, 2, 1, 64, 16 * 9000 + 7, 2, 300
+    K, V, q, logits, kcount = _rand_case(17, B, Hq, Hkv, D, N, G, outliers=True)
+    hip = PT.run_hip(K, V, q, G, k, logits=logits, kcount=kcount)
+    ora = PT.run_oracle(K, V, q, G, k, logits=logits, kcount=kcount)
+    assert hip["dev_status"] == 0
+    assert PT.compare(hip, ora, Hq, Hkv) <= PT.TIGHT
+
+
 def test_parity_mask_mode_fixed_k_and_all_pages():
     B, Hq, Hkv, D, N, G = 2, 8, 2, 128, 333, 8
     K, V, q, logits, _ = _rand_case(3, B, Hq, Hkv, D, N, G)
