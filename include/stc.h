@@ -186,7 +186,9 @@ int stc_score_pages(const stc_shape_t *shape, const void *q, const void *bounds,
  * bf16 inputs, float accumulation, float output.
  *   q, K as above; vpacked, mask, tok_off as written by stc_route_and_pack_values
  *   page_idx [B, Hkv, k_pages] int32, in; 1 <= k_pages <= NP; entries outside
- *            [0, NP) are skipped; a page must not be listed twice
+ *            [0, NP) are skipped; a page must not be listed twice.  NULL stands for
+ *            pages 0 .. k_pages-1 of every stream (with k_pages == NP: the whole cache,
+ *            no selection call needed)
  *   out      [B, Hq, D] float, out
  *   ws       stc_workspace_bytes(shape, STC_WS_ATTENTION, k_pages) bytes
  * Value slots at or beyond v_cap_groups are treated as dropped; v_cap_groups >= 1.

@@ -272,6 +272,8 @@ class RoutedCache:
         self.vpacked = torch.empty(B, Hkv, cap, D // G, dtype=torch.bfloat16, device=dev)
         self.dev_status = torch.zeros(1, dtype=torch.int32, device=dev)
         self.page_idx = torch.empty(B, Hkv, self.k_eff, dtype=torch.int32, device=dev)
+        if k_pages >= self.NP:      # every page is kept: the list never changes
+            self.page_idx.copy_(torch.arange(self.NP, dtype=torch.int32, device=dev))
         self.page_score = (torch.empty(B, Hkv, self.NP, dtype=torch.float32, device=dev)
                            if keep_scores else None)
         self.out = torch.empty(B, Hq, D, dtype=torch.float32, device=dev)
@@ -319,16 +321,19 @@ class RoutedCache:
         self.n_tail += 1
 
     def attend(self, q):
+        page_idx = self.page_idx if self.k_pages < self.NP else None
         if self.tail_cap:
             stc_decode_attention_tail(self.shape, q, self.K, self.vpacked, self.mask, self.tok_off,
-                                      self.page_idx, self.k_eff, self.K_tail, self.V_tail,
+                                      page_idx, self.k_eff, self.K_tail, self.V_tail,
                                       self.n_tail, self.tail_cap, self.out, self._ws_attn)
             return
         stc_decode_attention(self.shape, q, self.K, self.vpacked, self.mask, self.tok_off,
-                             self.page_idx, self.k_eff, self.out, self._ws_attn)
+                             page_idx, self.k_eff, self.out, self._ws_attn)
 
     def step(self, q):
-        """One decode step: page selection, then routed attention."""
-        self.select(q)
+        """One decode step: page selection, then routed attention.  When every page is kept
+        there is nothing to select: the attention call takes "all pages" as a missing list."""
+        if self.k_pages < self.NP:
+            self.select(q)
         self.attend(q)
         return self.out

@@ -155,7 +155,7 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
   if (lane < npages) {
     const int slot = pi0 + lane;
     if (slot < k_pages) {
-      my_pg = page_idx[(size_t)stream * k_pages + slot];
+      my_pg = page_idx ? page_idx[(size_t)stream * k_pages + slot] : slot;  // no list: pages 0..
       if (my_pg < 0 || my_pg >= NP) my_pg = -1;
     } else {
       my_pg = kTailPage | (slot - k_pages);

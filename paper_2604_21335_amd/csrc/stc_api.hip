@@ -165,8 +165,7 @@ int decode_attention_impl(const stc_shape_t* shape, const void* q, const void* K
                           const int32_t* page_idx, int k_pages, const void* K_tail,
                           const void* V_tail, int n_tail, int tail_cap, bool per_head, float* out,
                           void* ws, size_t ws_bytes, void* stream) {
-  if (!shape || !q || !K || !vpacked || !mask || !tok_off || !page_idx || !out)
-    return STC_ERR_NULL;
+  if (!shape || !q || !K || !vpacked || !mask || !tok_off || !out) return STC_ERR_NULL;
   if (!shape_ok(shape) || k_pages < 1 || k_pages > num_pages(shape) || shape->v_cap_groups < 1)
     return STC_ERR_SHAPE;
   // the kernels address one stream's keys and packed values with 32-bit byte offsets
@@ -178,7 +177,7 @@ int decode_attention_impl(const stc_shape_t* shape, const void* q, const void* K
     return STC_ERR_SHAPE;
   if (n_tail > 0 && (!K_tail || !V_tail)) return STC_ERR_NULL;
   if (!aligned16(q) || !aligned16(K) || !aligned16(vpacked) || !aligned16(mask) ||
-      !aligned16(tok_off) || !aligned16(page_idx) || !aligned16(out) ||
+      !aligned16(tok_off) || (page_idx && !aligned16(page_idx)) || !aligned16(out) ||
       (n_tail > 0 && (!aligned16(K_tail) || !aligned16(V_tail))))
     return STC_ERR_ALIGN;
   const int slots = k_pages + (n_tail + shape->P - 1) / shape->P;

@@ -54,6 +54,30 @@ def test_parity_topk_routing(case):
     assert worst <= PT.TIGHT
 
 
+def test_missing_page_list_means_leading_pages():
+    """stc_decode_attention with page_idx == NULL attends pages 0 .. k-1: the same bits as the
+    explicit list, for the whole cache and for a prefix of it."""
+    B, Hq, Hkv, D, N, G = 2, 8, 2, 128, 700, 8
+    K, V, q, logits, kcount = _rand_case(27, B, Hq, Hkv, D, N, G)
+    NP = (N + 15) // 16
+    hip = PT.run_hip(K, V, q, G, NP, logits=logits, kcount=kcount)     # step() passes no list
+    ora = PT.run_oracle(K, V, q, G, NP, logits=logits, kcount=kcount)
+    assert PT.compare(hip, ora, Hq, Hkv) <= PT.TIGHT
+    c = hip["cache"]
+    dq = PT.to_dev_bf16(q)
+    for k in (NP, 9):
+        idx = torch.arange(k, dtype=torch.int32, device="cuda:0").expand(B, Hkv, k).contiguous()
+        a, b_ = torch.empty_like(c.out), torch.empty_like(c.out)
+        ws = torch.empty(max(16, stc.stc_workspace_bytes(c.shape, stc.STC_WS_ATTENTION, k)),
+                         dtype=torch.uint8, device="cuda:0")
+        stc.stc_decode_attention(c.shape, dq, c.K, c.vpacked, c.mask, c.tok_off, idx, k, a, ws)
+        stc.stc_decode_attention(c.shape, dq, c.K, c.vpacked, c.mask, c.tok_off, None, k, b_, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b_)
+        if k == NP:
+            assert np.array_equal(a.cpu().numpy(), hip["out"])
+
+
 def test_parity_very_long_stream():
     """More than 8192 pages per stream (the selection kernel that re-reads its keys from
     memory) and an attention over 300 pages split over many workgroups."""
