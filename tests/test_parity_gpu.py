@@ -54,6 +54,56 @@ def test_parity_topk_routing(case):
     assert worst <= PT.TIGHT
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_and_modes(seed):
+    """A seeded sweep over shapes, group sizes, routing modes and tail lengths (small enough for
+    the oracle, ragged almost everywhere): every stream against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    D = int(rng.choice([64, 128]))
+    G = int(rng.choice([g for g in (1, 2, 4, 8, 16) if D // g >= 8]))
+    R = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 12, 16]))
+    Hkv, B = int(rng.integers(1, 4)), int(rng.integers(1, 3))
+    Hq = Hkv * R
+    N = int(rng.integers(1, 1200))
+    NP = (N + 15) // 16
+    k = int(rng.integers(1, NP + 3))
+    ntail = int(rng.choice([0, 0, 1, 16, int(rng.integers(1, 41))]))
+    K, V, q, logits, kcount = _rand_case(2000 + seed, B, Hq, Hkv, D, N, G, outliers=bool(seed % 2))
+    mode = seed % 4
+    kw = {}
+    if mode == 0:
+        kw = dict(logits=logits, kcount=kcount)
+    elif mode == 1:
+        kw = dict(logits=logits, kcount=int(rng.integers(0, G + 1)))
+    elif mode == 2:
+        kw = dict(mask_in=rng.integers(0, 1 << 16, size=(B, Hkv, N)).astype(np.uint16))
+    else:
+        kw = dict(logits=logits, global_k=int(rng.integers(0, G + 1)))
+    hip = PT.run_hip(K, V, q, G, k, **kw)
+    ora = PT.run_oracle(K, V, q, G, k, **kw)
+    assert hip["dev_status"] == 0
+    assert PT.compare(hip, ora, Hq, Hkv) <= PT.TIGHT
+    if ntail:
+        c = hip["cache"]
+        cap_t = ntail + int(rng.integers(0, 9))
+        Kt, Vt = randn_bf16(rng, (B, Hkv, cap_t, D)), randn_bf16(rng, (B, Hkv, cap_t, D))
+        slots = c.k_eff + (ntail + 15) // 16
+        ws = torch.empty(max(16, stc.stc_workspace_bytes(c.shape, stc.STC_WS_ATTENTION_TAIL, slots)),
+                         dtype=torch.uint8, device="cuda:0")
+        out = torch.full_like(c.out, float("nan"))
+        stc.stc_decode_attention_tail(c.shape, PT.to_dev_bf16(q), c.K, c.vpacked, c.mask, c.tok_off,
+                                      c.page_idx, c.k_eff, PT.to_dev_bf16(Kt), PT.to_dev_bf16(Vt),
+                                      ntail, cap_t, out, ws)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        for b in range(B):
+            for h in range(Hkv):
+                want = O.decode_attention(q[b, h * R:(h + 1) * R], K[b, h], V[b, h],
+                                          hip["mask"][b, h], hip["page_idx"][b, h], G,
+                                          K_tail=Kt[b, h, :ntail], V_tail=Vt[b, h, :ntail])
+                assert np.abs(got[b, h * R:(h + 1) * R] - want).max() < PT.TIGHT
+
+
 def test_missing_page_list_means_leading_pages():
     """stc_decode_attention with page_idx == NULL attends pages 0 .. k-1: the same bits as the
     explicit list, for the whole cache and for a prefix of it."""
