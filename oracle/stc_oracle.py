@@ -375,6 +375,20 @@ def select_pages_per_head_all(q_bits, bounds_bits, k):
     return idx, score
 
 
+def union_pages(page_idx_group, NP):
+    """page_idx_group[R, k]: the page lists of the R query heads of one KV head ->
+    (pages[U] ascending, heads[U] uint16): every page some head selected, once, with bit r of
+    heads[i] set iff head r selected pages[i].  An encoding that lets the group's heads share
+    one pass over the keys and values; entries outside [0, NP) are ignored."""
+    masks = np.zeros(NP, dtype=np.uint16)
+    for r, row in enumerate(np.asarray(page_idx_group)):
+        for p in row:
+            if 0 <= int(p) < NP:
+                masks[int(p)] |= np.uint16(1 << r)
+    pages = np.nonzero(masks)[0].astype(np.int32)
+    return pages, masks[pages]
+
+
 def decode_attention_per_head_all(q_bits, K_bits, V_bits, mask, page_idx, G, P=16):
     """page_idx[B, Hq, k]: query head j attends its own pages of KV head j // (Hq/Hkv).
     -> out[B, Hq, D] float32."""

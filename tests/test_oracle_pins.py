@@ -653,3 +653,24 @@ def test_router_then_routing_pipeline():
     top2 = np.argsort(-a, axis=1, kind="stable")[:, :2]
     want = (1 << top2[:, 0]) | (1 << top2[:, 1])
     assert np.array_equal(m, want.astype(np.uint16))
+
+
+def test_union_pages_is_the_set_union_with_membership():
+    rng = np.random.default_rng(73)
+    NP, R, k = 40, 5, 7
+    lists = np.stack([np.sort(rng.choice(NP, k, replace=False)) for _ in range(R)]).astype(np.int32)
+    lists[2, 3] = -1                                         # ignored entry
+    pages, heads = O.union_pages(lists, NP)
+    want = sorted(set(int(p) for row in lists for p in row if p >= 0))
+    assert list(pages) == want
+    for p, m in zip(pages, heads):
+        assert int(m) == sum(1 << r for r in range(R) if p in lists[r])
+    # attending the union with membership = attending each head's own list
+    D, G, N = 64, 4, NP * 16
+    K, V = randn_bf16(rng, (N, D)), randn_bf16(rng, (N, D))
+    q = randn_bf16(rng, (R, D))
+    mask = rng.integers(0, 1 << G, size=N).astype(np.uint16)
+    for r in range(R):
+        own = O.decode_attention(q[r:r + 1], K, V, mask, [p for p in lists[r] if p >= 0], G)
+        via = O.decode_attention(q[r:r + 1], K, V, mask, pages[(heads >> r) & 1 == 1], G)
+        assert np.abs(own - via).max() < 1e-6
