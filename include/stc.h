@@ -20,7 +20,8 @@
  *   decode step          stc_select_pages (+ stc_score_pages: its scoring half alone),
  *                        stc_decode_attention
  *   recent tokens        stc_append_tail, stc_decode_attention_tail (uncompressed tail)
- *   per-query-head form  stc_select_pages_per_head, stc_decode_attention_per_head
+ *   per-query-head form  stc_select_pages_per_head, stc_decode_attention_per_head,
+ *                        stc_union_pages + stc_decode_attention_union (shared K/V reads)
  *   helpers              stc_workspace_bytes, stc_bounds_bytes, stc_status_string, stc_version
  *
  * Conventions shared by every call
@@ -244,6 +245,27 @@ int stc_decode_attention_per_head(const stc_shape_t *shape, const void *q, const
                                   const void *vpacked, const uint16_t *mask,
                                   const uint32_t *tok_off, const int32_t *page_idx, int k_pages,
                                   float *out, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Per-query-head selection without reading a page once per head: stc_union_pages merges the
+ * page lists of the query heads of every KV head into one ascending list plus, per page, the
+ * set of heads that selected it; stc_decode_attention_union attends that list with all heads
+ * of the group sharing every K page and V run, a head giving no weight to the tokens of pages
+ * it did not select.  The output equals stc_decode_attention_per_head up to rounding.
+ *   page_idx_per_head [B, Hq, k_pages] int32, in: ascending lists (as written by
+ *               stc_select_pages_per_head)
+ *   union_idx   [B, Hkv, union_cap] int32, out: selected pages ascending, then -1
+ *   union_heads [B, Hkv, union_cap] uint16, out: bit r = head r of the group selected the page
+ *   union_cap   >= min(NP, (Hq/Hkv) * k_pages) and <= NP; (Hq/Hkv) * k_pages <= 16384
+ *   ws          stc_workspace_bytes(shape, STC_WS_ATTENTION, union_cap) bytes
+ */
+int stc_union_pages(const stc_shape_t *shape, const int32_t *page_idx_per_head, int k_pages,
+                    int32_t *union_idx, uint16_t *union_heads, int union_cap, void *stream);
+int stc_decode_attention_union(const stc_shape_t *shape, const void *q, const void *K,
+                               const void *vpacked, const uint16_t *mask,
+                               const uint32_t *tok_off, const int32_t *union_idx,
+                               const uint16_t *union_heads, int union_cap, float *out, void *ws,
+                               size_t ws_bytes, void *stream);
 
 /*
  * Value-group router (App. B.1: the S group logits of a token are one learned linear map of

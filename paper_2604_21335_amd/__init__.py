@@ -25,6 +25,7 @@ EXPORTS = ["stc_version", "stc_status_string", "stc_workspace_bytes", "stc_bound
            "stc_build_page_bounds",
            "stc_route_and_pack_values", "stc_select_pages", "stc_score_pages", "stc_decode_attention", "stc_decode_attention_tail", "stc_append_tail",
            "stc_select_pages_per_head", "stc_decode_attention_per_head", "stc_router_logits",
+           "stc_union_pages", "stc_decode_attention_union",
            "stc_compact_tokens"]
 
 
@@ -83,6 +84,11 @@ def load_library():
     lib.stc_select_pages_per_head.argtypes = lib.stc_select_pages.argtypes
     lib.stc_decode_attention_per_head.restype = ctypes.c_int
     lib.stc_decode_attention_per_head.argtypes = lib.stc_decode_attention.argtypes
+    lib.stc_union_pages.restype = ctypes.c_int
+    lib.stc_union_pages.argtypes = [shp, vp, ctypes.c_int, vp, vp, ctypes.c_int, vp]
+    lib.stc_decode_attention_union.restype = ctypes.c_int
+    lib.stc_decode_attention_union.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp,
+                                               sz, vp]
     lib.stc_decode_attention_tail.restype = ctypes.c_int
     lib.stc_decode_attention_tail.argtypes = [shp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp,
                                               ctypes.c_int, ctypes.c_int, vp, vp, sz, vp]
@@ -209,6 +215,25 @@ def stc_decode_attention_per_head(shape, q, K, vpacked, mask, tok_off, page_idx,
         _ptr(tok_off, _U32, "tok_off"), _ptr(page_idx, torch.int32, "page_idx"), int(k_pages),
         _ptr(out, torch.float32, "out"), _ptr(ws, None, "ws"), _nbytes(ws), _stream()),
         "stc_decode_attention_per_head")
+
+
+def stc_union_pages(shape, page_idx_per_head, k_pages, union_idx, union_heads):
+    _check(load_library().stc_union_pages(
+        ctypes.byref(shape), _ptr(page_idx_per_head, torch.int32, "page_idx_per_head"),
+        int(k_pages), _ptr(union_idx, torch.int32, "union_idx"),
+        _ptr(union_heads, _U16, "union_heads"), int(union_idx.shape[-1]), _stream()),
+        "stc_union_pages")
+
+
+def stc_decode_attention_union(shape, q, K, vpacked, mask, tok_off, union_idx, union_heads, out,
+                               ws):
+    _check(load_library().stc_decode_attention_union(
+        ctypes.byref(shape), _ptr(q, torch.bfloat16, "q"), _ptr(K, torch.bfloat16, "K"),
+        _ptr(vpacked, torch.bfloat16, "vpacked"), _ptr(mask, _U16, "mask"),
+        _ptr(tok_off, _U32, "tok_off"), _ptr(union_idx, torch.int32, "union_idx"),
+        _ptr(union_heads, _U16, "union_heads"), int(union_idx.shape[-1]),
+        _ptr(out, torch.float32, "out"), _ptr(ws, None, "ws"), _nbytes(ws), _stream()),
+        "stc_decode_attention_union")
 
 
 def stc_decode_attention_tail(shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, K_tail,

@@ -112,7 +112,8 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
     const uint32_t* __restrict__ tok_off, const int32_t* __restrict__ page_idx,
     float* __restrict__ partial, float* __restrict__ out, int Hq, int Hkv, int N, int NP, int G,
     uint32_t cap, int k_pages, int splits, const uint16_t* __restrict__ K_tail,
-    const uint16_t* __restrict__ V_tail, int n_tail, int tail_cap, int kv_div) {
+    const uint16_t* __restrict__ V_tail, int n_tail, int tail_cap, int kv_div,
+    const uint16_t* __restrict__ page_heads) {
   using C = AttnCfg<D>;
   constexpr int ppw = 2 * PAIRS;  // pages per wavefront
   extern __shared__ __align__(16) unsigned char lds[];  // WAVES * C::WAVE_LDS bytes
@@ -152,10 +153,12 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
   const int pi0 = (split * WAVES + wave) * ppw;
   const int npages = max(0, min(ppw, k_pages + tail_pages - pi0));
   int my_pg = -1;
+  int my_heads = 0xffff;  // heads of the group that attend the page (all, unless a list is given)
   if (lane < npages) {
     const int slot = pi0 + lane;
     if (slot < k_pages) {
       my_pg = page_idx ? page_idx[(size_t)stream * k_pages + slot] : slot;  // no list: pages 0..
+      if (page_heads) my_heads = page_heads[(size_t)stream * k_pages + slot];
       if (my_pg < 0 || my_pg >= NP) my_pg = -1;
     } else {
       my_pg = kTailPage | (slot - k_pages);
@@ -308,9 +311,11 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
       const int pg = pgs[it][x];
       const uint32_t t0 = pg < 0 ? 0 : page_no(pg) * kPage;
       const uint32_t lim = tok_lim(pg);
+      // a head that did not select this page gives its tokens no weight
+      const bool mine = (__builtin_amdgcn_readlane(my_heads, 2 * it + x) >> r16) & 1;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const bool tv = pg >= 0 && (t0 + 4 * kg + i < lim);
+        const bool tv = pg >= 0 && mine && (t0 + 4 * kg + i < lim);
         s[x][i] = tv ? sv[i] * scale : -INFINITY;  // weight of an absent token is exactly 0
         mx = fmaxf(mx, s[x][i]);
       }
@@ -565,7 +570,8 @@ size_t attention_ws_bytes(const stc_shape_t& s0, int k_pages, bool per_head) {
 int launch_attention(const stc_shape_t& s0, const void* q, const void* K, const void* vpacked,
                      const uint16_t* mask, const uint32_t* tok_off, const int32_t* page_idx,
                      int k_pages, const void* K_tail, const void* V_tail, int n_tail, int tail_cap,
-                     bool per_head, float* out, void* ws, hipStream_t st) {
+                     bool per_head, const uint16_t* page_heads, float* out, void* ws,
+                     hipStream_t st) {
   const stc_shape_t s = launch_shape(s0, per_head);
   const int kv_div = per_head ? s0.Hq / s0.Hkv : 1;
   const int NP = (s.N + kPage - 1) / kPage;
@@ -603,7 +609,8 @@ int launch_attention(const stc_shape_t& s0, const void* q, const void* K, const 
     attn_mfma_kernel<DD, PP, WW, TT><<<grid, 64 * WW, lds_bytes, st>>>(                           \
         (const uint16_t*)q, (const uint16_t*)K, (const unsigned char*)vpacked, mask, tok_off,     \
         page_idx, partial, out, s.Hq, s.Hkv, s.N, NP, s.G, (uint32_t)s.v_cap_groups, k_pages,     \
-        splits, (const uint16_t*)K_tail, (const uint16_t*)V_tail, n_tail, tail_cap, kv_div);      \
+        splits, (const uint16_t*)K_tail, (const uint16_t*)V_tail, n_tail, tail_cap, kv_div,       \
+        page_heads);                                                                              \
   }
 #ifdef STC_TUNE
 #define STC_ATTN_PICK(DD)                                  \

@@ -270,4 +270,62 @@ int launch_select(const stc_shape_t& s, const void* q, const void* bounds, int k
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
+// Union of the R page lists of a KV head's query heads, one workgroup per KV head.  The lists
+// (R*k entries, each ascending) sit in LDS; thread t takes pages t, t + 256, ..., looks its page
+// up in every list by binary search to get the set of heads that selected it, and a block scan
+// compacts the selected pages in page order.  Unused output slots get page -1.
+__global__ __launch_bounds__(256) void union_pages_kernel(const int32_t* __restrict__ lists,
+                                                          int32_t* __restrict__ union_idx,
+                                                          uint16_t* __restrict__ union_heads,
+                                                          int NP, int R, int k, int U) {
+  extern __shared__ int32_t s_list[];  // [R * k]
+  __shared__ int waves[4];
+  const int stream = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int n = R * k;
+  for (int i = tid; i < n; i += 256) s_list[i] = lists[(size_t)stream * n + i];
+  __syncthreads();
+  int32_t* out_idx = union_idx + (size_t)stream * U;
+  uint16_t* out_heads = union_heads + (size_t)stream * U;
+  int base = 0;  // union entries written so far (pages below the current tile)
+  for (int p0 = 0; p0 < NP; p0 += 256) {
+    const int p = p0 + tid;
+    uint32_t m = 0;
+    if (p < NP) {
+      for (int r = 0; r < R; ++r) {
+        // the list of head r is ascending: binary search
+        const int32_t* row = s_list + r * k;
+        int lo = 0, hi = k;
+        while (lo < hi) {
+          const int mid = (lo + hi) >> 1;
+          if (row[mid] < p) lo = mid + 1;
+          else hi = mid;
+        }
+        if (lo < k && row[lo] == p) m |= 1u << r;
+      }
+    }
+    int tot;
+    const int pos = base + block_exscan(m != 0, waves, &tot);
+    if (m != 0 && pos < U) {
+      out_idx[pos] = p;
+      out_heads[pos] = (uint16_t)m;
+    }
+    base += tot;
+  }
+  for (int i = min(base, U) + tid; i < U; i += 256) {
+    out_idx[i] = -1;
+    out_heads[i] = 0;
+  }
+}
+
+int launch_union_pages(const stc_shape_t& s, const int32_t* page_idx_per_head, int k_pages,
+                       int32_t* union_idx, uint16_t* union_heads, int U, hipStream_t st) {
+  const int NP = (s.N + kPage - 1) / kPage;
+  const int R = s.Hq / s.Hkv;
+  const size_t lds = (size_t)R * k_pages * sizeof(int32_t);
+  union_pages_kernel<<<s.B * s.Hkv, 256, lds, st>>>(page_idx_per_head, union_idx, union_heads, NP,
+                                                    R, k_pages, U);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 }  // namespace stc

@@ -163,8 +163,9 @@ namespace {
 int decode_attention_impl(const stc_shape_t* shape, const void* q, const void* K,
                           const void* vpacked, const uint16_t* mask, const uint32_t* tok_off,
                           const int32_t* page_idx, int k_pages, const void* K_tail,
-                          const void* V_tail, int n_tail, int tail_cap, bool per_head, float* out,
-                          void* ws, size_t ws_bytes, void* stream) {
+                          const void* V_tail, int n_tail, int tail_cap, bool per_head,
+                          const uint16_t* page_heads, float* out, void* ws, size_t ws_bytes,
+                          void* stream) {
   if (!shape || !q || !K || !vpacked || !mask || !tok_off || !out) return STC_ERR_NULL;
   if (!shape_ok(shape) || k_pages < 1 || k_pages > num_pages(shape) || shape->v_cap_groups < 1)
     return STC_ERR_SHAPE;
@@ -185,7 +186,8 @@ int decode_attention_impl(const stc_shape_t* shape, const void* q, const void* K
   const size_t need = stc::attention_ws_bytes(*shape, slots, per_head);
   if (need && (!ws || ws_bytes < need || !aligned16(ws))) return STC_ERR_WORKSPACE;
   return stc::launch_attention(*shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, K_tail,
-                               V_tail, n_tail, tail_cap, per_head, out, ws, (hipStream_t)stream)
+                               V_tail, n_tail, tail_cap, per_head, page_heads, out, ws,
+                               (hipStream_t)stream)
              ? STC_ERR_LAUNCH
              : STC_OK;
 }
@@ -197,7 +199,7 @@ int stc_decode_attention(const stc_shape_t* shape, const void* q, const void* K,
                          const int32_t* page_idx, int k_pages, float* out, void* ws,
                          size_t ws_bytes, void* stream) {
   return decode_attention_impl(shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, nullptr,
-                               nullptr, 0, 0, false, out, ws, ws_bytes, stream);
+                               nullptr, 0, 0, false, nullptr, out, ws, ws_bytes, stream);
 }
 
 int stc_decode_attention_per_head(const stc_shape_t* shape, const void* q, const void* K,
@@ -205,7 +207,7 @@ int stc_decode_attention_per_head(const stc_shape_t* shape, const void* q, const
                                   const uint32_t* tok_off, const int32_t* page_idx, int k_pages,
                                   float* out, void* ws, size_t ws_bytes, void* stream) {
   return decode_attention_impl(shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, nullptr,
-                               nullptr, 0, 0, true, out, ws, ws_bytes, stream);
+                               nullptr, 0, 0, true, nullptr, out, ws, ws_bytes, stream);
 }
 
 int stc_decode_attention_tail(const stc_shape_t* shape, const void* q, const void* K,
@@ -214,7 +216,34 @@ int stc_decode_attention_tail(const stc_shape_t* shape, const void* q, const voi
                               const void* V_tail, int n_tail, int tail_cap, float* out, void* ws,
                               size_t ws_bytes, void* stream) {
   return decode_attention_impl(shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, K_tail,
-                               V_tail, n_tail, tail_cap, false, out, ws, ws_bytes, stream);
+                               V_tail, n_tail, tail_cap, false, nullptr, out, ws, ws_bytes, stream);
+}
+
+int stc_union_pages(const stc_shape_t* shape, const int32_t* page_idx_per_head, int k_pages,
+                    int32_t* union_idx, uint16_t* union_heads, int union_cap, void* stream) {
+  if (!shape || !page_idx_per_head || !union_idx || !union_heads) return STC_ERR_NULL;
+  if (!shape_ok(shape) || k_pages < 1 || k_pages > num_pages(shape)) return STC_ERR_SHAPE;
+  const long long R = shape->Hq / shape->Hkv;
+  // every selected page must fit; the lists are staged in 64 KiB of LDS
+  const long long need = R * k_pages < num_pages(shape) ? R * k_pages : num_pages(shape);
+  if (union_cap < need || R * k_pages * 4 > 65536) return STC_ERR_SHAPE;
+  if (!aligned16(page_idx_per_head) || !aligned16(union_idx) || !aligned16(union_heads))
+    return STC_ERR_ALIGN;
+  return stc::launch_union_pages(*shape, page_idx_per_head, k_pages, union_idx, union_heads,
+                                 union_cap, (hipStream_t)stream)
+             ? STC_ERR_LAUNCH
+             : STC_OK;
+}
+
+int stc_decode_attention_union(const stc_shape_t* shape, const void* q, const void* K,
+                               const void* vpacked, const uint16_t* mask, const uint32_t* tok_off,
+                               const int32_t* union_idx, const uint16_t* union_heads,
+                               int union_cap, float* out, void* ws, size_t ws_bytes,
+                               void* stream) {
+  if (!union_idx || !union_heads) return STC_ERR_NULL;
+  if (!aligned16(union_heads)) return STC_ERR_ALIGN;
+  return decode_attention_impl(shape, q, K, vpacked, mask, tok_off, union_idx, union_cap, nullptr,
+                               nullptr, 0, 0, false, union_heads, out, ws, ws_bytes, stream);
 }
 
 int stc_append_tail(const stc_shape_t* shape, const void* k_new, const void* v_new, void* K_tail,

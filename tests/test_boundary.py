@@ -122,6 +122,13 @@ def test_null_alignment_and_workspace_errors():
                                              big, None) == stc.STC_ERR_SHAPE
     assert lib.stc_decode_attention_per_head(r, FAKE, FAKE, FAKE, FAKE, FAKE, ODD, 7, FAKE, FAKE,
                                              big, None) == stc.STC_ERR_ALIGN
+    # union of per-head lists
+    un = lambda k, cap, lists=FAKE: lib.stc_union_pages(r, lists, k, FAKE, FAKE, cap, None)  # noqa: E731
+    assert un(2, 6) == stc.STC_ERR_SHAPE                       # capacity below min(NP, R*k) = 7
+    assert un(0, 7) == stc.STC_ERR_SHAPE
+    assert un(2, 7, None) == stc.STC_ERR_NULL
+    assert lib.stc_decode_attention_union(r, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, 7, FAKE,
+                                          FAKE, big, None) == stc.STC_ERR_NULL
     # router projection
     rl = lambda B, dm, G, h=FAKE, bias=None: lib.stc_router_logits(  # noqa: E731
         B, 2, 10, dm, G, h, FAKE, bias, FAKE, None)

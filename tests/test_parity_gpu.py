@@ -344,6 +344,26 @@ def test_per_head_selection_and_attention(B, Hq, Hkv, D, N, G, k):
         assert np.array_equal(out.cpu().numpy(), hip["out"])
     else:
         assert not np.array_equal(want_idx[:, 0], want_idx[:, 1])   # heads really differ
+    # the same attention with the group's lists merged: every K page and V run read once
+    R = Hq // Hkv
+    U = min(NP, R * k)
+    uidx = torch.full((B, Hkv, U), -5, dtype=torch.int32, device=dev)
+    uheads = torch.full((B, Hkv, U), -1, dtype=torch.int16, device=dev)
+    stc.stc_union_pages(c.shape, idx, k, uidx, uheads)
+    ws_u = torch.empty(max(16, stc.stc_workspace_bytes(c.shape, stc.STC_WS_ATTENTION, U)),
+                       dtype=torch.uint8, device=dev)
+    out_u = torch.full_like(out, float("nan"))
+    stc.stc_decode_attention_union(c.shape, dq, c.K, c.vpacked, c.mask, c.tok_off, uidx, uheads,
+                                   out_u, ws_u)
+    torch.cuda.synchronize()
+    gi, gh = uidx.cpu().numpy(), PT.host_u16(uheads)
+    for b in range(B):
+        for h in range(Hkv):
+            pages, heads = O.union_pages(want_idx[b, h * R:(h + 1) * R], NP)
+            n = len(pages)
+            assert np.array_equal(gi[b, h, :n], pages) and np.array_equal(gh[b, h, :n], heads)
+            assert (gi[b, h, n:] == -1).all() and (gh[b, h, n:] == 0).all()
+    assert np.abs(out_u.cpu().numpy() - want).max() < PT.TIGHT
 
 
 @pytest.mark.parametrize("B,Hkv,N,dm,G,with_bias", [(2, 2, 301, 512, 8, True), (1, 3, 64, 128, 4, False),
