@@ -19,7 +19,8 @@
  *                        (token-level compaction helper)
  *   decode step          stc_select_pages (+ stc_score_pages: its scoring half alone),
  *                        stc_decode_attention
- *   recent tokens        stc_append_tail, stc_decode_attention_tail (uncompressed tail)
+ *   recent tokens        stc_append_tail, stc_decode_attention_tail (uncompressed tail),
+ *                        stc_flush_tail (tail tokens into the compressed cache, in place)
  *   per-query-head form  stc_select_pages_per_head, stc_decode_attention_per_head,
  *                        stc_union_pages + stc_decode_attention_union (shared K/V reads)
  *   helpers              stc_workspace_bytes, stc_bounds_bytes, stc_status_string, stc_version
@@ -58,7 +59,8 @@ typedef struct stc_shape {
   int32_t P;            /* page size in tokens: 16 */
   int32_t G;            /* value groups per token (paper's S): 1..16, D % G == 0,
                            group width gd = D/G >= 8 (16-byte multiples) */
-  int32_t reserved;     /* must be 0 */
+  int32_t N_cap;        /* token capacity of K, mask, tok_off and bounds per stream: their
+                           per-stream strides.  0 means N (no room to grow); else >= N. */
   int64_t v_cap_groups; /* capacity of each stream's packed value store, in groups */
 } stc_shape_t;
 
@@ -101,9 +103,10 @@ size_t stc_workspace_bytes(const stc_shape_t *shape, int which_call, int k_pages
  * Quest page summary (Stage I, Sec. 3.2; chunk 16, App. C.1): for every page p < NP =
  * ceil(N/P) and channel c, the minimum and the maximum of K[t, c] over the page's valid
  * tokens (t < N).  Exact (comparisons only); -0 orders below +0.
- *   K      [B, Hkv, N, D]  bf16, in
+ *   K      [B, Hkv, Ncap, D]  bf16, in (Ncap = N_cap, or N when N_cap is 0; rows >= N unused)
  *   bounds stc_bounds_bytes(shape) bytes, out.  A layout made for the scoring kernel:
- *          dwords [B*Hkv][NT][D/32][2][8][4][4] with NT = ceil(NP/8) tiles of 8 pages;
+ *          dwords [B*Hkv][NT][D/32][2][8][4][4] with NT = ceil(ceil(Ncap/16)/8) tiles of 8
+ *          pages;
  *          element [s][t][j][g][e][col][w] is page 8*t + 4*g + col, channel
  *          e*(D/8) + 4*j + w of stream s: bf16 minimum in the low half of the dword,
  *          bf16 maximum in the high half.  Pages >= NP of the last tile hold zeros.
@@ -129,8 +132,8 @@ size_t stc_bounds_bytes(const stc_shape_t *shape);
  *   logits  [B, Hkv, N, G] float, in (TOPK and GLOBAL)
  *   kcount  [B, Hkv, N] uint8, in (TOPK, may be NULL)
  *   mask_in [B, Hkv, N] uint16, in (MASK only)
- *   mask    [B, Hkv, N] uint16, out (may alias mask_in)
- *   tok_off [B, Hkv, N+1] uint32, out: exclusive prefix sum of popcount(mask)
+ *   mask    [B, Hkv, Ncap] uint16, out (may alias mask_in when Ncap == N)
+ *   tok_off [B, Hkv, Ncap+1] uint32, out: exclusive prefix sum of popcount(mask)
  *           per stream, in group units; tok_off[N] = kept groups of the stream
  *   vpacked [B, Hkv, v_cap_groups, D/G] bf16, out: group g of token t (if kept)
  *           is stored at group slot tok_off[t] + popcount(mask[t] & ((1<<g)-1));
@@ -245,6 +248,25 @@ int stc_decode_attention_per_head(const stc_shape_t *shape, const void *q, const
                                   const void *vpacked, const uint16_t *mask,
                                   const uint32_t *tok_off, const int32_t *page_idx, int k_pages,
                                   float *out, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Moves the oldest n_flush tokens of the uncompressed tail into the compressed cache, in
+ * place: they become tokens N .. N+n_flush-1 of every stream (N = shape->N, the count before
+ * the call; N + n_flush <= N_cap).  Keys are copied, values are routed and packed behind the
+ * stream's packed store, tok_off[N+1 .. N+n_flush] continue from tok_off[N], and the bounds of
+ * every page holding a new token are recomputed.  The arrays then equal, bit for bit, what
+ * cache construction over all N + n_flush tokens writes; the caller continues with
+ * shape->N + n_flush and drops the moved rows from its tail.
+ *   K_tail, V_tail [B, Hkv, tail_cap, D] bf16, in: rows 0 .. n_flush-1 are moved
+ *   mode     STC_ROUTE_MASK (mask_in [B, Hkv, n_flush]) or STC_ROUTE_TOPK (logits
+ *            [B, Hkv, n_flush, G], kcount [B, Hkv, n_flush] or fixed_k), as in
+ *            stc_route_and_pack_values; a global budget cannot be continued
+ *   K, bounds, mask, tok_off, vpacked, dev_status: the cache arrays, updated in place
+ */
+int stc_flush_tail(const stc_shape_t *shape, const void *K_tail, const void *V_tail, int n_flush,
+                   int tail_cap, int mode, const float *logits, const uint8_t *kcount,
+                   int fixed_k, const uint16_t *mask_in, void *K, void *bounds, uint16_t *mask,
+                   uint32_t *tok_off, void *vpacked, int32_t *dev_status, void *stream);
 
 /*
  * Per-query-head selection without reading a page once per head: stc_union_pages merges the

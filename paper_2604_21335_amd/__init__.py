@@ -25,7 +25,7 @@ EXPORTS = ["stc_version", "stc_status_string", "stc_workspace_bytes", "stc_bound
            "stc_build_page_bounds",
            "stc_route_and_pack_values", "stc_select_pages", "stc_score_pages", "stc_decode_attention", "stc_decode_attention_tail", "stc_append_tail",
            "stc_select_pages_per_head", "stc_decode_attention_per_head", "stc_router_logits",
-           "stc_union_pages", "stc_decode_attention_union",
+           "stc_union_pages", "stc_decode_attention_union", "stc_flush_tail",
            "stc_compact_tokens"]
 
 
@@ -38,12 +38,13 @@ class StcError(RuntimeError):
 class stc_shape_t(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
                 ("D", ctypes.c_int32), ("N", ctypes.c_int32), ("P", ctypes.c_int32),
-                ("G", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("G", ctypes.c_int32), ("N_cap", ctypes.c_int32),
                 ("v_cap_groups", ctypes.c_int64)]
 
 
-def make_shape(B, Hq, Hkv, D, N, G, v_cap_groups, P=16):
-    return stc_shape_t(B, Hq, Hkv, D, N, P, G, 0, v_cap_groups)
+def make_shape(B, Hq, Hkv, D, N, G, v_cap_groups, P=16, N_cap=0):
+    """N_cap: token capacity (stride) of K, mask, tok_off and bounds; 0 = exactly N."""
+    return stc_shape_t(B, Hq, Hkv, D, N, P, G, N_cap, v_cap_groups)
 
 
 _lib = None
@@ -84,6 +85,9 @@ def load_library():
     lib.stc_select_pages_per_head.argtypes = lib.stc_select_pages.argtypes
     lib.stc_decode_attention_per_head.restype = ctypes.c_int
     lib.stc_decode_attention_per_head.argtypes = lib.stc_decode_attention.argtypes
+    lib.stc_flush_tail.restype = ctypes.c_int
+    lib.stc_flush_tail.argtypes = [shp, vp, vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp,
+                                   ctypes.c_int, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.stc_union_pages.restype = ctypes.c_int
     lib.stc_union_pages.argtypes = [shp, vp, ctypes.c_int, vp, vp, ctypes.c_int, vp]
     lib.stc_decode_attention_union.restype = ctypes.c_int
@@ -153,7 +157,8 @@ def bounds_rows(bounds, shape):
     a pure re-ordering of its elements, for inspection and tests."""
     B, Hkv, D = shape.B, shape.Hkv, shape.D
     NP = (shape.N + shape.P - 1) // shape.P
-    nt = (NP + 7) // 8
+    cap = shape.N_cap or shape.N
+    nt = ((cap + shape.P - 1) // shape.P + 7) // 8          # tiles per stream in memory
     # dwords [s][t][j][g][e][col][w], each (min, max)
     t = bounds.reshape(B, Hkv, nt, D // 32, 2, 8, 4, 4, 2)
     # -> [B, Hkv, t, g, col, (min|max), e, j, w]
@@ -215,6 +220,18 @@ def stc_decode_attention_per_head(shape, q, K, vpacked, mask, tok_off, page_idx,
         _ptr(tok_off, _U32, "tok_off"), _ptr(page_idx, torch.int32, "page_idx"), int(k_pages),
         _ptr(out, torch.float32, "out"), _ptr(ws, None, "ws"), _nbytes(ws), _stream()),
         "stc_decode_attention_per_head")
+
+
+def stc_flush_tail(shape, K_tail, V_tail, n_flush, tail_cap, mode, logits, kcount, fixed_k, mask_in,
+                   K, bounds, mask, tok_off, vpacked, dev_status):
+    _check(load_library().stc_flush_tail(
+        ctypes.byref(shape), _ptr(K_tail, torch.bfloat16, "K_tail"),
+        _ptr(V_tail, torch.bfloat16, "V_tail"), int(n_flush), int(tail_cap), int(mode),
+        _ptr(logits, torch.float32, "logits"), _ptr(kcount, torch.uint8, "kcount"), int(fixed_k),
+        _ptr(mask_in, _U16, "mask_in"), _ptr(K, torch.bfloat16, "K"),
+        _ptr(bounds, torch.bfloat16, "bounds"), _ptr(mask, _U16, "mask"),
+        _ptr(tok_off, _U32, "tok_off"), _ptr(vpacked, torch.bfloat16, "vpacked"),
+        _ptr(dev_status, torch.int32, "dev_status"), _stream()), "stc_flush_tail")
 
 
 def stc_union_pages(shape, page_idx_per_head, k_pages, union_idx, union_heads):
@@ -281,15 +298,20 @@ class RoutedCache:
     """
 
     def __init__(self, B, Hq, Hkv, D, N, G, k_pages, v_cap_groups=None, device="cuda:0",
-                 keep_scores=True, tail_cap=0):
+                 keep_scores=True, tail_cap=0, n_cap=0):
+        """n_cap > N: room for n_cap tokens, so that tail tokens can be moved into the cache
+        (flush); the cache then keeps its own copy of K."""
         self.device = torch.device(device)
         self.B, self.Hq, self.Hkv, self.D, self.N, self.G = B, Hq, Hkv, D, N, G
+        self.n_cap = n_cap
+        self.keep_scores = keep_scores
         self.NP = (N + 15) // 16
         self.k_pages = k_pages
         self.k_eff = min(k_pages, self.NP)
-        cap = N * G if v_cap_groups is None else v_cap_groups
-        self.shape = make_shape(B, Hq, Hkv, D, N, G, cap)
+        cap = (n_cap or N) * G if v_cap_groups is None else v_cap_groups
+        self.shape = make_shape(B, Hq, Hkv, D, N, G, cap, N_cap=n_cap)
         dev = self.device
+        N = n_cap or N                      # strides of mask and tok_off
         self.bounds = torch.empty(stc_bounds_bytes(self.shape) // 2, dtype=torch.bfloat16,
                                   device=dev)
         self.mask = torch.empty(B, Hkv, N, dtype=torch.int16, device=dev)
@@ -305,7 +327,8 @@ class RoutedCache:
         self._ws_route = self._ws(STC_WS_ROUTE, 0)
         self._ws_select = self._ws(STC_WS_SELECT, k_pages)
         self._ws_attn = self._ws(STC_WS_ATTENTION, self.k_eff)
-        self.K = None
+        self.K = (torch.empty(B, Hkv, n_cap, D, dtype=torch.bfloat16, device=dev)
+                  if n_cap else None)
         # uncompressed tail of recent tokens (tail_cap = 0: none)
         self.tail_cap, self.n_tail = tail_cap, 0
         if tail_cap:
@@ -321,8 +344,11 @@ class RoutedCache:
         """Cache construction: page bounds of K, routing mask + packed store of V.  The mask
         comes from mask_in, from a global budget of N*global_k token-group pairs per stream,
         or from the per-token top kcount[t] / fixed_k of the logits."""
-        self.K = K
-        stc_build_page_bounds(self.shape, K, self.bounds)
+        if self.n_cap:
+            self.K[:, :, :self.N].copy_(K)
+        else:
+            self.K = K
+        stc_build_page_bounds(self.shape, self.K, self.bounds)
         mode = STC_ROUTE_MASK if mask_in is not None else STC_ROUTE_TOPK
         if global_k is not None:
             mode, fixed_k, kcount = STC_ROUTE_GLOBAL, int(global_k), None
@@ -344,6 +370,33 @@ class RoutedCache:
         stc_append_tail(self.shape, k_new, v_new, self.K_tail, self.V_tail, self.n_tail,
                         self.tail_cap)
         self.n_tail += 1
+
+    def flush(self, n, logits=None, kcount=None, fixed_k=0, mask_in=None):
+        """Move the oldest n tail tokens into the compressed cache (routing them by mask_in,
+        or by the top kcount[t] / fixed_k of logits) and shift the rest of the tail down."""
+        mode = STC_ROUTE_MASK if mask_in is not None else STC_ROUTE_TOPK
+        stc_flush_tail(self.shape, self.K_tail, self.V_tail, n, self.tail_cap, mode, logits, kcount,
+                       fixed_k, mask_in, self.K, self.bounds, self.mask, self.tok_off,
+                       self.vpacked, self.dev_status)
+        rest = self.n_tail - n
+        if rest:
+            self.K_tail[:, :, :rest] = self.K_tail[:, :, n:self.n_tail].clone()
+            self.V_tail[:, :, :rest] = self.V_tail[:, :, n:self.n_tail].clone()
+        self.n_tail = rest
+        self.N += n
+        self.shape.N = self.N
+        self.NP = (self.N + 15) // 16
+        self.k_eff = min(self.k_pages, self.NP)
+        dev = self.device
+        self.page_idx = torch.empty(self.B, self.Hkv, self.k_eff, dtype=torch.int32, device=dev)
+        if self.k_pages >= self.NP:
+            self.page_idx.copy_(torch.arange(self.NP, dtype=torch.int32, device=dev))
+        if self.keep_scores:
+            self.page_score = torch.empty(self.B, self.Hkv, self.NP, dtype=torch.float32,
+                                          device=dev)
+        self._ws_select = self._ws(STC_WS_SELECT, self.k_pages)
+        self._ws_attn = self._ws(STC_WS_ATTENTION_TAIL,
+                                 self.k_eff + (self.tail_cap + 15) // 16)
 
     def attend(self, q):
         page_idx = self.page_idx if self.k_pages < self.NP else None

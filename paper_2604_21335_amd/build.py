@@ -9,8 +9,8 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libstc.so")
 BUILD_DIR = os.path.join(PKG_DIR, "_build")
 
-SOURCES = ["stc_api.hip", "bounds.hip", "router.hip", "route_pack.hip", "score.hip",
-           "select.hip", "attention.hip"]
+SOURCES = ["stc_api.hip", "bounds.hip", "router.hip", "route_pack.hip", "flush.hip",
+           "score.hip", "select.hip", "attention.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",

@@ -113,7 +113,7 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
     float* __restrict__ partial, float* __restrict__ out, int Hq, int Hkv, int N, int NP, int G,
     uint32_t cap, int k_pages, int splits, const uint16_t* __restrict__ K_tail,
     const uint16_t* __restrict__ V_tail, int n_tail, int tail_cap, int kv_div,
-    const uint16_t* __restrict__ page_heads) {
+    const uint16_t* __restrict__ page_heads, int Ncap) {
   using C = AttnCfg<D>;
   constexpr int ppw = 2 * PAIRS;  // pages per wavefront
   extern __shared__ __align__(16) unsigned char lds[];  // WAVES * C::WAVE_LDS bytes
@@ -138,9 +138,9 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
   // kv_div > 1: the launch has one "stream" (page list, query, output) per query head and
   // kv_div of them share the cache of one KV head.
   const int kvs = stream / kv_div;
-  const unsigned char* Ks = (const unsigned char*)K + (size_t)kvs * N * D * 2;
-  const unsigned char* mask_s = (const unsigned char*)mask + (size_t)kvs * N * 2;
-  const unsigned char* off_s = (const unsigned char*)tok_off + (size_t)kvs * (N + 1) * 4;
+  const unsigned char* Ks = (const unsigned char*)K + (size_t)kvs * Ncap * D * 2;
+  const unsigned char* mask_s = (const unsigned char*)mask + (size_t)kvs * Ncap * 2;
+  const unsigned char* off_s = (const unsigned char*)tok_off + (size_t)kvs * (Ncap + 1) * 4;
   const unsigned char* vs = vpacked + (size_t)kvs * (size_t)cap * gbytes;
   // the uncompressed tail: dense K and V rows, i.e. a packed store in which every token kept
   // every group; its pages follow the selected ones in the list of page slots
@@ -610,7 +610,7 @@ int launch_attention(const stc_shape_t& s0, const void* q, const void* K, const 
         (const uint16_t*)q, (const uint16_t*)K, (const unsigned char*)vpacked, mask, tok_off,     \
         page_idx, partial, out, s.Hq, s.Hkv, s.N, NP, s.G, (uint32_t)s.v_cap_groups, k_pages,     \
         splits, (const uint16_t*)K_tail, (const uint16_t*)V_tail, n_tail, tail_cap, kv_div,       \
-        page_heads);                                                                              \
+        page_heads, token_cap(s));                                                                \
   }
 #ifdef STC_TUNE
 #define STC_ATTN_PICK(DD)                                  \

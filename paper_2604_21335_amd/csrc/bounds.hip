@@ -1,5 +1,6 @@
 // Quest page summary: per-page, per-channel min and max of the cached keys
 // (token-level stage of the paper, Sec. 3.2; chunk size 16 from App. C.1).
+#include "build_helpers.hpp"
 #include "stc_common.hpp"
 #include "stc_kernels.hpp"
 
@@ -12,7 +13,8 @@ namespace stc {
 // past the last one of a stream's last tile are written as zeros.
 template <int D>
 __global__ __launch_bounds__(256) void bounds_kernel(const uint4* __restrict__ K,
-                                                     uint4* __restrict__ bounds, int N, int NP) {
+                                                     uint4* __restrict__ bounds, int N, int NP,
+                                                     int Ncap) {
   constexpr int LPP = D / 8;  // threads per page
   const int stream = blockIdx.y;
   const int sub = threadIdx.x % LPP;
@@ -20,37 +22,11 @@ __global__ __launch_bounds__(256) void bounds_kernel(const uint4* __restrict__ K
   const int ntiles = (NP + kBoundsTilePages - 1) / kBoundsTilePages;
   if (page >= ntiles * kBoundsTilePages) return;
   const int t0 = page * kPage;
-  const int t1 = min(t0 + kPage, N);  // t1 <= t0 for a padding page
-  const uint4* row = K + ((size_t)stream * N + t0) * LPP + sub;
-  int mn[8], mx[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    mn[i] = 0x7fffffff;
-    mx[i] = (int)0x80000000;
-  }
-#pragma unroll 4
-  for (int t = t0; t < t1; ++t, row += LPP) {
-    const uint4 v = *row;
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int a = bf16_order(w[i] & 0xffffu);
-      const int b = bf16_order(w[i] >> 16);
-      mn[2 * i] = min(mn[2 * i], a);
-      mx[2 * i] = max(mx[2 * i], a);
-      mn[2 * i + 1] = min(mn[2 * i + 1], b);
-      mx[2 * i + 1] = max(mx[2 * i + 1], b);
-    }
-  }
+  const int t1 = min(t0 + kPage, N);  // t1 <= t0 for a padding page: zeros
   uint32_t w[8];  // per channel: minimum | maximum << 16
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-    w[i] = page < NP ? (bf16_unorder(mn[i]) | (bf16_unorder(mx[i]) << 16)) : 0u;
-  uint4* tile = bounds + ((size_t)stream * ntiles + page / kBoundsTilePages) *
-                             (bounds_tile_dwords(D) / 4);
-  const int pt = page % kBoundsTilePages;
-  tile[bounds_tile_unit(D, pt, 8 * sub)] = make_uint4(w[0], w[1], w[2], w[3]);
-  tile[bounds_tile_unit(D, pt, 8 * sub + 4)] = make_uint4(w[4], w[5], w[6], w[7]);
+  page_bounds_words<D>(K + ((size_t)stream * Ncap + t0) * LPP + sub, t1 - t0, w);
+  store_bounds_units<D>(
+      bounds + (size_t)stream * bounds_tiles(Ncap) * (bounds_tile_dwords(D) / 4), page, sub, w);
 }
 
 int launch_bounds(const stc_shape_t& s, const void* K, void* bounds, hipStream_t st) {
@@ -60,9 +36,11 @@ int launch_bounds(const stc_shape_t& s, const void* K, void* bounds, hipStream_t
   const int pages = (NP + kBoundsTilePages - 1) / kBoundsTilePages * kBoundsTilePages;
   dim3 grid((pages + pages_per_block - 1) / pages_per_block, streams);
   if (s.D == 128)
-    bounds_kernel<128><<<grid, 256, 0, st>>>((const uint4*)K, (uint4*)bounds, s.N, NP);
+    bounds_kernel<128><<<grid, 256, 0, st>>>((const uint4*)K, (uint4*)bounds, s.N, NP,
+                                          token_cap(s));
   else
-    bounds_kernel<64><<<grid, 256, 0, st>>>((const uint4*)K, (uint4*)bounds, s.N, NP);
+    bounds_kernel<64><<<grid, 256, 0, st>>>((const uint4*)K, (uint4*)bounds, s.N, NP,
+                                         token_cap(s));
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

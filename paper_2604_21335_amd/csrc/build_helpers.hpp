@@ -1,0 +1,71 @@
+// Device helpers shared by the cache-construction kernels and the kernel that appends tokens
+// to a built cache.
+#pragma once
+#include "stc_common.hpp"
+
+namespace stc {
+
+// Routing mask of one token: bit g set iff group g is among the c largest of its G logits
+// (equal logits: the lower group first).
+__device__ __forceinline__ uint32_t rank_mask(const float* __restrict__ lp, int c, int G) {
+  float a[16];
+#pragma unroll
+  for (int g = 0; g < 16; ++g) a[g] = g < G ? lp[g] : 0.f;
+  uint32_t m = 0;
+#pragma unroll
+  for (int g = 0; g < 16; ++g) {
+    if (g < G) {
+      int ahead = 0;  // groups ranked before g: larger logit, or equal with lower index
+#pragma unroll
+      for (int g2 = 0; g2 < 16; ++g2) {
+        if (g2 < G && g2 != g) ahead += (a[g2] > a[g]) || (g2 < g && a[g2] == a[g]);
+      }
+      if (ahead < c) m |= 1u << g;
+    }
+  }
+  return m;
+}
+
+// Minimum and maximum of 8 adjacent channels over `ntok` token rows (row stride D*2 bytes,
+// `row` points at the 16-byte piece of the first row); w[i] = min | max << 16 as bf16 bits,
+// -0 ordered below +0.  ntok <= 0 gives zeros.
+template <int D>
+__device__ __forceinline__ void page_bounds_words(const uint4* __restrict__ row, int ntok,
+                                                  uint32_t (&w)[8]) {
+  constexpr int LPP = D / 8;
+  int mn[8], mx[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    mn[i] = 0x7fffffff;
+    mx[i] = (int)0x80000000;
+  }
+#pragma unroll 4
+  for (int t = 0; t < ntok; ++t, row += LPP) {
+    const uint4 v = *row;
+    const uint32_t x[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int a = bf16_order(x[i] & 0xffffu);
+      const int b = bf16_order(x[i] >> 16);
+      mn[2 * i] = min(mn[2 * i], a);
+      mx[2 * i] = max(mx[2 * i], a);
+      mn[2 * i + 1] = min(mn[2 * i + 1], b);
+      mx[2 * i + 1] = max(mx[2 * i + 1], b);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+    w[i] = ntok > 0 ? (bf16_unorder(mn[i]) | (bf16_unorder(mx[i]) << 16)) : 0u;
+}
+
+// The two 16-byte units of channels 8*sub .. 8*sub+7 of page `page` in the tiled bounds layout.
+template <int D>
+__device__ __forceinline__ void store_bounds_units(uint4* __restrict__ stream_tiles, int page,
+                                                   int sub, const uint32_t (&w)[8]) {
+  uint4* tile = stream_tiles + (size_t)(page / kBoundsTilePages) * (bounds_tile_dwords(D) / 4);
+  const int pt = page % kBoundsTilePages;
+  tile[bounds_tile_unit(D, pt, 8 * sub)] = make_uint4(w[0], w[1], w[2], w[3]);
+  tile[bounds_tile_unit(D, pt, 8 * sub + 4)] = make_uint4(w[4], w[5], w[6], w[7]);
+}
+
+}  // namespace stc

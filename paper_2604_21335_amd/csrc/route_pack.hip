@@ -2,6 +2,7 @@
 // routing mask per token (or, for the LLM setting of Sec. 3.4 / App. B.1, the N*K
 // best token-group pairs of the whole stream), per-token offsets into the
 // group-packed store, and the packed copy of the kept value groups.
+#include "build_helpers.hpp"
 #include "stc_common.hpp"
 #include "stc_kernels.hpp"
 
@@ -41,35 +42,20 @@ __device__ __forceinline__ int block_exscan_256(int v, int* lds4, int* total) {
 __global__ __launch_bounds__(kChunk) void route_mask_kernel(
     int mode, const float* __restrict__ logits, const uint8_t* __restrict__ kcount, int fixed_k,
     const uint16_t* mask_in, uint16_t* mask, uint32_t* __restrict__ chunk_sum, int N, int G,
-    int nchunks) {
+    int nchunks, int Ncap, int mask_in_stride) {
   __shared__ int red[4];
   const int stream = blockIdx.y;
   const int t = blockIdx.x * kChunk + threadIdx.x;
   uint32_t m = 0;
   if (t < N) {
-    const size_t tok = (size_t)stream * N + t;
+    const size_t tok = (size_t)stream * N + t;  // dense inputs: logits, kcount
     if (mode == STC_ROUTE_MASK) {
-      m = mask_in[tok] & ((1u << G) - 1u);
+      m = mask_in[(size_t)stream * mask_in_stride + t] & ((1u << G) - 1u);
     } else {
       int c = kcount ? (int)kcount[tok] : fixed_k;
-      c = min(c, G);
-      float a[16];
-      const float* lp = logits + tok * G;
-#pragma unroll
-      for (int g = 0; g < 16; ++g) a[g] = g < G ? lp[g] : 0.f;
-#pragma unroll
-      for (int g = 0; g < 16; ++g) {
-        if (g < G) {
-          int ahead = 0;  // groups ranked before g: larger logit, or equal with lower index
-#pragma unroll
-          for (int g2 = 0; g2 < 16; ++g2) {
-            if (g2 < G && g2 != g) ahead += (a[g2] > a[g]) || (g2 < g && a[g2] == a[g]);
-          }
-          if (ahead < c) m |= 1u << g;
-        }
-      }
+      m = rank_mask(logits + tok * G, min(c, G), G);
     }
-    mask[tok] = (uint16_t)m;
+    mask[(size_t)stream * Ncap + t] = (uint16_t)m;
   }
   const int tot = block_sum_256(__popc(m), red);
   if (threadIdx.x == 0) chunk_sum[(size_t)stream * nchunks + blockIdx.x] = (uint32_t)tot;
@@ -115,7 +101,7 @@ __device__ __forceinline__ uint32_t block_exscan_1024(uint32_t v, uint32_t* lds1
 
 __global__ __launch_bounds__(kGlobalThreads) void route_global_kernel(
     const float* __restrict__ logits, uint16_t* __restrict__ mask, int N, int G,
-    uint32_t budget) {
+    uint32_t budget, int Ncap) {
   __shared__ uint32_t hist[kGlobalBins];
   __shared__ uint32_t waves[kGlobalThreads / 64];
   __shared__ uint32_t s_prefix, s_remaining;
@@ -123,7 +109,7 @@ __global__ __launch_bounds__(kGlobalThreads) void route_global_kernel(
   const int tid = threadIdx.x;
   const uint32_t n = (uint32_t)N * (uint32_t)G;
   const float* a = logits + (size_t)stream * n;
-  uint16_t* mk = mask + (size_t)stream * N;
+  uint16_t* mk = mask + (size_t)stream * Ncap;
 
   uint32_t prefix = 0, decided = 0, remaining = budget;
   if (budget > 0) {
@@ -196,7 +182,7 @@ __global__ __launch_bounds__(kGlobalThreads) void route_global_kernel(
 // stream total to tok_off[N] and flags a packed store that is too small.
 __global__ __launch_bounds__(256) void scan_chunks_kernel(uint32_t* chunk_sum, uint32_t* tok_off,
                                                           int32_t* dev_status, int N, int nchunks,
-                                                          long long cap) {
+                                                          long long cap, int Ncap) {
   __shared__ int red[4];
   const int stream = blockIdx.x;
   uint32_t* cs = chunk_sum + (size_t)stream * nchunks;
@@ -210,7 +196,7 @@ __global__ __launch_bounds__(256) void scan_chunks_kernel(uint32_t* chunk_sum, u
     carry += tot;
   }
   if (threadIdx.x == 0) {
-    tok_off[(size_t)stream * (N + 1) + N] = (uint32_t)carry;
+    tok_off[(size_t)stream * (Ncap + 1) + N] = (uint32_t)carry;
     if (dev_status && (long long)carry > cap) *dev_status = 1;
   }
 }
@@ -224,7 +210,7 @@ __global__ __launch_bounds__(kChunk) void pack_kernel(const uint4* __restrict__ 
                                                       const uint32_t* __restrict__ chunk_off,
                                                       uint32_t* __restrict__ tok_off,
                                                       uint4* __restrict__ vpacked, int N, int G,
-                                                      int nchunks, long long cap) {
+                                                      int nchunks, long long cap, int Ncap) {
   __shared__ int red[4];
   __shared__ uint32_t s_off[kChunk];
   __shared__ uint32_t s_mask[kChunk];
@@ -233,10 +219,10 @@ __global__ __launch_bounds__(kChunk) void pack_kernel(const uint4* __restrict__ 
   const int t0 = blockIdx.x * kChunk;
   const int t = t0 + threadIdx.x;
   uint32_t m = 0;
-  if (t < N) m = mask[(size_t)stream * N + t];
+  if (t < N) m = mask[(size_t)stream * Ncap + t];
   const int ex = block_exscan_256(__popc(m), red, nullptr);
   const uint32_t off = chunk_off[(size_t)stream * nchunks + blockIdx.x] + (uint32_t)ex;
-  if (t < N) tok_off[(size_t)stream * (N + 1) + t] = off;
+  if (t < N) tok_off[(size_t)stream * (Ncap + 1) + t] = off;
   s_off[threadIdx.x] = off;
   s_mask[threadIdx.x] = m;
   __syncthreads();
@@ -287,30 +273,33 @@ int launch_route_pack(const stc_shape_t& s, int mode, const void* V, const float
                       hipStream_t st) {
   const int streams = s.B * s.Hkv;
   const int nchunks = (s.N + kChunk - 1) / kChunk;
+  const int Ncap = token_cap(s);  // stride of mask and tok_off; V, logits, kcount are dense
+  int mask_in_stride = s.N;
   uint32_t* chunk = (uint32_t*)ws;
   dim3 grid(nchunks, streams);
   if (mode == STC_ROUTE_GLOBAL) {
     // the mask of the whole stream first, then the common path with that mask as given
     route_global_kernel<<<streams, kGlobalThreads, 0, st>>>(
-        logits, mask, s.N, s.G, (uint32_t)((long long)s.N * fixed_k));
+        logits, mask, s.N, s.G, (uint32_t)((long long)s.N * fixed_k), Ncap);
     if (hipGetLastError() != hipSuccess) return -1;
     mode = STC_ROUTE_MASK;
     mask_in = mask;
+    mask_in_stride = Ncap;
   }
   route_mask_kernel<<<grid, kChunk, 0, st>>>(mode, logits, kcount, fixed_k, mask_in, mask, chunk,
-                                             s.N, s.G, nchunks);
+                                             s.N, s.G, nchunks, Ncap, mask_in_stride);
   if (hipGetLastError() != hipSuccess) return -1;
   scan_chunks_kernel<<<streams, 256, 0, st>>>(chunk, tok_off, dev_status, s.N, nchunks,
-                                              (long long)s.v_cap_groups);
+                                              (long long)s.v_cap_groups, Ncap);
   if (hipGetLastError() != hipSuccess) return -1;
   if (s.D == 128)
     pack_kernel<128><<<grid, kChunk, 0, st>>>((const uint4*)V, mask, chunk, tok_off,
                                               (uint4*)vpacked, s.N, s.G, nchunks,
-                                              (long long)s.v_cap_groups);
+                                              (long long)s.v_cap_groups, Ncap);
   else
     pack_kernel<64><<<grid, kChunk, 0, st>>>((const uint4*)V, mask, chunk, tok_off,
                                              (uint4*)vpacked, s.N, s.G, nchunks,
-                                             (long long)s.v_cap_groups);
+                                             (long long)s.v_cap_groups, Ncap);
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

@@ -61,7 +61,8 @@ __device__ __forceinline__ bf16x4 as_bf16x4(uint32_t w0, uint32_t w1) {
 template <int D, int R, bool PER_HEAD>
 __global__ __launch_bounds__(256) __attribute__((STC_SCORE_WAVES_PER_SIMD))
 void score_mfma_kernel(const u32x4* __restrict__ tiles, const uint16_t* __restrict__ q,
-                       float* __restrict__ score, int NP, int Hq, int Hkv, int tiles_per_block) {
+                       float* __restrict__ score, int NP, int Hq, int Hkv, int tiles_per_block,
+                       int tiles_cap) {
   constexpr int CH = D / 8;        // channels per lane
   constexpr int NJ = CH / 4;       // 16-byte units per lane and tile
   constexpr int NG = (R + 3) / 4;  // groups of 4 query heads (MFMA rows)
@@ -89,7 +90,7 @@ void score_mfma_kernel(const u32x4* __restrict__ tiles, const uint16_t* __restri
   }
 
   const int t0 = blockIdx.x * tiles_per_block, t1 = min(t0 + tiles_per_block, ntiles);
-  const u32x4* base = tiles + (size_t)stream * ntiles * T16 + lane;
+  const u32x4* base = tiles + (size_t)stream * tiles_cap * T16 + lane;  // capacity stride
   float* out = score + (size_t)stream * (PER_HEAD ? R : 1) * NP;
   const int tlast = t1 - 1;
 
@@ -162,7 +163,7 @@ __global__ __launch_bounds__(256) void score_any_kernel(const u32x4* __restrict_
                                                         const uint16_t* __restrict__ q,
                                                         float* __restrict__ score, int NP, int Hq,
                                                         int Hkv, int R, int tiles_per_block,
-                                                        int per_head) {
+                                                        int per_head, int tiles_cap) {
   constexpr int CH = D / 8, NJ = CH / 4, T16 = NJ * 64;
   const int stream = blockIdx.y;
   const int b = stream / Hkv, kvh = stream % Hkv;
@@ -170,7 +171,7 @@ __global__ __launch_bounds__(256) void score_any_kernel(const u32x4* __restrict_
   const int e = (lane >> 2) & 7;
   const int ntiles = (NP + kBoundsTilePages - 1) / kBoundsTilePages;
   const int t0 = blockIdx.x * tiles_per_block, t1 = min(t0 + tiles_per_block, ntiles);
-  const u32x4* base = tiles + (size_t)stream * ntiles * T16 + lane;
+  const u32x4* base = tiles + (size_t)stream * tiles_cap * T16 + lane;  // capacity stride
   float* out = score + (size_t)stream * (per_head ? R : 1) * NP;
   for (int t = t0 + wave; t < t1; t += 4) {
     uint32_t w[CH];
@@ -208,6 +209,7 @@ static void launch_score_d(const stc_shape_t& s, const void* q, const void* boun
   const int streams = s.B * s.Hkv;
   const int R = s.Hq / s.Hkv;
   const int ntiles = (NP + kBoundsTilePages - 1) / kBoundsTilePages;
+  const int tcap = bounds_tiles(token_cap(s));  // tiles per stream in memory
   // about three workgroups per CU (what the register budget keeps resident), so the whole
   // grid runs as one generation and the per-wavefront set-up is paid once per several tiles
   const int want_blocks = max(1, 768 / streams);
@@ -220,10 +222,10 @@ static void launch_score_d(const stc_shape_t& s, const void* q, const void* boun
   case RR:                                                                                  \
     if (per_head)                                                                           \
       score_mfma_kernel<D, RR, true><<<grid, 256, 0, st>>>(t4, q16, score, NP, s.Hq, s.Hkv, \
-                                                           tpb);                            \
+                                                           tpb, tcap);                      \
     else                                                                                    \
       score_mfma_kernel<D, RR, false><<<grid, 256, 0, st>>>(t4, q16, score, NP, s.Hq,       \
-                                                            s.Hkv, tpb);                    \
+                                                            s.Hkv, tpb, tcap);              \
     break;
   switch (R) {
     STC_SCORE_CASE(1)
@@ -236,7 +238,7 @@ static void launch_score_d(const stc_shape_t& s, const void* q, const void* boun
     STC_SCORE_CASE(8)
     default:
       score_any_kernel<D><<<grid, 256, 0, st>>>(t4, q16, score, NP, s.Hq, s.Hkv, R, tpb,
-                                                per_head ? 1 : 0);
+                                                per_head ? 1 : 0, tcap);
   }
 #undef STC_SCORE_CASE
 }

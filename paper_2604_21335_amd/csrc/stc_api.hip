@@ -15,11 +15,12 @@ bool shape_ok(const stc_shape_t* s) {
   if (s->P != 16) return false;
   if (s->G < 1 || s->G > 16 || (s->G & (s->G - 1)) != 0) return false;
   if (s->D % s->G != 0 || s->D / s->G < 8) return false;
-  if (s->reserved != 0 || s->v_cap_groups < 0) return false;
+  if (s->v_cap_groups < 0) return false;
+  if (s->N_cap != 0 && (s->N_cap < s->N || (long long)s->N_cap > (1ll << 30))) return false;
   if ((long long)s->B * s->Hkv > kMaxGridY) return false;
   if ((long long)s->N > (1ll << 30)) return false;
   // the packed store is addressed with 32-bit group offsets
-  if ((long long)s->N * s->G >= (1ll << 32)) return false;
+  if ((long long)stc::token_cap(*s) * s->G >= (1ll << 32)) return false;
   return true;
 }
 
@@ -69,7 +70,7 @@ size_t stc_workspace_bytes(const stc_shape_t* shape, int which_call, int k_pages
 
 size_t stc_bounds_bytes(const stc_shape_t* shape) {
   if (!shape || !shape_ok(shape)) return 0;
-  const size_t tiles = (num_pages(shape) + stc::kBoundsTilePages - 1) / stc::kBoundsTilePages;
+  const size_t tiles = stc::bounds_tiles(stc::token_cap(*shape));
   return (size_t)shape->B * shape->Hkv * tiles * stc::kBoundsTilePages * shape->D * 4;
 }
 
@@ -170,7 +171,7 @@ int decode_attention_impl(const stc_shape_t* shape, const void* q, const void* K
   if (!shape_ok(shape) || k_pages < 1 || k_pages > num_pages(shape) || shape->v_cap_groups < 1)
     return STC_ERR_SHAPE;
   // the kernels address one stream's keys and packed values with 32-bit byte offsets
-  if ((long long)shape->N * shape->D * 2 >= (1ll << 32) ||
+  if ((long long)stc::token_cap(*shape) * shape->D * 2 >= (1ll << 32) ||
       shape->v_cap_groups * (shape->D / shape->G) * 2 >= (1ll << 32))
     return STC_ERR_SHAPE;
   if (n_tail < 0 || tail_cap < 0 || n_tail > tail_cap ||
@@ -217,6 +218,34 @@ int stc_decode_attention_tail(const stc_shape_t* shape, const void* q, const voi
                               size_t ws_bytes, void* stream) {
   return decode_attention_impl(shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, K_tail,
                                V_tail, n_tail, tail_cap, false, nullptr, out, ws, ws_bytes, stream);
+}
+
+int stc_flush_tail(const stc_shape_t* shape, const void* K_tail, const void* V_tail, int n_flush,
+                   int tail_cap, int mode, const float* logits, const uint8_t* kcount, int fixed_k,
+                   const uint16_t* mask_in, void* K, void* bounds, uint16_t* mask,
+                   uint32_t* tok_off, void* vpacked, int32_t* dev_status, void* stream) {
+  if (!shape || !K_tail || !V_tail || !K || !bounds || !mask || !tok_off || !vpacked)
+    return STC_ERR_NULL;
+  if (!shape_ok(shape) || n_flush < 1 || n_flush > tail_cap ||
+      (long long)shape->N + n_flush > stc::token_cap(*shape))
+    return STC_ERR_SHAPE;
+  if (mode == STC_ROUTE_TOPK) {
+    if (!logits) return STC_ERR_NULL;
+    if (!kcount && (fixed_k < 0 || fixed_k > shape->G)) return STC_ERR_SHAPE;
+  } else if (mode == STC_ROUTE_MASK) {
+    if (!mask_in) return STC_ERR_NULL;
+  } else {
+    return STC_ERR_SHAPE;  // a global budget is not incremental
+  }
+  if (!aligned16(K_tail) || !aligned16(V_tail) || !aligned16(K) || !aligned16(bounds) ||
+      !aligned16(mask) || !aligned16(tok_off) || !aligned16(vpacked) ||
+      (logits && !aligned16(logits)) || (mask_in && !aligned16(mask_in)))
+    return STC_ERR_ALIGN;
+  return stc::launch_flush_tail(*shape, K_tail, V_tail, n_flush, tail_cap, mode, logits, kcount,
+                                fixed_k, mask_in, K, bounds, mask, tok_off, vpacked, dev_status,
+                                (hipStream_t)stream)
+             ? STC_ERR_LAUNCH
+             : STC_OK;
 }
 
 int stc_union_pages(const stc_shape_t* shape, const int32_t* page_idx_per_head, int k_pages,

@@ -12,6 +12,12 @@ namespace stc {
 
 constexpr int kBoundsTilePages = 8;  // pages per tile of the bounds layout
 
+// Token capacity of a stream's K, mask, tok_off and bounds arrays (their per-stream strides).
+inline int token_cap(const stc_shape_t& s) { return s.N_cap ? s.N_cap : s.N; }
+__host__ __device__ inline int bounds_tiles(int tokens) {
+  return ((tokens + 15) / 16 + kBoundsTilePages - 1) / kBoundsTilePages;
+}
+
 int launch_bounds(const stc_shape_t& s, const void* K, void* bounds, hipStream_t st);
 
 size_t route_ws_bytes(const stc_shape_t& s);
@@ -37,6 +43,10 @@ int launch_attention(const stc_shape_t& s, const void* q, const void* K, const v
 // the heads that selected each page.
 int launch_union_pages(const stc_shape_t& s, const int32_t* page_idx_per_head, int k_pages,
                        int32_t* union_idx, uint16_t* union_heads, int U, hipStream_t st);
+int launch_flush_tail(const stc_shape_t& s, const void* K_tail, const void* V_tail, int n,
+                      int tail_cap, int mode, const float* logits, const uint8_t* kcount,
+                      int fixed_k, const uint16_t* mask_in, void* K, void* bounds, uint16_t* mask,
+                      uint32_t* tok_off, void* vpacked, int32_t* dev_status, hipStream_t st);
 int launch_append_tail(const stc_shape_t& s, const void* k_new, const void* v_new, void* K_tail,
                        void* V_tail, int n_tail, int tail_cap, hipStream_t st);
 

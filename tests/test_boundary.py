@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def _shape(**kw):
-    d = dict(B=2, Hq=8, Hkv=2, D=128, N=100, G=8, v_cap_groups=800)
+    d = dict(B=2, Hq=8, Hkv=2, D=128, N=100, G=8, v_cap_groups=800, N_cap=0)
     d.update(kw)
     return stc.make_shape(**d)
 
@@ -122,6 +122,23 @@ def test_null_alignment_and_workspace_errors():
                                              big, None) == stc.STC_ERR_SHAPE
     assert lib.stc_decode_attention_per_head(r, FAKE, FAKE, FAKE, FAKE, FAKE, ODD, 7, FAKE, FAKE,
                                              big, None) == stc.STC_ERR_ALIGN
+    # flush of tail tokens into the cache: needs room (N_cap) and a routing input
+    sc = _shape(N_cap=140)
+    rc = ctypes.byref(sc)
+    fl = lambda shp, n, mode, logits, mask_in, K=FAKE: lib.stc_flush_tail(  # noqa: E731
+        shp, FAKE, FAKE, n, 64, mode, logits, None, 2, mask_in, K, FAKE, FAKE, FAKE, FAKE, None,
+        None)
+    assert fl(r, 8, stc.STC_ROUTE_TOPK, FAKE, None) == stc.STC_ERR_SHAPE        # no capacity
+    assert fl(rc, 41, stc.STC_ROUTE_TOPK, FAKE, None) == stc.STC_ERR_SHAPE      # 100 + 41 > 140
+    assert fl(rc, 0, stc.STC_ROUTE_TOPK, FAKE, None) == stc.STC_ERR_SHAPE
+    assert fl(rc, 8, stc.STC_ROUTE_GLOBAL, FAKE, None) == stc.STC_ERR_SHAPE
+    assert fl(rc, 8, stc.STC_ROUTE_TOPK, None, None) == stc.STC_ERR_NULL
+    assert fl(rc, 8, stc.STC_ROUTE_MASK, None, None) == stc.STC_ERR_NULL
+    assert fl(rc, 8, stc.STC_ROUTE_MASK, None, FAKE, None) == stc.STC_ERR_NULL
+    assert fl(rc, 8, stc.STC_ROUTE_MASK, None, ODD) == stc.STC_ERR_ALIGN
+    assert lib.stc_build_page_bounds(ctypes.byref(_shape(N_cap=50)), FAKE, FAKE,
+                                     None) == stc.STC_ERR_SHAPE                  # capacity < N
+    assert stc.stc_bounds_bytes(sc) == 2 * 2 * 2 * 8 * 128 * 4                   # 9 pages -> 2 tiles
     # union of per-head lists
     un = lambda k, cap, lists=FAKE: lib.stc_union_pages(r, lists, k, FAKE, FAKE, cap, None)  # noqa: E731
     assert un(2, 6) == stc.STC_ERR_SHAPE                       # capacity below min(NP, R*k) = 7

@@ -395,6 +395,73 @@ def test_router_logits_bits_and_routing(B, Hkv, N, dm, G, with_bias):
                 assert np.array_equal(hip["mask"][b, kvh], m)
 
 
+def _cache_equals_full_build(c, K_all, V_all, logits_all, kcount_all, G):
+    """Every array of cache `c` (N tokens so far, capacity strides) against construction from
+    scratch over the same N tokens by the oracle."""
+    N = c.N
+    bounds = PT.host_bf16(c.bounds_rows())
+    mask = PT.host_u16(c.mask)[:, :, :N]
+    off = c.tok_off.cpu().numpy().view(np.uint32)[:, :, :N + 1]
+    vp = PT.host_bf16(c.vpacked)
+    B, Hkv = K_all.shape[:2]
+    for b in range(B):
+        for h in range(Hkv):
+            assert np.array_equal(bounds[b, h], O.page_bounds(K_all[b, h, :N]))
+            m = O.route_mask(logits_all[b, h, :N], kcount_all[b, h, :N])
+            o = O.token_offsets(m, G)
+            assert np.array_equal(mask[b, h], m) and np.array_equal(off[b, h], o)
+            assert np.array_equal(vp[b, h, :int(o[-1])], O.pack_values(V_all[b, h, :N], m, o, G))
+    assert np.array_equal(PT.host_bf16(c.K)[:, :, :N], K_all[:, :, :N])
+
+
+@pytest.mark.parametrize("D,G,Hq,Hkv,N0", [(128, 8, 14, 2, 600), (64, 4, 4, 4, 33), (128, 16, 3, 1, 1024)])
+def test_flush_tail_into_the_cache_equals_full_build(D, G, Hq, Hkv, N0):
+    """A decode loop with cache growth: append new tokens to the tail, attend, and from time to
+    time move the oldest tail tokens into the compressed cache in place.  After every flush
+    the cache equals construction from scratch over all its tokens, bit for bit; every decode
+    step is checked against the oracle."""
+    B, k, n_cap, tail_cap = 2, 12, N0 + 160, 48
+    total = N0 + 150
+    K_all, V_all, _, logits_all, kcount_all = _rand_case(120 + D + N0, B, Hq, Hkv, D, total, G,
+                                                         outliers=True)
+    rng = np.random.default_rng(121)
+    dev = "cuda:0"
+    c = stc.RoutedCache(B, Hq, Hkv, D, N0, G, k, device=dev, tail_cap=tail_cap, n_cap=n_cap)
+    c.vpacked.view(torch.int16).fill_(0x7FC0)
+    c.build(PT.to_dev_bf16(K_all[:, :, :N0]), PT.to_dev_bf16(V_all[:, :, :N0]),
+            logits=torch.from_numpy(logits_all[:, :, :N0].copy()).to(dev),
+            kcount=torch.from_numpy(kcount_all[:, :, :N0].copy()).to(dev))
+    torch.cuda.synchronize()
+    _cache_equals_full_build(c, K_all, V_all, logits_all, kcount_all, G)      # capacity strides
+    R = Hq // Hkv
+    seen = N0                      # tokens handed to the cache or its tail so far
+    for step in range(150):
+        c.append(PT.to_dev_bf16(K_all[:, :, seen]), PT.to_dev_bf16(V_all[:, :, seen]))
+        seen += 1
+        if c.n_tail == tail_cap or step in (6, 20):          # flush all but the newest few
+            n = max(1, c.n_tail - int(rng.integers(0, 9)))
+            lo = c.N
+            c.flush(n, logits=torch.from_numpy(logits_all[:, :, lo:lo + n].copy()).to(dev),
+                    kcount=torch.from_numpy(kcount_all[:, :, lo:lo + n].copy()).to(dev))
+            torch.cuda.synchronize()
+            assert int(c.dev_status.item()) == 0 and c.N == lo + n and c.N + c.n_tail == seen
+            _cache_equals_full_build(c, K_all, V_all, logits_all, kcount_all, G)
+        if step % 7 == 0 or c.n_tail == 0:
+            qs = randn_bf16(rng, (B, Hq, D))
+            c.step(PT.to_dev_bf16(qs))
+            torch.cuda.synchronize()
+            got, idx = c.out.cpu().numpy(), c.page_idx.cpu().numpy()
+            b, h = step % B, step % Hkv
+            Kc, Vc = K_all[b, h, :c.N], V_all[b, h, :c.N]
+            m = O.route_mask(logits_all[b, h, :c.N], kcount_all[b, h, :c.N])
+            sc = O.page_scores(qs[b, h * R:(h + 1) * R], O.page_bounds(Kc))
+            want_idx = O.select_pages(sc, k)
+            assert np.array_equal(idx[b, h], want_idx)
+            want = O.decode_attention(qs[b, h * R:(h + 1) * R], Kc, Vc, m, want_idx, G,
+                                      K_tail=K_all[b, h, c.N:seen], V_tail=V_all[b, h, c.N:seen])
+            assert np.abs(got[b, h * R:(h + 1) * R] - want).max() < PT.TIGHT
+
+
 def test_score_pages_alone_matches_oracle_bits():
     B, Hq, Hkv, D, N, G = 2, 14, 2, 128, 3000, 8
     K, V, q, logits, kcount = _rand_case(21, B, Hq, Hkv, D, N, G, outliers=True)
