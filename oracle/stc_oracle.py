@@ -36,7 +36,7 @@ What each routine follows (paper = "Sub-Token Routing for KV Cache Compression")
   rho_total         Sec. 3.3 "Compression ratio" and App. C.2:
                     rho_total = r * (1 + K/S) / 2.
 
-Readings where the paper is silent (also listed in the design notes):
+Readings where the paper is silent:
   * bf16 tensors are passed as uint16 bit patterns; widening to float is exact.
   * min/max of +0 and -0: -0 orders below +0, so the result does not depend on
     the order in which a page is reduced.

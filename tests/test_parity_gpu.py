@@ -628,7 +628,7 @@ def test_workload_reduced_every_stream(name):
 
 @pytest.mark.parametrize("name", W.ORDER)
 def test_workload_full_size_sampled_streams(name):
-    """Full BASELINE sizes, in the launch configuration the benchmark times."""
+    """The full workload sizes, in the launch configuration the benchmark times."""
     w = W.WORKLOADS[name]
     c, t = _run_workload(w)
     assert int(c.dev_status.item()) == 0
