@@ -55,9 +55,12 @@ Readings where the paper is silent:
   * the softmax denominator runs over every selected token, whether or not any
     of its value groups were kept.
 
-parity unpinned: the GQA rule (max over the group's heads) and the absence of
-forced "window" pages are this build's readings; the paper gives nothing to
-check them against.
+parity unpinned: the GQA rule (max over the group's heads, or one page list per
+query head), the absence of forced "window" pages, keeping recent tokens in an
+always-attended uncompressed tail, applying the global budget at cache build
+to all cached tokens, and the router as a plain linear map without a query
+summary are this build's readings; the paper gives nothing to check them
+against.  The arithmetic of each of them is pinned by the tests.
 """
 import math
 
