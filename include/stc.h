@@ -18,7 +18,7 @@
  *                        stc_router_logits (the router's projection), stc_compact_tokens
  *                        (token-level compaction helper)
  *   decode step          stc_select_pages (+ stc_score_pages: its scoring half alone),
- *                        stc_decode_attention
+ *                        stc_decode_attention; stc_decode_step does both in one call
  *   recent tokens        stc_append_tail, stc_decode_attention_tail (uncompressed tail),
  *                        stc_flush_tail (tail tokens into the compressed cache, in place)
  *   per-query-head form  stc_select_pages_per_head, stc_decode_attention_per_head,
@@ -80,7 +80,8 @@ enum {
   STC_WS_ATTENTION = 3,
   STC_WS_ATTENTION_TAIL = 4,
   STC_WS_SELECT_PER_HEAD = 5,
-  STC_WS_ATTENTION_PER_HEAD = 6
+  STC_WS_ATTENTION_PER_HEAD = 6,
+  STC_WS_STEP = 7
 };
 
 /* routing modes of stc_route_and_pack_values */
@@ -203,6 +204,21 @@ int stc_decode_attention(const stc_shape_t *shape, const void *q, const void *K,
                          const void *vpacked, const uint16_t *mask, const uint32_t *tok_off,
                          const int32_t *page_idx, int k_pages, float *out, void *ws,
                          size_t ws_bytes, void *stream);
+
+/*
+ * One decode step of the compressed cache: the page selection of stc_select_pages (Quest
+ * bound scores, top-k_pages per stream; Sec. 3.4) followed by the attention of
+ * stc_decode_attention over the selected pages (Sec. 3.3), with the same results bit for
+ * bit as the two calls in a row.  The attention workgroups select their stream's pages from
+ * the page scores themselves, which saves the launch that orders the scores.
+ *   q, bounds, K, vpacked, mask, tok_off, k_pages, out: as in the two calls
+ *   page_idx [B, Hkv, k_pages] int32, out: the selected pages, ascending (required)
+ *   ws       stc_workspace_bytes(shape, STC_WS_STEP, k_pages) bytes
+ */
+int stc_decode_step(const stc_shape_t *shape, const void *q, const void *bounds, const void *K,
+                    const void *vpacked, const uint16_t *mask, const uint32_t *tok_off,
+                    int k_pages, int32_t *page_idx, float *out, void *ws, size_t ws_bytes,
+                    void *stream);
 
 /*
  * Routed decode attention with an uncompressed tail of recent tokens: the tokens generated

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libstc.so")
 STC_OK = 0
 STC_ERR_NULL, STC_ERR_SHAPE, STC_ERR_ALIGN, STC_ERR_WORKSPACE, STC_ERR_LAUNCH = -1, -2, -3, -4, -5
 STC_WS_ROUTE, STC_WS_SELECT, STC_WS_ATTENTION, STC_WS_ATTENTION_TAIL = 1, 2, 3, 4
-STC_WS_SELECT_PER_HEAD, STC_WS_ATTENTION_PER_HEAD = 5, 6
+STC_WS_SELECT_PER_HEAD, STC_WS_ATTENTION_PER_HEAD, STC_WS_STEP = 5, 6, 7
 STC_ROUTE_MASK, STC_ROUTE_TOPK, STC_ROUTE_GLOBAL = 0, 1, 2
 
 EXPORTS = ["stc_version", "stc_status_string", "stc_workspace_bytes", "stc_bounds_bytes",
@@ -26,7 +26,7 @@ EXPORTS = ["stc_version", "stc_status_string", "stc_workspace_bytes", "stc_bound
            "stc_route_and_pack_values", "stc_select_pages", "stc_score_pages", "stc_decode_attention", "stc_decode_attention_tail", "stc_append_tail",
            "stc_select_pages_per_head", "stc_decode_attention_per_head", "stc_router_logits",
            "stc_union_pages", "stc_decode_attention_union", "stc_flush_tail",
-           "stc_compact_tokens"]
+           "stc_compact_tokens", "stc_decode_step"]
 
 
 class StcError(RuntimeError):
@@ -96,6 +96,8 @@ def load_library():
     lib.stc_decode_attention_tail.restype = ctypes.c_int
     lib.stc_decode_attention_tail.argtypes = [shp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp,
                                               ctypes.c_int, ctypes.c_int, vp, vp, sz, vp]
+    lib.stc_decode_step.restype = ctypes.c_int
+    lib.stc_decode_step.argtypes = [shp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp, vp, sz, vp]
     lib.stc_append_tail.restype = ctypes.c_int
     lib.stc_append_tail.argtypes = [shp, vp, vp, vp, vp, ctypes.c_int, ctypes.c_int, vp]
     lib.stc_router_logits.restype = ctypes.c_int
@@ -253,6 +255,15 @@ def stc_decode_attention_union(shape, q, K, vpacked, mask, tok_off, union_idx, u
         "stc_decode_attention_union")
 
 
+def stc_decode_step(shape, q, bounds, K, vpacked, mask, tok_off, k_pages, page_idx, out, ws):
+    _check(load_library().stc_decode_step(
+        ctypes.byref(shape), _ptr(q, torch.bfloat16, "q"), _ptr(bounds, torch.bfloat16, "bounds"),
+        _ptr(K, torch.bfloat16, "K"), _ptr(vpacked, torch.bfloat16, "vpacked"),
+        _ptr(mask, _U16, "mask"), _ptr(tok_off, _U32, "tok_off"), int(k_pages),
+        _ptr(page_idx, torch.int32, "page_idx"), _ptr(out, torch.float32, "out"),
+        _ptr(ws, None, "ws"), _nbytes(ws), _stream()), "stc_decode_step")
+
+
 def stc_decode_attention_tail(shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, K_tail,
                               V_tail, n_tail, tail_cap, out, ws):
     _check(load_library().stc_decode_attention_tail(
@@ -321,12 +332,11 @@ class RoutedCache:
         self.page_idx = torch.empty(B, Hkv, self.k_eff, dtype=torch.int32, device=dev)
         if k_pages >= self.NP:      # every page is kept: the list never changes
             self.page_idx.copy_(torch.arange(self.NP, dtype=torch.int32, device=dev))
-        self.page_score = (torch.empty(B, Hkv, self.NP, dtype=torch.float32, device=dev)
-                           if keep_scores else None)
         self.out = torch.empty(B, Hq, D, dtype=torch.float32, device=dev)
         self._ws_route = self._ws(STC_WS_ROUTE, 0)
         self._ws_select = self._ws(STC_WS_SELECT, k_pages)
         self._ws_attn = self._ws(STC_WS_ATTENTION, self.k_eff)
+        self._alloc_step()
         self.K = (torch.empty(B, Hkv, n_cap, D, dtype=torch.bfloat16, device=dev)
                   if n_cap else None)
         # uncompressed tail of recent tokens (tail_cap = 0: none)
@@ -335,6 +345,17 @@ class RoutedCache:
             self.K_tail = torch.empty(B, Hkv, tail_cap, D, dtype=torch.bfloat16, device=dev)
             self.V_tail = torch.empty_like(self.K_tail)
             self._ws_attn = self._ws(STC_WS_ATTENTION_TAIL, self.k_eff + (tail_cap + 15) // 16)
+
+    def _alloc_step(self):
+        """Workspace of stc_decode_step.  The page scores are at its front: page_score is a view
+        of them, so that both forms of step() leave the scores there."""
+        self._ws_step = self._ws(STC_WS_STEP, self.k_eff)
+        self.page_score = None
+        if self.keep_scores:
+            n = self.B * self.Hkv * self.NP
+            src = (self._ws_step if self.k_pages < self.NP else
+                   torch.empty(4 * n, dtype=torch.uint8, device=self.device))
+            self.page_score = src[:4 * n].view(torch.float32).view(self.B, self.Hkv, self.NP)
 
     def _ws(self, which, k):
         n = stc_workspace_bytes(self.shape, which, k)
@@ -391,12 +412,10 @@ class RoutedCache:
         self.page_idx = torch.empty(self.B, self.Hkv, self.k_eff, dtype=torch.int32, device=dev)
         if self.k_pages >= self.NP:
             self.page_idx.copy_(torch.arange(self.NP, dtype=torch.int32, device=dev))
-        if self.keep_scores:
-            self.page_score = torch.empty(self.B, self.Hkv, self.NP, dtype=torch.float32,
-                                          device=dev)
         self._ws_select = self._ws(STC_WS_SELECT, self.k_pages)
         self._ws_attn = self._ws(STC_WS_ATTENTION_TAIL,
                                  self.k_eff + (self.tail_cap + 15) // 16)
+        self._alloc_step()
 
     def attend(self, q):
         page_idx = self.page_idx if self.k_pages < self.NP else None
@@ -408,10 +427,16 @@ class RoutedCache:
         stc_decode_attention(self.shape, q, self.K, self.vpacked, self.mask, self.tok_off,
                              page_idx, self.k_eff, self.out, self._ws_attn)
 
-    def step(self, q):
+    def step(self, q, one_call=True):
         """One decode step: page selection, then routed attention.  When every page is kept
-        there is nothing to select: the attention call takes "all pages" as a missing list."""
+        there is nothing to select: the attention call takes "all pages" as a missing list.
+        one_call: through stc_decode_step (the page scores then stay in its workspace)
+        instead of stc_select_pages + stc_decode_attention."""
         if self.k_pages < self.NP:
+            if one_call and not self.tail_cap:
+                stc_decode_step(self.shape, q, self.bounds, self.K, self.vpacked, self.mask,
+                                self.tok_off, self.k_eff, self.page_idx, self.out, self._ws_step)
+                return self.out
             self.select(q)
         self.attend(q)
         return self.out

@@ -17,6 +17,7 @@
 
 #include "stc_common.hpp"
 #include "stc_kernels.hpp"
+#include "topk_block.hpp"
 
 namespace stc {
 
@@ -105,7 +106,10 @@ __device__ long long* stc_dbg_ptr = nullptr;
 // next pair's K rows.  All loads are unconditional (addresses of absent pages or
 // tokens collapse to one valid location and the result is discarded) so that they
 // stay in flight across the arithmetic.
-template <int D, int PAIRS, int WAVES, bool TAIL>
+// SELECT_IPT > 0: no page list is given; every workgroup first selects the stream's k pages
+// from the page scores itself (the same selection as the stand-alone kernel, SELECT_IPT keys
+// per thread), keeps the ones of its own split and writes them to the list.
+template <int D, int PAIRS, int WAVES, bool TAIL, int SELECT_IPT>
 __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K,
     const unsigned char* __restrict__ vpacked, const uint16_t* __restrict__ mask,
@@ -113,7 +117,8 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
     float* __restrict__ partial, float* __restrict__ out, int Hq, int Hkv, int N, int NP, int G,
     uint32_t cap, int k_pages, int splits, const uint16_t* __restrict__ K_tail,
     const uint16_t* __restrict__ V_tail, int n_tail, int tail_cap, int kv_div,
-    const uint16_t* __restrict__ page_heads, int Ncap) {
+    const uint16_t* __restrict__ page_heads, int Ncap, const float* __restrict__ sel_score,
+    int32_t* __restrict__ sel_list) {
   using C = AttnCfg<D>;
   constexpr int ppw = 2 * PAIRS;  // pages per wavefront
   extern __shared__ __align__(16) unsigned char lds[];  // WAVES * C::WAVE_LDS bytes
@@ -163,6 +168,23 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
     } else {
       my_pg = kTailPage | (slot - k_pages);
     }
+  }
+  if constexpr (SELECT_IPT > 0) {
+    __shared__ int32_t s_pages[WAVES * ppw];
+    if (threadIdx.x < WAVES * ppw) s_pages[threadIdx.x] = -1;
+    __syncthreads();
+    const int lo = split * WAVES * ppw;  // first list position of this workgroup
+    int32_t* list = sel_list + (size_t)stream * k_pages;
+    topk_block<SELECT_IPT, 64 * WAVES>(sel_score + (size_t)stream * NP, NP, k_pages,
+                                       [&](int pos, int page) {
+                                         const unsigned r = (unsigned)(pos - lo);
+                                         if (r < (unsigned)(WAVES * ppw)) {
+                                           s_pages[r] = page;
+                                           list[pos] = page;
+                                         }
+                                       });
+    __syncthreads();
+    my_pg = lane < npages ? s_pages[wave * ppw + lane] : -1;
   }
   const int npairs = (npages + 1) / 2;
 
@@ -567,21 +589,89 @@ size_t attention_ws_bytes(const stc_shape_t& s0, int k_pages, bool per_head) {
   return (size_t)s.B * s.Hq * splits * partial_stride(s.D) * sizeof(float);
 }
 
+namespace {
+
+struct AttnArgs {
+  const uint16_t *q, *K;
+  const unsigned char* vpacked;
+  const uint16_t* mask;
+  const uint32_t* tok_off;
+  const int32_t* page_idx;
+  float *partial, *out;
+  int Hq, Hkv, N, NP, G;
+  uint32_t cap;
+  int k_pages, splits;
+  const uint16_t *K_tail, *V_tail;
+  int n_tail, tail_cap, kv_div;
+  const uint16_t* page_heads;
+  int Ncap;
+  const float* sel_score;
+  int32_t* sel_list;
+  dim3 grid;
+  hipStream_t st;
+};
+
+template <int D, int PAIRS, int WAVES, bool TAIL, int SELECT_IPT>
+int attn_go(const AttnArgs& a) {
+  // workgroups of 8 wavefronts at D = 128 need more than the default 64 KiB of LDS
+  constexpr int lds_bytes = WAVES * AttnCfg<D>::WAVE_LDS;
+  static const hipError_t attr = hipFuncSetAttribute(
+      (const void*)attn_mfma_kernel<D, PAIRS, WAVES, TAIL, SELECT_IPT>,
+      hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+  if (attr != hipSuccess) return -1;
+  attn_mfma_kernel<D, PAIRS, WAVES, TAIL, SELECT_IPT><<<a.grid, 64 * WAVES, lds_bytes, a.st>>>(
+      a.q, a.K, a.vpacked, a.mask, a.tok_off, a.page_idx, a.partial, a.out, a.Hq, a.Hkv, a.N, a.NP,
+      a.G, a.cap, a.k_pages, a.splits, a.K_tail, a.V_tail, a.n_tail, a.tail_cap, a.kv_div,
+      a.page_heads, a.Ncap, a.sel_score, a.sel_list);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+template <int D>
+int attn_dispatch(const AttnArgs& a, const AttnPlan& plan, bool tail, bool select) {
+  if (select) {  // selection inside the kernel: no tail, 2048 keys over the workgroup's threads
+    if (plan.waves == 8) return attn_go<D, 1, 8, false, 4>(a);
+    return attn_go<D, 1, 4, false, 8>(a);
+  }
+#ifdef STC_TUNE
+  if (plan.ppw == 4) {
+    if (plan.waves == 8)
+      return tail ? attn_go<D, 2, 8, true, 0>(a) : attn_go<D, 2, 8, false, 0>(a);
+    return tail ? attn_go<D, 2, 4, true, 0>(a) : attn_go<D, 2, 4, false, 0>(a);
+  }
+#endif
+  if (plan.waves == 8) return tail ? attn_go<D, 1, 8, true, 0>(a) : attn_go<D, 1, 8, false, 0>(a);
+  return tail ? attn_go<D, 1, 4, true, 0>(a) : attn_go<D, 1, 4, false, 0>(a);
+}
+
+}  // namespace
+
+// Selection inside the attention kernel repeats a stream's top-k in each of its workgroups.
+// Measured against the separate selection launch it is faster while all workgroups are
+// resident at once (two per compute unit) and a stream's keys fit four per thread, and
+// slower beyond (the repeated prologue then delays a second round of workgroups).
+bool attention_can_select(const stc_shape_t& s, int k_pages) {
+  const int NP = (s.N + kPage - 1) / kPage;
+  if (k_pages >= NP || NP > 2048) return false;
+  return (long long)s.B * s.Hkv * attention_plan(s, k_pages).splits <= 512;
+}
+
 int launch_attention(const stc_shape_t& s0, const void* q, const void* K, const void* vpacked,
                      const uint16_t* mask, const uint32_t* tok_off, const int32_t* page_idx,
                      int k_pages, const void* K_tail, const void* V_tail, int n_tail, int tail_cap,
-                     bool per_head, const uint16_t* page_heads, float* out, void* ws,
-                     hipStream_t st) {
+                     bool per_head, const uint16_t* page_heads, const float* sel_score,
+                     int32_t* sel_list, float* out, void* ws, hipStream_t st) {
   const stc_shape_t s = launch_shape(s0, per_head);
-  const int kv_div = per_head ? s0.Hq / s0.Hkv : 1;
   const int NP = (s.N + kPage - 1) / kPage;
   const int streams = s.B * s.Hkv;
   const int tail_pages = (n_tail + kPage - 1) / kPage;
   if (tail_pages == 0) K_tail = V_tail = K;  // any valid address: never read
   const AttnPlan plan = attention_plan(s, k_pages + tail_pages);
-  const int splits = plan.splits;
-  dim3 grid(splits, streams);
-  float* partial = (float*)ws;
+  AttnArgs a{(const uint16_t*)q, (const uint16_t*)K, (const unsigned char*)vpacked, mask, tok_off,
+             page_idx, (float*)ws, out, s.Hq, s.Hkv, s.N, NP, s.G, (uint32_t)s.v_cap_groups,
+             k_pages, plan.splits, (const uint16_t*)K_tail, (const uint16_t*)V_tail, n_tail,
+             tail_cap, per_head ? s0.Hq / s0.Hkv : 1, page_heads, token_cap(s), sel_score,
+             sel_list, dim3(plan.splits, streams), st};
+  if (sel_score && (NP > 2048 || tail_pages || per_head || page_heads)) return -1;
 #ifdef STC_TUNE
   {
     long long* p = nullptr;
@@ -593,53 +683,14 @@ int launch_attention(const stc_shape_t& s0, const void* q, const void* K, const 
     }
   }
 #endif
-  // workgroups of 8 wavefronts at D = 128 need more than the default 64 KiB of LDS
-#define STC_ATTN_LAUNCH(DD, PP, WW)                                    \
-  {                                                                    \
-    if (tail_pages > 0) STC_ATTN_LAUNCH_T(DD, PP, WW, true)            \
-    else STC_ATTN_LAUNCH_T(DD, PP, WW, false)                          \
-  }
-#define STC_ATTN_LAUNCH_T(DD, PP, WW, TT)                                                         \
-  {                                                                                               \
-    constexpr int lds_bytes = WW * AttnCfg<DD>::WAVE_LDS;                                         \
-    static const hipError_t attr = hipFuncSetAttribute(                                           \
-        (const void*)attn_mfma_kernel<DD, PP, WW, TT>,                                            \
-        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);                                   \
-    if (attr != hipSuccess) return -1;                                                            \
-    attn_mfma_kernel<DD, PP, WW, TT><<<grid, 64 * WW, lds_bytes, st>>>(                           \
-        (const uint16_t*)q, (const uint16_t*)K, (const unsigned char*)vpacked, mask, tok_off,     \
-        page_idx, partial, out, s.Hq, s.Hkv, s.N, NP, s.G, (uint32_t)s.v_cap_groups, k_pages,     \
-        splits, (const uint16_t*)K_tail, (const uint16_t*)V_tail, n_tail, tail_cap, kv_div,       \
-        page_heads, token_cap(s));                                                                \
-  }
-#ifdef STC_TUNE
-#define STC_ATTN_PICK(DD)                                  \
-  if (plan.waves == 8) {                                   \
-    if (plan.ppw == 2) STC_ATTN_LAUNCH(DD, 1, 8)           \
-    else STC_ATTN_LAUNCH(DD, 2, 8)                         \
-  } else {                                                 \
-    if (plan.ppw == 2) STC_ATTN_LAUNCH(DD, 1, 4)           \
-    else STC_ATTN_LAUNCH(DD, 2, 4)                         \
-  }
-#else
-#define STC_ATTN_PICK(DD)                                  \
-  if (plan.waves == 8) STC_ATTN_LAUNCH(DD, 1, 8)           \
-  else STC_ATTN_LAUNCH(DD, 1, 4)
-#endif
-  if (s.D == 128) {
-    STC_ATTN_PICK(128)
-  } else {
-    STC_ATTN_PICK(64)
-  }
-#undef STC_ATTN_PICK
-#undef STC_ATTN_LAUNCH_T
-#undef STC_ATTN_LAUNCH
-  if (hipGetLastError() != hipSuccess) return -1;
-  if (splits > 1) {
+  const int rc = s.D == 128 ? attn_dispatch<128>(a, plan, tail_pages > 0, sel_score != nullptr)
+                            : attn_dispatch<64>(a, plan, tail_pages > 0, sel_score != nullptr);
+  if (rc) return -1;
+  if (plan.splits > 1) {
     if (s.D == 128)
-      attn_combine_kernel<128><<<s.B * s.Hq, 128, 0, st>>>(partial, out, splits);
+      attn_combine_kernel<128><<<s.B * s.Hq, 128, 0, st>>>(a.partial, out, plan.splits);
     else
-      attn_combine_kernel<64><<<s.B * s.Hq, 64, 0, st>>>(partial, out, splits);
+      attn_combine_kernel<64><<<s.B * s.Hq, 64, 0, st>>>(a.partial, out, plan.splits);
     if (hipGetLastError() != hipSuccess) return -1;
   }
   return 0;

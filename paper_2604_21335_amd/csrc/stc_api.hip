@@ -30,6 +30,13 @@ size_t select_ws_bytes(const stc_shape_t* s, bool per_head = false) {
   return (size_t)s->B * (per_head ? s->Hq : s->Hkv) * num_pages(s) * sizeof(float);
 }
 
+// Page scores at the front of the workspace of stc_decode_step, padded so that the attention
+// partials behind them start on a 256-byte boundary.
+size_t step_score_bytes(const stc_shape_t* s, int k_pages) {
+  if (k_pages >= num_pages(s)) return 0;
+  return (select_ws_bytes(s) + 255) & ~(size_t)255;
+}
+
 }  // namespace
 
 extern "C" {
@@ -64,6 +71,9 @@ size_t stc_workspace_bytes(const stc_shape_t* shape, int which_call, int k_pages
     case STC_WS_ATTENTION_PER_HEAD:
       if (k_pages < 1 || k_pages > num_pages(shape)) return 0;
       return stc::attention_ws_bytes(*shape, k_pages, true);
+    case STC_WS_STEP:
+      if (k_pages < 1 || k_pages > num_pages(shape)) return 0;
+      return step_score_bytes(shape, k_pages) + stc::attention_ws_bytes(*shape, k_pages);
     default: return 0;
   }
 }
@@ -161,12 +171,12 @@ int stc_score_pages(const stc_shape_t* shape, const void* q, const void* bounds,
 
 namespace {
 
-int decode_attention_impl(const stc_shape_t* shape, const void* q, const void* K,
-                          const void* vpacked, const uint16_t* mask, const uint32_t* tok_off,
-                          const int32_t* page_idx, int k_pages, const void* K_tail,
-                          const void* V_tail, int n_tail, int tail_cap, bool per_head,
-                          const uint16_t* page_heads, float* out, void* ws, size_t ws_bytes,
-                          void* stream) {
+// Argument checks of the attention calls; launches nothing.
+int decode_attention_check(const stc_shape_t* shape, const void* q, const void* K,
+                           const void* vpacked, const uint16_t* mask, const uint32_t* tok_off,
+                           const int32_t* page_idx, int k_pages, const void* K_tail,
+                           const void* V_tail, int n_tail, int tail_cap, bool per_head,
+                           const float* out, const void* ws, size_t ws_bytes) {
   if (!shape || !q || !K || !vpacked || !mask || !tok_off || !out) return STC_ERR_NULL;
   if (!shape_ok(shape) || k_pages < 1 || k_pages > num_pages(shape) || shape->v_cap_groups < 1)
     return STC_ERR_SHAPE;
@@ -186,9 +196,22 @@ int decode_attention_impl(const stc_shape_t* shape, const void* q, const void* K
   if (per_head && (long long)shape->B * shape->Hq > kMaxGridY) return STC_ERR_SHAPE;
   const size_t need = stc::attention_ws_bytes(*shape, slots, per_head);
   if (need && (!ws || ws_bytes < need || !aligned16(ws))) return STC_ERR_WORKSPACE;
+  return STC_OK;
+}
+
+int decode_attention_impl(const stc_shape_t* shape, const void* q, const void* K,
+                          const void* vpacked, const uint16_t* mask, const uint32_t* tok_off,
+                          const int32_t* page_idx, int k_pages, const void* K_tail,
+                          const void* V_tail, int n_tail, int tail_cap, bool per_head,
+                          const uint16_t* page_heads, float* out, void* ws, size_t ws_bytes,
+                          void* stream) {
+  const int rc = decode_attention_check(shape, q, K, vpacked, mask, tok_off, page_idx, k_pages,
+                                        K_tail, V_tail, n_tail, tail_cap, per_head, out, ws,
+                                        ws_bytes);
+  if (rc) return rc;
   return stc::launch_attention(*shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, K_tail,
-                               V_tail, n_tail, tail_cap, per_head, page_heads, out, ws,
-                               (hipStream_t)stream)
+                               V_tail, n_tail, tail_cap, per_head, page_heads, nullptr, nullptr,
+                               out, ws, (hipStream_t)stream)
              ? STC_ERR_LAUNCH
              : STC_OK;
 }
@@ -218,6 +241,37 @@ int stc_decode_attention_tail(const stc_shape_t* shape, const void* q, const voi
                               size_t ws_bytes, void* stream) {
   return decode_attention_impl(shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, K_tail,
                                V_tail, n_tail, tail_cap, false, nullptr, out, ws, ws_bytes, stream);
+}
+
+int stc_decode_step(const stc_shape_t* shape, const void* q, const void* bounds, const void* K,
+                    const void* vpacked, const uint16_t* mask, const uint32_t* tok_off,
+                    int k_pages, int32_t* page_idx, float* out, void* ws, size_t ws_bytes,
+                    void* stream) {
+  if (!shape || !q || !bounds || !page_idx) return STC_ERR_NULL;
+  if (!shape_ok(shape) || k_pages < 1 || k_pages > num_pages(shape)) return STC_ERR_SHAPE;
+  if (!aligned16(bounds) || !aligned16(page_idx)) return STC_ERR_ALIGN;
+  const size_t sb = step_score_bytes(shape, k_pages);
+  if (sb && (!ws || ws_bytes < sb || !aligned16(ws))) return STC_ERR_WORKSPACE;
+  char* attn_ws = ws ? (char*)ws + sb : nullptr;
+  const size_t attn_bytes = ws_bytes >= sb ? ws_bytes - sb : 0;
+  const int rc = decode_attention_check(shape, q, K, vpacked, mask, tok_off, nullptr, k_pages,
+                                        nullptr, nullptr, 0, 0, false, out, attn_ws, attn_bytes);
+  if (rc) return rc;
+  const hipStream_t st = (hipStream_t)stream;
+  if (k_pages >= num_pages(shape) || !stc::attention_can_select(*shape, k_pages)) {
+    if (stc::launch_select(*shape, q, bounds, k_pages, page_idx, (float*)ws, false, st) ||
+        stc::launch_attention(*shape, q, K, vpacked, mask, tok_off,
+                              k_pages >= num_pages(shape) ? nullptr : page_idx, k_pages, nullptr,
+                              nullptr, 0, 0, false, nullptr, nullptr, nullptr, out, attn_ws, st))
+      return STC_ERR_LAUNCH;
+    return STC_OK;
+  }
+  if (stc::launch_score(*shape, q, bounds, (float*)ws, false, st) ||
+      stc::launch_attention(*shape, q, K, vpacked, mask, tok_off, nullptr, k_pages, nullptr,
+                            nullptr, 0, 0, false, nullptr, (const float*)ws, page_idx, out,
+                            attn_ws, st))
+    return STC_ERR_LAUNCH;
+  return STC_OK;
 }
 
 int stc_flush_tail(const stc_shape_t* shape, const void* K_tail, const void* V_tail, int n_flush,

@@ -37,8 +37,12 @@ size_t attention_ws_bytes(const stc_shape_t& s, int k_pages, bool per_head = fal
 int launch_attention(const stc_shape_t& s, const void* q, const void* K, const void* vpacked,
                      const uint16_t* mask, const uint32_t* tok_off, const int32_t* page_idx,
                      int k_pages, const void* K_tail, const void* V_tail, int n_tail, int tail_cap,
-                     bool per_head, const uint16_t* page_heads, float* out, void* ws,
-                     hipStream_t st);
+                     bool per_head, const uint16_t* page_heads, const float* sel_score,
+                     int32_t* sel_list, float* out, void* ws, hipStream_t st);
+// sel_score != nullptr: no page list is read; the attention workgroups select the k pages of
+// their stream from these scores themselves and write the list to sel_list.  Only if
+// attention_can_select().
+bool attention_can_select(const stc_shape_t& s, int k_pages);
 // Union of the page lists of the query heads of every KV head (ascending, padded with -1) and
 // the heads that selected each page.
 int launch_union_pages(const stc_shape_t& s, const int32_t* page_idx_per_head, int k_pages,

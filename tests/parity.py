@@ -41,8 +41,22 @@ def run_hip(K, V, q, G, k_pages, logits=None, kcount=None, fixed_k=0, mask_in=No
             fixed_k=int(kcount) if np.isscalar(kcount) and kcount is not None else fixed_k,
             mask_in=None if mask_in is None else to_dev_u16(mask_in, dev), global_k=global_k)
     c.page_score.fill_(float("nan"))
-    c.step(dq)
-    torch.cuda.synchronize()
+    if k_pages < (N + 15) // 16:
+        # the step as two calls (selection, attention) and as one: the same bits
+        c.step(dq, one_call=False)
+        torch.cuda.synchronize()
+        two = (c.page_idx.clone(), c.out.clone(), c.page_score.clone())
+        c.page_score.fill_(float("nan"))
+        c.page_idx.fill_(-7)
+        c.out.fill_(float("nan"))
+        c.step(dq)
+        torch.cuda.synchronize()
+        assert torch.equal(two[0], c.page_idx), "page lists of the one-call step differ"
+        assert torch.equal(two[1], c.out), "outputs of the one-call step differ"
+        assert torch.equal(two[2].view(torch.int32), c.page_score.view(torch.int32))
+    else:
+        c.step(dq)
+        torch.cuda.synchronize()
     return {
         "bounds": host_bf16(c.bounds_rows()), "bounds_raw": host_bf16(c.bounds), "mask": host_u16(c.mask),
         "tok_off": c.tok_off.cpu().numpy().view(np.uint32), "vpacked": host_bf16(c.vpacked),

@@ -97,6 +97,19 @@ def test_null_alignment_and_workspace_errors():
     assert att2(None, big) == stc.STC_ERR_WORKSPACE
     assert lib.stc_decode_attention(ctypes.byref(_shape(v_cap_groups=0)), FAKE, FAKE, FAKE, FAKE,
                                     FAKE, FAKE, 7, FAKE, FAKE, big, None) == stc.STC_ERR_SHAPE
+    # one-call step: workspace = scores + attention partials, page list required
+    step = lambda q, idx, k, ws, wsb, sh=s2: lib.stc_decode_step(  # noqa: E731
+        ctypes.byref(sh), q, FAKE, FAKE, FAKE, FAKE, FAKE, k, idx, FAKE, ws, wsb, None)
+    need_step = stc.stc_workspace_bytes(s2, stc.STC_WS_STEP, 64)
+    assert need_step >= need + stc.stc_workspace_bytes(s2, stc.STC_WS_SELECT, 64)
+    assert step(FAKE, FAKE, 64, FAKE, need_step - 1) == stc.STC_ERR_WORKSPACE
+    assert step(FAKE, FAKE, 64, None, big) == stc.STC_ERR_WORKSPACE
+    assert step(FAKE, None, 64, FAKE, big) == stc.STC_ERR_NULL
+    assert step(None, FAKE, 64, FAKE, big) == stc.STC_ERR_NULL
+    assert step(FAKE, ODD, 64, FAKE, big) == stc.STC_ERR_ALIGN
+    assert step(FAKE, FAKE, 0, FAKE, big) == stc.STC_ERR_SHAPE
+    assert step(FAKE, FAKE, 257, FAKE, big) == stc.STC_ERR_SHAPE
+    assert stc.stc_workspace_bytes(s, stc.STC_WS_STEP, 7) == 0       # every page kept, one split
     # attention with a tail: tail arguments
     tail = lambda kt, vt, n, capt: lib.stc_decode_attention_tail(  # noqa: E731
         r, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 7, kt, vt, n, capt, FAKE, FAKE, big, None)

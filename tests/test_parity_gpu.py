@@ -128,6 +128,43 @@ def test_missing_page_list_means_leading_pages():
             assert np.array_equal(a.cpu().numpy(), hip["out"])
 
 
+@pytest.mark.parametrize("B,Hkv,R,N,k", [
+    (16, 4, 2, 32768, 128),     # 64 streams x 8 workgroups: selection inside the attention kernel
+    (16, 4, 2, 32768, 144),     # 9 workgroups per stream: selection launch + attention launch
+    (2, 2, 7, 32784, 128),      # 2049 pages: one too many for the keys held in registers
+    (3, 1, 4, 4000, 7),         # workgroups of 4 wavefronts, ragged last page
+    (1, 2, 1, 3333, 100),       # 7 workgroups of 8 wavefronts, ragged list end
+])
+def test_decode_step_is_the_two_calls_in_one(B, Hkv, R, N, k):
+    """stc_decode_step through the C ABI with a workspace of its own, used twice without
+    clearing: page list and output bit for bit those of stc_select_pages followed by
+    stc_decode_attention, on both sides of every switch between its two launch plans."""
+    Hq, D, G = Hkv * R, 128, 8
+    dev = "cuda:0"
+    g = torch.Generator(device=dev)
+    g.manual_seed(N + k)
+    K = torch.randn(B, Hkv, N, D, device=dev, generator=g).bfloat16()
+    V = torch.randn(B, Hkv, N, D, device=dev, generator=g).bfloat16()
+    logits = torch.randn(B, Hkv, N, G, device=dev, generator=g)
+    c = stc.RoutedCache(B, Hq, Hkv, D, N, G, k, device=dev)
+    c.build(K, V, logits=logits, fixed_k=3)
+    ws = torch.full((stc.stc_workspace_bytes(c.shape, stc.STC_WS_STEP, k),), 0xA5,
+                    dtype=torch.uint8, device=dev)
+    for trial in range(2):
+        q = torch.randn(B, Hq, D, device=dev, generator=g).bfloat16()
+        c.step(q, one_call=False)
+        idx = torch.full_like(c.page_idx, -3)
+        out = torch.full_like(c.out, float("nan"))
+        stc.stc_decode_step(c.shape, q, c.bounds, c.K, c.vpacked, c.mask, c.tok_off, k, idx, out, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(idx, c.page_idx)
+        assert torch.equal(out, c.out)
+    # the list against the oracle on one stream (the two-call path is checked everywhere else)
+    b, h = B - 1, Hkv - 1
+    sc = O.page_scores(W.bf16_bits(q[b, h * R:(h + 1) * R]), O.page_bounds(W.bf16_bits(K[b, h])))
+    assert np.array_equal(idx[b, h].cpu().numpy(), O.select_pages(sc, k))
+
+
 def test_parity_very_long_stream():
     """More than 8192 pages per stream (the selection kernel that re-reads its keys from
     memory) and an attention over 300 pages split over many workgroups."""
