@@ -19,6 +19,7 @@
  *                        (token-level compaction helper)
  *   decode step          stc_select_pages (+ stc_score_pages: its scoring half alone),
  *                        stc_decode_attention; stc_decode_step does both in one call
+ *                        (stc_decode_step_tail: with the uncompressed tail)
  *   recent tokens        stc_append_tail, stc_decode_attention_tail (uncompressed tail),
  *                        stc_flush_tail (tail tokens into the compressed cache, in place)
  *   per-query-head form  stc_select_pages_per_head, stc_decode_attention_per_head,
@@ -81,7 +82,8 @@ enum {
   STC_WS_ATTENTION_TAIL = 4,
   STC_WS_SELECT_PER_HEAD = 5,
   STC_WS_ATTENTION_PER_HEAD = 6,
-  STC_WS_STEP = 7
+  STC_WS_STEP = 7,
+  STC_WS_STEP_TAIL = 8
 };
 
 /* routing modes of stc_route_and_pack_values */
@@ -95,8 +97,8 @@ int stc_version(void);
 const char *stc_status_string(int status);
 
 /* Bytes of device workspace the given call needs for this shape (0 = none).
- * k_pages is only used by STC_WS_SELECT / STC_WS_ATTENTION / STC_WS_ATTENTION_TAIL (for the
- * last one it is the number of selected pages plus ceil(n_tail / P), at their largest).  Returns 0 for an
+ * k_pages is not used by STC_WS_ROUTE.  For STC_WS_ATTENTION_TAIL and STC_WS_STEP_TAIL it is
+ * the number of selected pages plus ceil(n_tail / P), at their largest.  Returns 0 for an
  * invalid shape (the call itself then reports the error). */
 size_t stc_workspace_bytes(const stc_shape_t *shape, int which_call, int k_pages);
 
@@ -236,6 +238,18 @@ int stc_decode_attention_tail(const stc_shape_t *shape, const void *q, const voi
                               const int32_t *page_idx, int k_pages, const void *K_tail,
                               const void *V_tail, int n_tail, int tail_cap, float *out, void *ws,
                               size_t ws_bytes, void *stream);
+
+/*
+ * stc_decode_step with the uncompressed tail of stc_decode_attention_tail: the same results bit
+ * for bit as stc_select_pages followed by stc_decode_attention_tail.
+ *   ws       stc_workspace_bytes(shape, STC_WS_STEP_TAIL, k_pages + ceil(n_tail/P)) bytes, the
+ *            second argument at its largest (as for STC_WS_ATTENTION_TAIL)
+ */
+int stc_decode_step_tail(const stc_shape_t *shape, const void *q, const void *bounds,
+                         const void *K, const void *vpacked, const uint16_t *mask,
+                         const uint32_t *tok_off, int k_pages, const void *K_tail,
+                         const void *V_tail, int n_tail, int tail_cap, int32_t *page_idx,
+                         float *out, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Per-step append: writes the new token's key and value of every stream (k_new, v_new

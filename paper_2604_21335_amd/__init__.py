@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libstc.so")
 STC_OK = 0
 STC_ERR_NULL, STC_ERR_SHAPE, STC_ERR_ALIGN, STC_ERR_WORKSPACE, STC_ERR_LAUNCH = -1, -2, -3, -4, -5
 STC_WS_ROUTE, STC_WS_SELECT, STC_WS_ATTENTION, STC_WS_ATTENTION_TAIL = 1, 2, 3, 4
-STC_WS_SELECT_PER_HEAD, STC_WS_ATTENTION_PER_HEAD, STC_WS_STEP = 5, 6, 7
+STC_WS_SELECT_PER_HEAD, STC_WS_ATTENTION_PER_HEAD, STC_WS_STEP, STC_WS_STEP_TAIL = 5, 6, 7, 8
 STC_ROUTE_MASK, STC_ROUTE_TOPK, STC_ROUTE_GLOBAL = 0, 1, 2
 
 EXPORTS = ["stc_version", "stc_status_string", "stc_workspace_bytes", "stc_bounds_bytes",
@@ -26,7 +26,7 @@ EXPORTS = ["stc_version", "stc_status_string", "stc_workspace_bytes", "stc_bound
            "stc_route_and_pack_values", "stc_select_pages", "stc_score_pages", "stc_decode_attention", "stc_decode_attention_tail", "stc_append_tail",
            "stc_select_pages_per_head", "stc_decode_attention_per_head", "stc_router_logits",
            "stc_union_pages", "stc_decode_attention_union", "stc_flush_tail",
-           "stc_compact_tokens", "stc_decode_step"]
+           "stc_compact_tokens", "stc_decode_step", "stc_decode_step_tail"]
 
 
 class StcError(RuntimeError):
@@ -98,6 +98,9 @@ def load_library():
                                               ctypes.c_int, ctypes.c_int, vp, vp, sz, vp]
     lib.stc_decode_step.restype = ctypes.c_int
     lib.stc_decode_step.argtypes = [shp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp, vp, sz, vp]
+    lib.stc_decode_step_tail.restype = ctypes.c_int
+    lib.stc_decode_step_tail.argtypes = [shp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp,
+                                         ctypes.c_int, ctypes.c_int, vp, vp, vp, sz, vp]
     lib.stc_append_tail.restype = ctypes.c_int
     lib.stc_append_tail.argtypes = [shp, vp, vp, vp, vp, ctypes.c_int, ctypes.c_int, vp]
     lib.stc_router_logits.restype = ctypes.c_int
@@ -264,6 +267,18 @@ def stc_decode_step(shape, q, bounds, K, vpacked, mask, tok_off, k_pages, page_i
         _ptr(ws, None, "ws"), _nbytes(ws), _stream()), "stc_decode_step")
 
 
+def stc_decode_step_tail(shape, q, bounds, K, vpacked, mask, tok_off, k_pages, K_tail, V_tail,
+                         n_tail, tail_cap, page_idx, out, ws):
+    _check(load_library().stc_decode_step_tail(
+        ctypes.byref(shape), _ptr(q, torch.bfloat16, "q"), _ptr(bounds, torch.bfloat16, "bounds"),
+        _ptr(K, torch.bfloat16, "K"), _ptr(vpacked, torch.bfloat16, "vpacked"),
+        _ptr(mask, _U16, "mask"), _ptr(tok_off, _U32, "tok_off"), int(k_pages),
+        _ptr(K_tail, torch.bfloat16, "K_tail"), _ptr(V_tail, torch.bfloat16, "V_tail"),
+        int(n_tail), int(tail_cap), _ptr(page_idx, torch.int32, "page_idx"),
+        _ptr(out, torch.float32, "out"), _ptr(ws, None, "ws"), _nbytes(ws), _stream()),
+        "stc_decode_step_tail")
+
+
 def stc_decode_attention_tail(shape, q, K, vpacked, mask, tok_off, page_idx, k_pages, K_tail,
                               V_tail, n_tail, tail_cap, out, ws):
     _check(load_library().stc_decode_attention_tail(
@@ -336,7 +351,6 @@ class RoutedCache:
         self._ws_route = self._ws(STC_WS_ROUTE, 0)
         self._ws_select = self._ws(STC_WS_SELECT, k_pages)
         self._ws_attn = self._ws(STC_WS_ATTENTION, self.k_eff)
-        self._alloc_step()
         self.K = (torch.empty(B, Hkv, n_cap, D, dtype=torch.bfloat16, device=dev)
                   if n_cap else None)
         # uncompressed tail of recent tokens (tail_cap = 0: none)
@@ -345,15 +359,19 @@ class RoutedCache:
             self.K_tail = torch.empty(B, Hkv, tail_cap, D, dtype=torch.bfloat16, device=dev)
             self.V_tail = torch.empty_like(self.K_tail)
             self._ws_attn = self._ws(STC_WS_ATTENTION_TAIL, self.k_eff + (tail_cap + 15) // 16)
+        self._alloc_step()
 
     def _alloc_step(self):
         """Workspace of stc_decode_step.  The page scores are at its front: page_score is a view
         of them, so that both forms of step() leave the scores there."""
-        self._ws_step = self._ws(STC_WS_STEP, self.k_eff)
+        if self.tail_cap:
+            self._ws_step = self._ws(STC_WS_STEP_TAIL, self.k_eff + (self.tail_cap + 15) // 16)
+        else:
+            self._ws_step = self._ws(STC_WS_STEP, self.k_eff)
         self.page_score = None
         if self.keep_scores:
             n = self.B * self.Hkv * self.NP
-            src = (self._ws_step if self.k_pages < self.NP else
+            src = (self._ws_step if self.k_pages < self.NP or self.tail_cap else
                    torch.empty(4 * n, dtype=torch.uint8, device=self.device))
             self.page_score = src[:4 * n].view(torch.float32).view(self.B, self.Hkv, self.NP)
 
@@ -433,7 +451,13 @@ class RoutedCache:
         one_call: through stc_decode_step (the page scores then stay in its workspace)
         instead of stc_select_pages + stc_decode_attention."""
         if self.k_pages < self.NP:
-            if one_call and not self.tail_cap:
+            if one_call and self.tail_cap:
+                stc_decode_step_tail(self.shape, q, self.bounds, self.K, self.vpacked, self.mask,
+                                     self.tok_off, self.k_eff, self.K_tail, self.V_tail,
+                                     self.n_tail, self.tail_cap, self.page_idx, self.out,
+                                     self._ws_step)
+                return self.out
+            if one_call:
                 stc_decode_step(self.shape, q, self.bounds, self.K, self.vpacked, self.mask,
                                 self.tok_off, self.k_eff, self.page_idx, self.out, self._ws_step)
                 return self.out

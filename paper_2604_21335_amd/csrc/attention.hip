@@ -108,7 +108,8 @@ __device__ long long* stc_dbg_ptr = nullptr;
 // stay in flight across the arithmetic.
 // SELECT_IPT > 0: no page list is given; every workgroup first selects the stream's k pages
 // from the page scores itself (the same selection as the stand-alone kernel, SELECT_IPT keys
-// per thread), keeps the ones of its own split and writes them to the list.
+// per thread), keeps the ones of its own split and writes them to the list.  Tail pages keep
+// their slots behind the k selected ones.
 template <int D, int PAIRS, int WAVES, bool TAIL, int SELECT_IPT>
 __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K,
@@ -184,7 +185,7 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
                                          }
                                        });
     __syncthreads();
-    my_pg = lane < npages ? s_pages[wave * ppw + lane] : -1;
+    if (lane < npages && pi0 + lane < k_pages) my_pg = s_pages[wave * ppw + lane];
   }
   const int npairs = (npages + 1) / 2;
 
@@ -628,9 +629,10 @@ int attn_go(const AttnArgs& a) {
 
 template <int D>
 int attn_dispatch(const AttnArgs& a, const AttnPlan& plan, bool tail, bool select) {
-  if (select) {  // selection inside the kernel: no tail, 2048 keys over the workgroup's threads
-    if (plan.waves == 8) return attn_go<D, 1, 8, false, 4>(a);
-    return attn_go<D, 1, 4, false, 8>(a);
+  if (select) {  // selection inside the kernel: 2048 keys over the workgroup's threads
+    if (plan.waves == 8)
+      return tail ? attn_go<D, 1, 8, true, 4>(a) : attn_go<D, 1, 8, false, 4>(a);
+    return tail ? attn_go<D, 1, 4, true, 8>(a) : attn_go<D, 1, 4, false, 8>(a);
   }
 #ifdef STC_TUNE
   if (plan.ppw == 4) {
@@ -649,10 +651,10 @@ int attn_dispatch(const AttnArgs& a, const AttnPlan& plan, bool tail, bool selec
 // Measured against the separate selection launch it is faster while all workgroups are
 // resident at once (two per compute unit) and a stream's keys fit four per thread, and
 // slower beyond (the repeated prologue then delays a second round of workgroups).
-bool attention_can_select(const stc_shape_t& s, int k_pages) {
+bool attention_can_select(const stc_shape_t& s, int k_pages, int tail_pages) {
   const int NP = (s.N + kPage - 1) / kPage;
   if (k_pages >= NP || NP > 2048) return false;
-  return (long long)s.B * s.Hkv * attention_plan(s, k_pages).splits <= 512;
+  return (long long)s.B * s.Hkv * attention_plan(s, k_pages + tail_pages).splits <= 512;
 }
 
 int launch_attention(const stc_shape_t& s0, const void* q, const void* K, const void* vpacked,
@@ -671,7 +673,7 @@ int launch_attention(const stc_shape_t& s0, const void* q, const void* K, const 
              k_pages, plan.splits, (const uint16_t*)K_tail, (const uint16_t*)V_tail, n_tail,
              tail_cap, per_head ? s0.Hq / s0.Hkv : 1, page_heads, token_cap(s), sel_score,
              sel_list, dim3(plan.splits, streams), st};
-  if (sel_score && (NP > 2048 || tail_pages || per_head || page_heads)) return -1;
+  if (sel_score && (NP > 2048 || per_head || page_heads)) return -1;
 #ifdef STC_TUNE
   {
     long long* p = nullptr;

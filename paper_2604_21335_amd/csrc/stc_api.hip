@@ -74,6 +74,9 @@ size_t stc_workspace_bytes(const stc_shape_t* shape, int which_call, int k_pages
     case STC_WS_STEP:
       if (k_pages < 1 || k_pages > num_pages(shape)) return 0;
       return step_score_bytes(shape, k_pages) + stc::attention_ws_bytes(*shape, k_pages);
+    case STC_WS_STEP_TAIL:  // k_pages counts the tail's pages too; scores always have room
+      if (k_pages < 1) return 0;
+      return step_score_bytes(shape, 0) + stc::attention_ws_bytes(*shape, k_pages);
     default: return 0;
   }
 }
@@ -243,35 +246,67 @@ int stc_decode_attention_tail(const stc_shape_t* shape, const void* q, const voi
                                V_tail, n_tail, tail_cap, false, nullptr, out, ws, ws_bytes, stream);
 }
 
-int stc_decode_step(const stc_shape_t* shape, const void* q, const void* bounds, const void* K,
-                    const void* vpacked, const uint16_t* mask, const uint32_t* tok_off,
-                    int k_pages, int32_t* page_idx, float* out, void* ws, size_t ws_bytes,
-                    void* stream) {
+namespace {
+
+// Selection followed by attention (with or without a tail) on one stream.  score_bytes =
+// size of the score region at the front of the workspace.
+int decode_step_impl(const stc_shape_t* shape, const void* q, const void* bounds, const void* K,
+                     const void* vpacked, const uint16_t* mask, const uint32_t* tok_off,
+                     int k_pages, const void* K_tail, const void* V_tail, int n_tail,
+                     int tail_cap, int32_t* page_idx, float* out, void* ws, size_t ws_bytes,
+                     size_t score_bytes, void* stream) {
   if (!shape || !q || !bounds || !page_idx) return STC_ERR_NULL;
   if (!shape_ok(shape) || k_pages < 1 || k_pages > num_pages(shape)) return STC_ERR_SHAPE;
   if (!aligned16(bounds) || !aligned16(page_idx)) return STC_ERR_ALIGN;
-  const size_t sb = step_score_bytes(shape, k_pages);
-  if (sb && (!ws || ws_bytes < sb || !aligned16(ws))) return STC_ERR_WORKSPACE;
-  char* attn_ws = ws ? (char*)ws + sb : nullptr;
-  const size_t attn_bytes = ws_bytes >= sb ? ws_bytes - sb : 0;
+  const bool selecting = k_pages < num_pages(shape);
+  if (selecting && (!ws || ws_bytes < score_bytes || !aligned16(ws))) return STC_ERR_WORKSPACE;
+  char* attn_ws = ws ? (char*)ws + score_bytes : nullptr;
+  const size_t attn_bytes = ws_bytes >= score_bytes ? ws_bytes - score_bytes : 0;
   const int rc = decode_attention_check(shape, q, K, vpacked, mask, tok_off, nullptr, k_pages,
-                                        nullptr, nullptr, 0, 0, false, out, attn_ws, attn_bytes);
+                                        K_tail, V_tail, n_tail, tail_cap, false, out, attn_ws,
+                                        attn_bytes);
   if (rc) return rc;
   const hipStream_t st = (hipStream_t)stream;
-  if (k_pages >= num_pages(shape) || !stc::attention_can_select(*shape, k_pages)) {
+  const int tail_pages = (n_tail + shape->P - 1) / shape->P;
+  if (!selecting || !stc::attention_can_select(*shape, k_pages, tail_pages)) {
     if (stc::launch_select(*shape, q, bounds, k_pages, page_idx, (float*)ws, false, st) ||
         stc::launch_attention(*shape, q, K, vpacked, mask, tok_off,
-                              k_pages >= num_pages(shape) ? nullptr : page_idx, k_pages, nullptr,
-                              nullptr, 0, 0, false, nullptr, nullptr, nullptr, out, attn_ws, st))
+                              selecting ? page_idx : nullptr, k_pages, K_tail, V_tail, n_tail,
+                              tail_cap, false, nullptr, nullptr, nullptr, out, attn_ws, st))
       return STC_ERR_LAUNCH;
     return STC_OK;
   }
   if (stc::launch_score(*shape, q, bounds, (float*)ws, false, st) ||
-      stc::launch_attention(*shape, q, K, vpacked, mask, tok_off, nullptr, k_pages, nullptr,
-                            nullptr, 0, 0, false, nullptr, (const float*)ws, page_idx, out,
-                            attn_ws, st))
+      stc::launch_attention(*shape, q, K, vpacked, mask, tok_off, nullptr, k_pages, K_tail,
+                            V_tail, n_tail, tail_cap, false, nullptr, (const float*)ws, page_idx,
+                            out, attn_ws, st))
     return STC_ERR_LAUNCH;
   return STC_OK;
+}
+
+}  // namespace
+
+int stc_decode_step(const stc_shape_t* shape, const void* q, const void* bounds, const void* K,
+                    const void* vpacked, const uint16_t* mask, const uint32_t* tok_off,
+                    int k_pages, int32_t* page_idx, float* out, void* ws, size_t ws_bytes,
+                    void* stream) {
+  if (!shape) return STC_ERR_NULL;
+  if (!shape_ok(shape)) return STC_ERR_SHAPE;
+  return decode_step_impl(shape, q, bounds, K, vpacked, mask, tok_off, k_pages, nullptr, nullptr,
+                          0, 0, page_idx, out, ws, ws_bytes, step_score_bytes(shape, k_pages),
+                          stream);
+}
+
+int stc_decode_step_tail(const stc_shape_t* shape, const void* q, const void* bounds,
+                         const void* K, const void* vpacked, const uint16_t* mask,
+                         const uint32_t* tok_off, int k_pages, const void* K_tail,
+                         const void* V_tail, int n_tail, int tail_cap, int32_t* page_idx,
+                         float* out, void* ws, size_t ws_bytes, void* stream) {
+  if (!shape) return STC_ERR_NULL;
+  if (!shape_ok(shape)) return STC_ERR_SHAPE;
+  return decode_step_impl(shape, q, bounds, K, vpacked, mask, tok_off, k_pages, K_tail, V_tail,
+                          n_tail, tail_cap, page_idx, out, ws, ws_bytes,
+                          step_score_bytes(shape, 0), stream);
 }
 
 int stc_flush_tail(const stc_shape_t* shape, const void* K_tail, const void* V_tail, int n_flush,

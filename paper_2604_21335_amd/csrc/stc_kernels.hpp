@@ -42,7 +42,7 @@ int launch_attention(const stc_shape_t& s, const void* q, const void* K, const v
 // sel_score != nullptr: no page list is read; the attention workgroups select the k pages of
 // their stream from these scores themselves and write the list to sel_list.  Only if
 // attention_can_select().
-bool attention_can_select(const stc_shape_t& s, int k_pages);
+bool attention_can_select(const stc_shape_t& s, int k_pages, int tail_pages);
 // Union of the page lists of the query heads of every KV head (ascending, padded with -1) and
 // the heads that selected each page.
 int launch_union_pages(const stc_shape_t& s, const int32_t* page_idx_per_head, int k_pages,

@@ -110,6 +110,14 @@ def test_null_alignment_and_workspace_errors():
     assert step(FAKE, FAKE, 0, FAKE, big) == stc.STC_ERR_SHAPE
     assert step(FAKE, FAKE, 257, FAKE, big) == stc.STC_ERR_SHAPE
     assert stc.stc_workspace_bytes(s, stc.STC_WS_STEP, 7) == 0       # every page kept, one split
+    stept = lambda n, capt, ws, wsb: lib.stc_decode_step_tail(  # noqa: E731
+        ctypes.byref(s2), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 64, FAKE, FAKE, n, capt, FAKE, FAKE,
+        ws, wsb, None)
+    need_tail = stc.stc_workspace_bytes(s2, stc.STC_WS_STEP_TAIL, 64 + 3)
+    assert need_tail >= need_step
+    assert stept(40, 48, FAKE, need_tail - 1) == stc.STC_ERR_WORKSPACE
+    assert stept(49, 48, FAKE, big) == stc.STC_ERR_SHAPE
+    assert stept(-1, 48, FAKE, big) == stc.STC_ERR_SHAPE
     # attention with a tail: tail arguments
     tail = lambda kt, vt, n, capt: lib.stc_decode_attention_tail(  # noqa: E731
         r, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 7, kt, vt, n, capt, FAKE, FAKE, big, None)

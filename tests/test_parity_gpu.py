@@ -298,7 +298,14 @@ def test_attention_with_uncompressed_tail(B, Hq, Hkv, D, N, G, k, ntail):
     out0 = torch.full_like(c.out, float("nan"))
     stc.stc_decode_attention_tail(shp, dq, c.K, c.vpacked, c.mask, c.tok_off, c.page_idx, c.k_eff,
                                   None, None, 0, 0, out0, ws)
+    # selection + attention with the tail in one call: the bits of the two calls
+    ws1 = torch.full((max(16, stc.stc_workspace_bytes(shp, stc.STC_WS_STEP_TAIL, slots)),), 0x5A,
+                     dtype=torch.uint8, device="cuda:0")
+    out1, idx1 = torch.full_like(c.out, float("nan")), torch.full_like(c.page_idx, -9)
+    stc.stc_decode_step_tail(shp, dq, c.bounds, c.K, c.vpacked, c.mask, c.tok_off, c.k_eff, dKt, dVt,
+                             ntail, cap_t, idx1, out1, ws1)
     torch.cuda.synchronize()
+    assert torch.equal(idx1, c.page_idx) and torch.equal(out1, out)
     assert np.array_equal(out0.cpu().numpy(), hip["out"])
     got = out.cpu().numpy()
     R = Hq // Hkv
@@ -329,8 +336,14 @@ def test_append_then_attend_step_by_step():
     for s_ in range(steps):
         qs = randn_bf16(rng, (B, Hq, D))
         c.append(PT.to_dev_bf16(new_k[s_]), PT.to_dev_bf16(new_v[s_]))
+        c.step(PT.to_dev_bf16(qs), one_call=False)
+        torch.cuda.synchronize()
+        two = (c.page_idx.clone(), c.out.clone())
+        c.page_idx.fill_(-5)
+        c.out.fill_(float("nan"))
         c.step(PT.to_dev_bf16(qs))
         torch.cuda.synchronize()
+        assert torch.equal(two[0], c.page_idx) and torch.equal(two[1], c.out)
         assert c.n_tail == s_ + 1
         got, idx = c.out.cpu().numpy(), c.page_idx.cpu().numpy()
         for (b, h) in ((0, 0), (1, 1)):
