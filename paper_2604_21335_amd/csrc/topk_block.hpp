@@ -5,12 +5,43 @@
 
 namespace stc {
 
-__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
-  for (int d = 1; d < 64; d <<= 1) {
-    const int o = __shfl_up(v, d);
-    if (lane >= d) v += o;
-  }
+// One step of a wavefront scan on the data-parallel-primitive path (no LDS traffic): lanes
+// whose source lies outside the row, or whose row is masked off, combine with `ident`.
+#define STC_DPP_STEP(v, op, ident, ctrl, row_mask) \
+  v = op(v, (uint32_t)__builtin_amdgcn_update_dpp((int)(ident), (int)(v), ctrl, row_mask, 0xf, false))
+
+struct OpAdd {
+  __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return a + b; }
+};
+struct OpMin {
+  __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return min(a, b); }
+};
+struct OpMax {
+  __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return max(a, b); }
+};
+
+// Inclusive scan over the 64 lanes: shifts by 1, 2, 4, 8 inside each row of 16 lanes, then
+// lane 15 of rows 0 and 2 into rows 1 and 3, then lane 31 into rows 2 and 3.
+template <class Op>
+__device__ __forceinline__ uint32_t wave_scan(uint32_t v, Op op, uint32_t ident) {
+  STC_DPP_STEP(v, op, ident, 0x111, 0xf);  // row_shr:1
+  STC_DPP_STEP(v, op, ident, 0x112, 0xf);  // row_shr:2
+  STC_DPP_STEP(v, op, ident, 0x114, 0xf);  // row_shr:4
+  STC_DPP_STEP(v, op, ident, 0x118, 0xf);  // row_shr:8
+  STC_DPP_STEP(v, op, ident, 0x142, 0xa);  // row_bcast:15 into rows 1 and 3
+  STC_DPP_STEP(v, op, ident, 0x143, 0xc);  // row_bcast:31 into rows 2 and 3
   return v;
+}
+#undef STC_DPP_STEP
+
+// Reduction over the 64 lanes, in a scalar register.
+template <class Op>
+__device__ __forceinline__ uint32_t wave_reduce(uint32_t v, Op op, uint32_t ident) {
+  return (uint32_t)__builtin_amdgcn_readlane((int)wave_scan(v, op, ident), 63);
+}
+
+__device__ __forceinline__ int wave_incl_scan(int v, int /*lane*/) {
+  return (int)wave_scan((uint32_t)v, OpAdd{}, 0u);
 }
 
 // Exclusive scan over the block (thread order); *total = block sum.
@@ -31,21 +62,45 @@ __device__ __forceinline__ int block_exscan(int v, int* lds_waves, int* total) {
   return base + inc - v;
 }
 
+// The same scan for callers that keep two buffers of per-wavefront sums and alternate
+// between them: a buffer is written again two barriers after it was last read at the
+// earliest, so the barrier behind the reads can go.
+template <int NW>
+__device__ __forceinline__ uint32_t block_exscan_once(uint32_t v, uint32_t* lds_waves,
+                                                      uint32_t* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t inc = wave_scan(v, OpAdd{}, 0u);
+  if (lane == 63) lds_waves[wave] = inc;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    const uint32_t x = lds_waves[w];
+    if (w < wave) base += x;
+    tot += x;
+  }
+  *total = tot;
+  return base + inc - v;
+}
+
 // Top-k pages of a stream by one workgroup of THREADS threads with the keys held in
-// registers: thread t owns the IPT adjacent pages t*IPT .. (NP <= THREADS * IPT).  The selected
-// pages are handed to emit(position in the ascending list, page).  Each radix pass is a
-// shared-memory histogram of one key byte, a block scan over the digits in descending
-// order and a broadcast of the digit that holds the k-th largest key.
+// registers: thread t owns the IPT adjacent pages t*IPT .. (NP <= THREADS * IPT <= 65535).
+// The selected pages are handed to emit(position in the ascending list, page).  Each radix
+// pass is a shared-memory histogram of one key byte, a block scan over the digits in
+// descending order and a broadcast of the digit that holds the k-th largest key.
 template <int IPT, int THREADS, class Emit>
 __device__ __forceinline__ void topk_block(const float* __restrict__ sc, int NP, int k,
                                            Emit emit) {
+  constexpr int NW = THREADS / 64;
   __shared__ int hist[256];
-  __shared__ int waves[THREADS / 64];
+  __shared__ uint32_t waves[2][NW];  // per-wavefront sums of the block scans, alternating
+  __shared__ uint32_t s_min[NW], s_max[NW];
   __shared__ uint32_t s_prefix;
   __shared__ int s_remaining, s_cand, s_ncand;
   __shared__ uint32_t cand[64];
   const int tid = threadIdx.x;
   const int i0 = tid * IPT;
+  int flip = 0;  // which buffer of `waves` the next scan uses
 
   // keys of absent pages (index >= NP) are 0, below the key of any finite float
   uint32_t key[IPT];
@@ -65,6 +120,7 @@ __device__ __forceinline__ void topk_block(const float* __restrict__ sc, int NP,
 #pragma unroll
     for (int j = 0; j < IPT; ++j) key[j] = i0 + j < NP ? float_key(sc[i0 + j]) : 0u;
   }
+  if (tid < 256) hist[tid] = 0;
 
   // Bits above the highest bit in which two keys differ are common to all keys and
   // need no pass; starting at that bit also spreads the first histogram over many
@@ -73,15 +129,12 @@ __device__ __forceinline__ void topk_block(const float* __restrict__ sc, int NP,
 #pragma unroll
   for (int j = 0; j < IPT; ++j)
     if (i0 + j < NP) kmin = min(kmin, key[j]), kmax = max(kmax, key[j]);
-  for (int d = 32; d >= 1; d >>= 1) {
-    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, d));
-    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, d));
-  }
-  __shared__ uint32_t s_min[THREADS / 64], s_max[THREADS / 64];
+  kmin = wave_reduce(kmin, OpMin{}, 0xffffffffu);
+  kmax = wave_reduce(kmax, OpMax{}, 0u);
   if ((tid & 63) == 0) s_min[tid >> 6] = kmin, s_max[tid >> 6] = kmax;
   __syncthreads();
 #pragma unroll
-  for (int w = 0; w < THREADS / 64; ++w) kmin = min(kmin, s_min[w]), kmax = max(kmax, s_max[w]);
+  for (int w = 0; w < NW; ++w) kmin = min(kmin, s_min[w]), kmax = max(kmax, s_max[w]);
   const uint32_t diff = kmin ^ kmax;
   const int top = diff ? 31 - __clz(diff) : 0;  // highest differing bit
   int shift = max(top - 7, 0);
@@ -89,19 +142,23 @@ __device__ __forceinline__ void topk_block(const float* __restrict__ sc, int NP,
   uint32_t prefix = kmax & decided;
   int remaining = k;  // rank of the k-th largest key among the keys sharing the prefix
   // The last window may overlap bits that are already fixed; keys are filtered on all
-  // fixed bits, so the digit found repeats them.
+  // fixed bits, so the digit found repeats them.  The histogram is zero on entry to every
+  // pass: each bin is cleared by the thread that read it.
   for (;; shift = max(shift - 8, 0)) {
-    if (tid < 256) hist[tid] = 0;
-    __syncthreads();
 #pragma unroll
     for (int j = 0; j < IPT; ++j) {
       const bool in = (key[j] & decided) == prefix;
       if (in && i0 + j < NP) atomicAdd(&hist[(key[j] >> shift) & 255u], 1);
     }
     __syncthreads();
-    const int cnt = tid < 256 ? hist[255 - tid] : 0;  // digits in descending order
-    int tot;
-    const int above = block_exscan(cnt, waves, &tot);  // keys with a larger digit
+    int cnt = 0;
+    if (tid < 256) {
+      cnt = hist[255 - tid];  // digits in descending order
+      hist[255 - tid] = 0;
+    }
+    uint32_t tot;
+    const int above = (int)block_exscan_once<NW>((uint32_t)cnt, waves[flip], &tot);
+    flip ^= 1;
     if (tid < 256 && above < remaining && remaining <= above + cnt) {
       s_prefix = (prefix & ~(255u << shift)) | ((uint32_t)(255 - tid) << shift);
       s_remaining = remaining - above;
@@ -113,13 +170,13 @@ __device__ __forceinline__ void topk_block(const float* __restrict__ sc, int NP,
     remaining = s_remaining;
     decided = ~((1u << shift) - 1u);
     if (shift == 0) break;
-    if (s_cand <= 64) {
+    const int c = s_cand;
+    if (c <= 64) {
       // Few keys are left: list them, and let one wavefront rank them directly.
 #pragma unroll
       for (int j = 0; j < IPT; ++j)
         if (i0 + j < NP && (key[j] & decided) == prefix) cand[atomicAdd(&s_ncand, 1)] = key[j];
       __syncthreads();
-      const int c = s_cand;
       if (tid < c) {
         const uint32_t mine = cand[tid];
         int gt = 0, ge = 0;
@@ -140,32 +197,24 @@ __device__ __forceinline__ void topk_block(const float* __restrict__ sc, int NP,
     }
   }
   // prefix = key of the k-th largest score; `remaining` of the pages equal to it are
-  // taken, lowest page index first.
-  int eq = 0;
-#pragma unroll
-  for (int j = 0; j < IPT; ++j) eq += (i0 + j < NP) && key[j] == prefix;
-  int tot;
-  const int eq_before = block_exscan(eq, waves, &tot);
-  int sel = 0;
-  uint32_t take = 0;  // bit j: page i0 + j is selected
-  {
-    int e = eq_before;
-#pragma unroll
-    for (int j = 0; j < IPT; ++j) {
-      if (i0 + j < NP) {
-        bool t = key[j] > prefix;
-        if (key[j] == prefix) t = e++ < remaining;
-        if (t) {
-          take |= 1u << j;
-          ++sel;
-        }
-      }
-    }
-  }
-  int pos = block_exscan(sel, waves, &tot);
+  // taken, lowest page index first.  One scan carries both counts of a thread: pages above
+  // the key in the low half, pages equal to it in the high half.
+  uint32_t both = 0;
 #pragma unroll
   for (int j = 0; j < IPT; ++j)
-    if (((take >> j) & 1u) && pos < k) emit(pos++, i0 + j);
+    if (i0 + j < NP) both += (key[j] > prefix ? 1u : 0u) + (key[j] == prefix ? 0x10000u : 0u);
+  uint32_t tot;
+  const uint32_t before = block_exscan_once<NW>(both, waves[flip], &tot);
+  int e = (int)(before >> 16);                           // equal pages in front of this thread
+  int pos = (int)(before & 0xffffu) + min(e, remaining);  // selected pages in front of it
+#pragma unroll
+  for (int j = 0; j < IPT; ++j) {
+    if (i0 + j < NP) {
+      bool t = key[j] > prefix;
+      if (key[j] == prefix) t = e++ < remaining;
+      if (t && pos < k) emit(pos++, i0 + j);
+    }
+  }
 }
 
 }  // namespace stc
