@@ -21,7 +21,7 @@ HIPCC_FLAGS = [
 # matrix-core results are consumed by vector instructions right away, so keep them in
 # ordinary vector registers (no copies out of the accumulation registers)
 _VGPR_MFMA = ["-mllvm", "-amdgpu-mfma-vgpr-form"]
-FILE_FLAGS = {"score.hip": _VGPR_MFMA, "attention.hip": _VGPR_MFMA}
+FILE_FLAGS = {"score.hip": _VGPR_MFMA, "attention.hip": _VGPR_MFMA, "router.hip": _VGPR_MFMA}
 
 
 def _hipcc():

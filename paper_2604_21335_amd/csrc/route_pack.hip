@@ -62,14 +62,25 @@ __global__ __launch_bounds__(kChunk) void route_mask_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// Global token-group budget (Sec. 3.4; App. B.1: M = N*K of the N x S pairs): one
-// 1024-thread workgroup per stream finds the key of the M-th largest logit by a radix
-// select over the stream's N*G logits (12 + 10 + 10 bits; the wide first digit spreads
-// logits that share sign and exponent over many bins), then walks the tokens in order and
-// keeps every pair above that key plus the first `remaining` pairs equal to it.
+// Global token-group budget (Sec. 3.4; App. B.1: M = N*K of the N x S pairs): the key of the
+// M-th largest of a stream's N*G logits by a radix select (12 + 10 + 10 bits; the wide first
+// digit spreads logits that share sign and exponent over many bins), then every pair above
+// that key is kept plus the first `remaining` pairs equal to it in (token, group) order.
+// Every pass over the logits is spread over the whole chip: many workgroups per stream build
+// the digit histogram (shared memory first, then one atomic per non-empty bin), one workgroup
+// per stream picks the digit.  Per-stream state lives in the workspace.
 // ---------------------------------------------------------------------------
 constexpr int kGlobalThreads = 1024;
 constexpr int kGlobalBins = 4096;
+constexpr int kHistThreads = 256;
+constexpr int kHistSlice = 16384;  // logits per histogram workgroup
+
+struct GlobalState {
+  uint32_t prefix;     // key bits fixed so far
+  uint32_t decided;    // mask of those bits
+  uint32_t remaining;  // rank of the wanted key among the keys that share the prefix
+  uint32_t pad;
+};
 
 // Order-preserving key of a finite float with -0 and +0 mapped to one key.
 __device__ __forceinline__ uint32_t logit_key(float f) {
@@ -99,83 +110,156 @@ __device__ __forceinline__ uint32_t block_exscan_1024(uint32_t v, uint32_t* lds1
   return base + inc - v;
 }
 
-__global__ __launch_bounds__(kGlobalThreads) void route_global_kernel(
-    const float* __restrict__ logits, uint16_t* __restrict__ mask, int N, int G,
-    uint32_t budget, int Ncap) {
-  __shared__ uint32_t hist[kGlobalBins];
+__device__ __forceinline__ int global_shift(int pass) { return pass == 0 ? 20 : (pass == 1 ? 10 : 0); }
+__device__ __forceinline__ uint32_t global_bins(int pass) { return pass == 0 ? 4096u : 1024u; }
+
+// Start of a selection: empty histograms, nothing decided, rank = budget.
+__global__ __launch_bounds__(256) void global_init_kernel(uint32_t* __restrict__ hist,
+                                                          GlobalState* __restrict__ state,
+                                                          int streams, uint32_t budget) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < streams * kGlobalBins) hist[i] = 0u;
+  if (i < streams) state[i] = GlobalState{0u, 0u, budget, 0u};
+}
+
+// Histogram of digit `pass` over the keys that share the stream's prefix; workgroup
+// blockIdx.x covers logits [blockIdx.x * slice, +slice) of stream blockIdx.y.
+__global__ __launch_bounds__(kHistThreads) void global_hist_kernel(
+    const float* __restrict__ logits, uint32_t* __restrict__ hist,
+    const GlobalState* __restrict__ state, uint32_t n, uint32_t slice, int pass) {
+  __shared__ uint32_t lh[kGlobalBins];
+  const int stream = blockIdx.y;
+  const int tid = threadIdx.x;
+  const int shift = global_shift(pass);
+  const uint32_t bins = global_bins(pass);
+  const uint32_t prefix = state[stream].prefix, decided = state[stream].decided;
+  for (uint32_t i = tid; i < bins; i += kHistThreads) lh[i] = 0u;
+  __syncthreads();
+  const float* a = logits + (size_t)stream * n;
+  const uint32_t lo = blockIdx.x * slice, hi = n - lo < slice ? n : lo + slice;
+  auto count = [&](float f) {
+    const uint32_t key = logit_key(f);
+    if ((key & decided) == prefix) atomicAdd(&lh[(key >> shift) & (bins - 1)], 1u);
+  };
+  if ((n & 3u) == 0) {  // every stream and slice starts on a 16-byte boundary
+    for (uint32_t i = lo + 4 * tid; i < hi; i += 4 * kHistThreads) {
+      const float4 v = *(const float4*)(a + i);
+      count(v.x), count(v.y), count(v.z), count(v.w);
+    }
+  } else {
+    for (uint32_t i = lo + tid; i < hi; i += kHistThreads) count(a[i]);
+  }
+  __syncthreads();
+  uint32_t* gh = hist + (size_t)stream * kGlobalBins;
+  for (uint32_t i = tid; i < bins; i += kHistThreads) {
+    const uint32_t c = lh[i];
+    if (c) atomicAdd(&gh[i], c);
+  }
+}
+
+// The digit that holds the wanted key: block scan over the stream's histogram in descending
+// digit order.  Leaves the histogram empty for the next pass.
+__global__ __launch_bounds__(kGlobalThreads) void global_pick_kernel(
+    uint32_t* __restrict__ hist, GlobalState* __restrict__ state, int pass) {
   __shared__ uint32_t waves[kGlobalThreads / 64];
-  __shared__ uint32_t s_prefix, s_remaining;
   const int stream = blockIdx.x;
   const int tid = threadIdx.x;
+  const int shift = global_shift(pass);
+  const uint32_t bins = global_bins(pass);
+  uint32_t* gh = hist + (size_t)stream * kGlobalBins;
+  const GlobalState st = state[stream];
+  // thread t owns the 4 adjacent digits 4095-4t .. 4092-4t (descending order)
+  uint32_t c[4], own = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t d = kGlobalBins - 1 - (4 * tid + j);
+    c[j] = d < bins ? gh[d] : 0u;
+    if (d < bins) gh[d] = 0u;
+    own += c[j];
+  }
+  uint32_t tot;
+  uint32_t above = block_exscan_1024(own, waves, &tot);  // pairs with a larger digit
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (above < st.remaining && st.remaining <= above + c[j]) {
+      GlobalState nx;
+      nx.prefix = st.prefix | ((uint32_t)(kGlobalBins - 1 - (4 * tid + j)) << shift);
+      nx.decided = st.decided | ((bins - 1) << shift);
+      nx.remaining = st.remaining - above;
+      nx.pad = 0u;
+      state[stream] = nx;
+    }
+    above += c[j];
+  }
+}
+
+// Pairs equal to the stream's key per chunk of 256 tokens (the chunks of the mask kernel).
+__global__ __launch_bounds__(kChunk) void global_eq_kernel(const float* __restrict__ logits,
+                                                           const GlobalState* __restrict__ state,
+                                                           uint32_t* __restrict__ chunk_eq, int N,
+                                                           int G, int nchunks) {
+  __shared__ int red[4];
+  const int stream = blockIdx.y;
+  const uint32_t key = state[stream].prefix;
   const uint32_t n = (uint32_t)N * (uint32_t)G;
   const float* a = logits + (size_t)stream * n;
-  uint16_t* mk = mask + (size_t)stream * Ncap;
+  const uint32_t lo = (uint32_t)blockIdx.x * kChunk * G;
+  const uint32_t hi = n - lo < (uint32_t)kChunk * G ? n : lo + (uint32_t)kChunk * G;
+  int eq = 0;
+  for (uint32_t i = lo + threadIdx.x; i < hi; i += kChunk) eq += logit_key(a[i]) == key;
+  const int tot = block_sum_256(eq, red);
+  if (threadIdx.x == 0) chunk_eq[(size_t)stream * nchunks + blockIdx.x] = (uint32_t)tot;
+}
 
-  uint32_t prefix = 0, decided = 0, remaining = budget;
-  if (budget > 0) {
-    // digits from the top: bits 31..20, 19..10, 9..0
-    for (int pass = 0; pass < 3; ++pass) {
-      const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
-      const uint32_t bins = pass == 0 ? 4096u : 1024u;
-      for (uint32_t i = tid; i < kGlobalBins; i += kGlobalThreads) hist[i] = 0;
-      __syncthreads();
-      for (uint32_t i = tid; i < n; i += kGlobalThreads) {
-        const uint32_t key = logit_key(a[i]);
-        if ((key & decided) == prefix) atomicAdd(&hist[(key >> shift) & (bins - 1)], 1u);
-      }
-      __syncthreads();
-      // thread t owns the 4 adjacent digits 4095-4t .. 4092-4t (descending order)
-      uint32_t c[4], own = 0;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const uint32_t d = kGlobalBins - 1 - (4 * tid + j);
-        c[j] = d < bins ? hist[d] : 0u;
-        own += c[j];
-      }
-      uint32_t tot;
-      uint32_t above = block_exscan_1024(own, waves, &tot);  // pairs with a larger digit
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if (above < remaining && remaining <= above + c[j]) {
-          s_prefix = prefix | ((uint32_t)(kGlobalBins - 1 - (4 * tid + j)) << shift);
-          s_remaining = remaining - above;
-        }
-        above += c[j];
-      }
-      __syncthreads();
-      prefix = s_prefix;
-      remaining = s_remaining;
-      decided |= (bins - 1) << shift;
-      __syncthreads();
-    }
-  }
-  // prefix = key of the budget-th largest logit; `remaining` of the pairs equal to it are
-  // kept, lowest (token, group) first.  budget == 0 keeps nothing.
-  uint32_t carry = 0;  // pairs equal to the key in earlier tiles
-  for (int t0 = 0; t0 < N; t0 += kGlobalThreads) {
-    const int t = t0 + tid;
-    uint32_t key[16];
-    uint32_t eq = 0;
-#pragma unroll
-    for (int g = 0; g < 16; ++g) {
-      key[g] = (g < G && t < N) ? logit_key(a[(size_t)t * G + g]) : 0u;
-      eq += (g < G && t < N && budget > 0) && key[g] == prefix;
-    }
-    uint32_t tot;
-    uint32_t e = carry + block_exscan_1024(eq, waves, &tot);
-    uint32_t m = 0;
-    if (budget > 0) {
-#pragma unroll
-      for (int g = 0; g < 16; ++g) {
-        if (g < G && t < N) {
-          if (key[g] > prefix) m |= 1u << g;
-          else if (key[g] == prefix && e++ < remaining) m |= 1u << g;
-        }
-      }
-    }
-    if (t < N) mk[t] = (uint16_t)m;
+// Exclusive scan of a stream's per-chunk counts, in place.
+__global__ __launch_bounds__(256) void global_eq_scan_kernel(uint32_t* chunk_eq, int nchunks) {
+  __shared__ int red[4];
+  uint32_t* cs = chunk_eq + (size_t)blockIdx.x * nchunks;
+  int carry = 0;
+  for (int base = 0; base < nchunks; base += 256) {
+    const int i = base + threadIdx.x;
+    const int v = i < nchunks ? (int)cs[i] : 0;
+    int tot;
+    const int ex = block_exscan_256(v, red, &tot);
+    if (i < nchunks) cs[i] = (uint32_t)(carry + ex);
     carry += tot;
   }
+}
+
+// Masks of a chunk of 256 tokens from the stream's key: pairs above it, and the first
+// `remaining` pairs equal to it in (token, group) order.  Also the chunk's number of kept
+// groups, as route_mask_kernel writes it.  budget == 0 keeps nothing.
+__global__ __launch_bounds__(kChunk) void global_mask_kernel(
+    const float* __restrict__ logits, const GlobalState* __restrict__ state,
+    const uint32_t* __restrict__ chunk_eq, uint16_t* __restrict__ mask,
+    uint32_t* __restrict__ chunk_sum, int N, int G, int nchunks, int Ncap, uint32_t budget) {
+  __shared__ int red[4];
+  const int stream = blockIdx.y;
+  const int t = blockIdx.x * kChunk + threadIdx.x;
+  const uint32_t prefix = state[stream].prefix, remaining = state[stream].remaining;
+  const float* a = logits + ((size_t)stream * N + min(t, N - 1)) * G;
+  uint32_t key[16];
+  int eq = 0;
+#pragma unroll
+  for (int g = 0; g < 16; ++g) {
+    key[g] = (g < G && t < N) ? logit_key(a[g]) : 0u;
+    eq += (g < G && t < N && budget > 0) && key[g] == prefix;
+  }
+  uint32_t e = (budget > 0 ? chunk_eq[(size_t)stream * nchunks + blockIdx.x] : 0u) +
+               (uint32_t)block_exscan_256(eq, red, nullptr);
+  uint32_t m = 0;
+  if (budget > 0) {
+#pragma unroll
+    for (int g = 0; g < 16; ++g) {
+      if (g < G && t < N) {
+        if (key[g] > prefix) m |= 1u << g;
+        else if (key[g] == prefix && e++ < remaining) m |= 1u << g;
+      }
+    }
+  }
+  if (t < N) mask[(size_t)stream * Ncap + t] = (uint16_t)m;
+  const int tot = block_sum_256(__popc(m), red);
+  if (threadIdx.x == 0) chunk_sum[(size_t)stream * nchunks + blockIdx.x] = (uint32_t)tot;
 }
 
 // Step 2: per stream, exclusive scan of the chunk sums (in place); writes the
@@ -262,10 +346,30 @@ __global__ __launch_bounds__(256) void compact_kernel(const uint4* __restrict__ 
   dst[((size_t)stream * n_keep + i) * PPT + pc] = v;
 }
 
-size_t route_ws_bytes(const stc_shape_t& s) {
+namespace {
+
+// Workspace: kept groups per chunk, then (global budget only) equal-key counts per chunk,
+// the per-stream digit histograms and the per-stream selection state.
+struct RouteWs {
+  size_t chunk_sum, chunk_eq, hist, state, total;
+};
+
+RouteWs route_ws_layout(const stc_shape_t& s) {
+  const size_t streams = (size_t)s.B * s.Hkv;
   const size_t nchunks = (s.N + kChunk - 1) / kChunk;
-  return (size_t)s.B * s.Hkv * nchunks * sizeof(uint32_t);
+  auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  RouteWs w;
+  w.chunk_sum = 0;
+  w.chunk_eq = up(streams * nchunks * sizeof(uint32_t));
+  w.hist = w.chunk_eq + up(streams * nchunks * sizeof(uint32_t));
+  w.state = w.hist + up(streams * kGlobalBins * sizeof(uint32_t));
+  w.total = w.state + up(streams * sizeof(GlobalState));
+  return w;
 }
+
+}  // namespace
+
+size_t route_ws_bytes(const stc_shape_t& s) { return route_ws_layout(s).total; }
 
 int launch_route_pack(const stc_shape_t& s, int mode, const void* V, const float* logits,
                       const uint8_t* kcount, int fixed_k, const uint16_t* mask_in, uint16_t* mask,
@@ -274,20 +378,33 @@ int launch_route_pack(const stc_shape_t& s, int mode, const void* V, const float
   const int streams = s.B * s.Hkv;
   const int nchunks = (s.N + kChunk - 1) / kChunk;
   const int Ncap = token_cap(s);  // stride of mask and tok_off; V, logits, kcount are dense
-  int mask_in_stride = s.N;
-  uint32_t* chunk = (uint32_t*)ws;
+  const RouteWs lay = route_ws_layout(s);
+  uint32_t* chunk = (uint32_t*)((char*)ws + lay.chunk_sum);
   dim3 grid(nchunks, streams);
   if (mode == STC_ROUTE_GLOBAL) {
-    // the mask of the whole stream first, then the common path with that mask as given
-    route_global_kernel<<<streams, kGlobalThreads, 0, st>>>(
-        logits, mask, s.N, s.G, (uint32_t)((long long)s.N * fixed_k), Ncap);
-    if (hipGetLastError() != hipSuccess) return -1;
-    mode = STC_ROUTE_MASK;
-    mask_in = mask;
-    mask_in_stride = Ncap;
+    uint32_t* chunk_eq = (uint32_t*)((char*)ws + lay.chunk_eq);
+    uint32_t* hist = (uint32_t*)((char*)ws + lay.hist);
+    GlobalState* state = (GlobalState*)((char*)ws + lay.state);
+    const uint32_t budget = (uint32_t)((long long)s.N * fixed_k);
+    const uint32_t n = (uint32_t)s.N * (uint32_t)s.G;
+    global_init_kernel<<<(streams * kGlobalBins + 255) / 256, 256, 0, st>>>(hist, state, streams,
+                                                                            budget);
+    if (budget > 0) {
+      dim3 hgrid((unsigned)(((unsigned long long)n + kHistSlice - 1) / kHistSlice), streams);
+      for (int pass = 0; pass < 3; ++pass) {
+        global_hist_kernel<<<hgrid, kHistThreads, 0, st>>>(logits, hist, state, n, kHistSlice,
+                                                           pass);
+        global_pick_kernel<<<streams, kGlobalThreads, 0, st>>>(hist, state, pass);
+      }
+      global_eq_kernel<<<grid, kChunk, 0, st>>>(logits, state, chunk_eq, s.N, s.G, nchunks);
+      global_eq_scan_kernel<<<streams, 256, 0, st>>>(chunk_eq, nchunks);
+    }
+    global_mask_kernel<<<grid, kChunk, 0, st>>>(logits, state, chunk_eq, mask, chunk, s.N, s.G,
+                                                nchunks, Ncap, budget);
+  } else {
+    route_mask_kernel<<<grid, kChunk, 0, st>>>(mode, logits, kcount, fixed_k, mask_in, mask, chunk,
+                                               s.N, s.G, nchunks, Ncap, s.N);
   }
-  route_mask_kernel<<<grid, kChunk, 0, st>>>(mode, logits, kcount, fixed_k, mask_in, mask, chunk,
-                                             s.N, s.G, nchunks, Ncap, mask_in_stride);
   if (hipGetLastError() != hipSuccess) return -1;
   scan_chunks_kernel<<<streams, 256, 0, st>>>(chunk, tok_off, dev_status, s.N, nchunks,
                                               (long long)s.v_cap_groups, Ncap);

@@ -78,6 +78,25 @@ __device__ __forceinline__ float row_max(float x) {
   return x;
 }
 
+// Rows 0,1 and rows 2,3 (of 16 lanes) exchange values: every lane gets the sum of its own
+// and the partner row's value.
+__device__ __forceinline__ float row_pair_sum(float u) {
+  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(u), __float_as_uint(u), false,
+                                                  false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Sum over the 8 chunk lanes of a page (lane bits 2, 3, 4), continuing the balanced tree:
+// chunks (0,1)(2,3).. first.  row_ror:n makes lane i read lane i-n of its row, so after the
+// two rotations the lanes with bit 2 set hold ((c0+c1)+(c2+c3)) of their row; the row
+// exchange adds chunks 4..7.  Valid in lanes with (lane & 0x1c) == 4.
+__device__ __forceinline__ float chunk_tree_sum(float u) {
+  u += dpp_f32<0x124>(u);  // row_ror:4
+  u += dpp_f32<0x128>(u);  // row_ror:8
+  return row_pair_sum(u);
+}
+constexpr int kChunkSumLanes = 4;  // (lane & 0x1c) of the lanes that hold the page's sum
+
 // Value of lane `src_lane` (wave-uniform index) as a scalar.
 __device__ __forceinline__ float readlane_f32(float x, int src_lane) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), src_lane));

@@ -182,7 +182,9 @@ def test_null_alignment_and_workspace_errors():
 
 def test_workspace_sizes():
     s = _shape(N=4096, v_cap_groups=4096 * 8)
-    assert stc.stc_workspace_bytes(s, stc.STC_WS_ROUTE) == 2 * 2 * 16 * 4
+    # kept groups and equal keys per chunk of 256 tokens, a 4096-bin histogram and 16 bytes of
+    # selection state per stream, each region rounded up to 256 bytes
+    assert stc.stc_workspace_bytes(s, stc.STC_WS_ROUTE) == 256 + 256 + 4 * 4096 * 4 + 256
     assert stc.stc_workspace_bytes(s, stc.STC_WS_SELECT, 64) == 2 * 2 * 256 * 4
     assert stc.stc_workspace_bytes(s, stc.STC_WS_SELECT, 256) == 0       # all pages: no scores
     assert stc.stc_workspace_bytes(s, stc.STC_WS_ATTENTION, 300) == 0    # k beyond NP
