@@ -7,10 +7,26 @@ namespace stc {
 
 // Routing mask of one token: bit g set iff group g is among the c largest of its G logits
 // (equal logits: the lower group first).
+// The G logits of one token (16-byte loads when G is a multiple of 4: the row is then
+// 16-byte aligned); entries at and beyond G are 0.
+__device__ __forceinline__ void load_token_logits(const float* __restrict__ lp, int G,
+                                                  float (&a)[16]) {
+  if ((G & 3) == 0) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (4 * q < G) v = *(const float4*)(lp + 4 * q);
+      a[4 * q] = v.x, a[4 * q + 1] = v.y, a[4 * q + 2] = v.z, a[4 * q + 3] = v.w;
+    }
+  } else {
+#pragma unroll
+    for (int g = 0; g < 16; ++g) a[g] = g < G ? lp[g] : 0.f;
+  }
+}
+
 __device__ __forceinline__ uint32_t rank_mask(const float* __restrict__ lp, int c, int G) {
   float a[16];
-#pragma unroll
-  for (int g = 0; g < 16; ++g) a[g] = g < G ? lp[g] : 0.f;
+  load_token_logits(lp, G, a);
   uint32_t m = 0;
 #pragma unroll
   for (int g = 0; g < 16; ++g) {

@@ -79,7 +79,7 @@ struct GlobalState {
   uint32_t prefix;     // key bits fixed so far
   uint32_t decided;    // mask of those bits
   uint32_t remaining;  // rank of the wanted key among the keys that share the prefix
-  uint32_t pad;
+  uint32_t take_all;   // after the last pass: every pair equal to the key is kept
 };
 
 // Order-preserving key of a finite float with -0 and +0 mapped to one key.
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(kGlobalThreads) void global_pick_kernel(
       nx.prefix = st.prefix | ((uint32_t)(kGlobalBins - 1 - (4 * tid + j)) << shift);
       nx.decided = st.decided | ((bins - 1) << shift);
       nx.remaining = st.remaining - above;
-      nx.pad = 0u;
+      nx.take_all = nx.remaining == c[j] ? 1u : 0u;
       state[stream] = nx;
     }
     above += c[j];
@@ -200,6 +200,7 @@ __global__ __launch_bounds__(kChunk) void global_eq_kernel(const float* __restri
                                                            int G, int nchunks) {
   __shared__ int red[4];
   const int stream = blockIdx.y;
+  if (state[stream].take_all) return;  // no ranks among equal pairs needed
   const uint32_t key = state[stream].prefix;
   const uint32_t n = (uint32_t)N * (uint32_t)G;
   const float* a = logits + (size_t)stream * n;
@@ -212,8 +213,11 @@ __global__ __launch_bounds__(kChunk) void global_eq_kernel(const float* __restri
 }
 
 // Exclusive scan of a stream's per-chunk counts, in place.
-__global__ __launch_bounds__(256) void global_eq_scan_kernel(uint32_t* chunk_eq, int nchunks) {
+__global__ __launch_bounds__(256) void global_eq_scan_kernel(uint32_t* chunk_eq,
+                                                             const GlobalState* __restrict__ state,
+                                                             int nchunks) {
   __shared__ int red[4];
+  if (state[blockIdx.x].take_all) return;
   uint32_t* cs = chunk_eq + (size_t)blockIdx.x * nchunks;
   int carry = 0;
   for (int base = 0; base < nchunks; base += 256) {
@@ -236,16 +240,19 @@ __global__ __launch_bounds__(kChunk) void global_mask_kernel(
   __shared__ int red[4];
   const int stream = blockIdx.y;
   const int t = blockIdx.x * kChunk + threadIdx.x;
-  const uint32_t prefix = state[stream].prefix, remaining = state[stream].remaining;
-  const float* a = logits + ((size_t)stream * N + min(t, N - 1)) * G;
+  const GlobalState gs = state[stream];
+  const uint32_t prefix = gs.prefix, remaining = gs.remaining;
+  const bool ranked = budget > 0 && !gs.take_all;  // equal pairs are taken in order
+  float lg[16];
+  load_token_logits(logits + ((size_t)stream * N + min(t, N - 1)) * G, G, lg);
   uint32_t key[16];
   int eq = 0;
 #pragma unroll
   for (int g = 0; g < 16; ++g) {
-    key[g] = (g < G && t < N) ? logit_key(a[g]) : 0u;
-    eq += (g < G && t < N && budget > 0) && key[g] == prefix;
+    key[g] = (g < G && t < N) ? logit_key(lg[g]) : 0u;
+    eq += (g < G && t < N && ranked) && key[g] == prefix;
   }
-  uint32_t e = (budget > 0 ? chunk_eq[(size_t)stream * nchunks + blockIdx.x] : 0u) +
+  uint32_t e = (ranked ? chunk_eq[(size_t)stream * nchunks + blockIdx.x] : 0u) +
                (uint32_t)block_exscan_256(eq, red, nullptr);
   uint32_t m = 0;
   if (budget > 0) {
@@ -253,7 +260,7 @@ __global__ __launch_bounds__(kChunk) void global_mask_kernel(
     for (int g = 0; g < 16; ++g) {
       if (g < G && t < N) {
         if (key[g] > prefix) m |= 1u << g;
-        else if (key[g] == prefix && e++ < remaining) m |= 1u << g;
+        else if (key[g] == prefix && (!ranked || e++ < remaining)) m |= 1u << g;
       }
     }
   }
@@ -397,7 +404,7 @@ int launch_route_pack(const stc_shape_t& s, int mode, const void* V, const float
         global_pick_kernel<<<streams, kGlobalThreads, 0, st>>>(hist, state, pass);
       }
       global_eq_kernel<<<grid, kChunk, 0, st>>>(logits, state, chunk_eq, s.N, s.G, nchunks);
-      global_eq_scan_kernel<<<streams, 256, 0, st>>>(chunk_eq, nchunks);
+      global_eq_scan_kernel<<<streams, 256, 0, st>>>(chunk_eq, state, nchunks);
     }
     global_mask_kernel<<<grid, kChunk, 0, st>>>(logits, state, chunk_eq, mask, chunk, s.N, s.G,
                                                 nchunks, Ncap, budget);
