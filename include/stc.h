@@ -331,6 +331,8 @@ int stc_decode_attention_union(const stc_shape_t *shape, const void *q, const vo
  *   W      [G, d_model] bf16, in; G in {1, 2, 4, 8, 16}
  *   bias   [G] float, in, may be NULL
  *   logits [B, Hkv, N, G] float, out
+ * h and W hold zeros or normal bf16 numbers (a subnormal bf16 input counts as zero), and their
+ * products stay in the normal float range.
  */
 int stc_router_logits(int32_t B, int32_t Hkv, int32_t N, int32_t d_model, int32_t G,
                       const void *h, const void *W, const float *bias, float *logits,

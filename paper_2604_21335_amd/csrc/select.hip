@@ -116,44 +116,52 @@ int launch_select(const stc_shape_t& s, const void* q, const void* bounds, int k
 }
 
 // Union of the R page lists of a KV head's query heads, one workgroup per KV head.  The lists
-// (R*k entries, each ascending) sit in LDS; thread t takes pages t, t + 256, ..., looks its page
-// up in every list by binary search to get the set of heads that selected it, and a block scan
-// compacts the selected pages in page order.  Unused output slots get page -1.
+// (R*k entries) sit in LDS.  Pages are walked in tiles of kUnionTile: every list entry that
+// falls into the tile ORs its head's bit into the tile's array of head sets, then thread t
+// takes the tile's pages 16t .. 16t+15 in order and a block scan compacts the pages with a
+// non-empty set.  Unused output slots get page -1.
+constexpr int kUnionTile = 4096;
+
 __global__ __launch_bounds__(256) void union_pages_kernel(const int32_t* __restrict__ lists,
                                                           int32_t* __restrict__ union_idx,
                                                           uint16_t* __restrict__ union_heads,
                                                           int NP, int R, int k, int U) {
   extern __shared__ int32_t s_list[];  // [R * k]
+  __shared__ uint32_t s_set[kUnionTile];
   __shared__ int waves[4];
+  constexpr int PPT = kUnionTile / 256;  // pages per thread and tile
   const int stream = blockIdx.x;
   const int tid = threadIdx.x;
   const int n = R * k;
   for (int i = tid; i < n; i += 256) s_list[i] = lists[(size_t)stream * n + i];
-  __syncthreads();
   int32_t* out_idx = union_idx + (size_t)stream * U;
   uint16_t* out_heads = union_heads + (size_t)stream * U;
   int base = 0;  // union entries written so far (pages below the current tile)
-  for (int p0 = 0; p0 < NP; p0 += 256) {
-    const int p = p0 + tid;
-    uint32_t m = 0;
-    if (p < NP) {
-      for (int r = 0; r < R; ++r) {
-        // the list of head r is ascending: binary search
-        const int32_t* row = s_list + r * k;
-        int lo = 0, hi = k;
-        while (lo < hi) {
-          const int mid = (lo + hi) >> 1;
-          if (row[mid] < p) lo = mid + 1;
-          else hi = mid;
-        }
-        if (lo < k && row[lo] == p) m |= 1u << r;
-      }
+  for (int p0 = 0; p0 < NP; p0 += kUnionTile) {
+    for (int i = tid; i < kUnionTile; i += 256) s_set[i] = 0u;
+    __syncthreads();  // also: the lists are in LDS
+    const int p1 = min(p0 + kUnionTile, NP);
+    for (int i = tid; i < n; i += 256) {
+      const int p = s_list[i];
+      if (p >= p0 && p < p1) atomicOr(&s_set[p - p0], 1u << (i / k));
+    }
+    __syncthreads();
+    uint32_t m[PPT];
+    int cnt = 0;
+#pragma unroll
+    for (int j = 0; j < PPT; ++j) {
+      m[j] = s_set[tid * PPT + j];
+      cnt += m[j] != 0;
     }
     int tot;
-    const int pos = base + block_exscan(m != 0, waves, &tot);
-    if (m != 0 && pos < U) {
-      out_idx[pos] = p;
-      out_heads[pos] = (uint16_t)m;
+    int pos = base + block_exscan(cnt, waves, &tot);  // ends with a barrier: s_set may be reused
+#pragma unroll
+    for (int j = 0; j < PPT; ++j) {
+      if (m[j] != 0 && pos < U) {
+        out_idx[pos] = p0 + tid * PPT + j;
+        out_heads[pos] = (uint16_t)m[j];
+      }
+      pos += m[j] != 0;
     }
     base += tot;
   }
@@ -168,6 +176,10 @@ int launch_union_pages(const stc_shape_t& s, const int32_t* page_idx_per_head, i
   const int NP = (s.N + kPage - 1) / kPage;
   const int R = s.Hq / s.Hkv;
   const size_t lds = (size_t)R * k_pages * sizeof(int32_t);
+  // up to 64 KiB of lists next to the 16 KiB of head sets: beyond the default LDS limit
+  static const hipError_t attr = hipFuncSetAttribute(
+      (const void*)union_pages_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
+  if (attr != hipSuccess) return -1;
   union_pages_kernel<<<s.B * s.Hkv, 256, lds, st>>>(page_idx_per_head, union_idx, union_heads, NP,
                                                     R, k_pages, U);
   return hipGetLastError() == hipSuccess ? 0 : -1;

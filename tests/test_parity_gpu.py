@@ -416,6 +416,31 @@ def test_per_head_selection_and_attention(B, Hq, Hkv, D, N, G, k):
     assert np.abs(out_u.cpu().numpy() - want).max() < PT.TIGHT
 
 
+@pytest.mark.parametrize("B,Hkv,R,NP,k", [(2, 1, 7, 9003, 300),      # three tiles of head sets
+                                          (1, 2, 16, 5000, 1000),    # 62.5 KiB of lists in LDS
+                                          (1, 1, 3, 4096, 4096)])    # every page, one full tile
+def test_union_pages_long_streams_and_long_lists(B, Hkv, R, NP, k):
+    """stc_union_pages on given lists (ascending, distinct per head): several tiles of pages,
+    lists near the size limit, and an output that is the whole range of pages."""
+    rng = np.random.default_rng(NP + k)
+    lists = np.stack([np.sort(rng.choice(NP, size=k, replace=False)) for _ in range(B * Hkv * R)])
+    lists = lists.reshape(B, Hkv * R, k).astype(np.int32)
+    shape = stc.make_shape(B, Hkv * R, Hkv, 128, NP * 16, 8, NP * 16 * 8)
+    U = min(NP, R * k)
+    dev = "cuda:0"
+    uidx = torch.full((B, Hkv, U), -5, dtype=torch.int32, device=dev)
+    uheads = torch.full((B, Hkv, U), -1, dtype=torch.int16, device=dev)
+    stc.stc_union_pages(shape, torch.from_numpy(lists).to(dev), k, uidx, uheads)
+    torch.cuda.synchronize()
+    gi, gh = uidx.cpu().numpy(), PT.host_u16(uheads)
+    for b in range(B):
+        for h in range(Hkv):
+            pages, heads = O.union_pages(lists[b, h * R:(h + 1) * R], NP)
+            n = len(pages)
+            assert np.array_equal(gi[b, h, :n], pages) and np.array_equal(gh[b, h, :n], heads)
+            assert (gi[b, h, n:] == -1).all() and (gh[b, h, n:] == 0).all()
+
+
 @pytest.mark.parametrize("B,Hkv,N,dm,G,with_bias", [(2, 2, 301, 512, 8, True), (1, 3, 64, 128, 4, False),
                                                      (1, 1, 1000, 3584, 8, True),
                                                      (2, 1, 77, 256, 16, False), (1, 2, 50, 384, 1, True)])
