@@ -62,7 +62,11 @@ struct AttnCfg {
   static constexpr int META = 2 * TILE;     // per pair: 2 x 16 words (mask | relative offset << 16)
   static constexpr int ZERO = META + 128;   // 16 zero bytes: what dropped units read
   static constexpr int WAVE_LDS = ZERO + 16;
-  static_assert(16 * D * 4 + 16 * 2 * 4 <= 2 * TILE, "merge buffer fits the tiles");
+  // merge buffer of a wavefront: 16 head rows of D floats, each row padded by 4 floats so that
+  // the 16 heads' 16-byte writes of one channel group fall into different banks
+  static constexpr int MROW = D + 4;
+  static constexpr int MML = 16 * MROW * 4;  // byte offset of the 16 (m, l) pairs behind it
+  static_assert(MML + 16 * 2 * 4 <= 2 * TILE, "merge buffer fits the tiles");
 };
 
 // 16 zero bytes in device memory: where lanes beyond the end of a packed run read
@@ -465,11 +469,11 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
 
   // ---- merge the workgroup's wavefronts: each leaves (m, l, acc[16][D]) in its own LDS region.
   // acc[cb][i] of lane (head r16, kg) is channel (4*kg + i)*CB + cb.
-  float* macc = (float*)wl;                // [16][D]
-  float* mml = (float*)(wl + 16 * D * 4);  // [16][2]
+  float* macc = (float*)wl;             // [16][MROW]
+  float* mml = (float*)(wl + C::MML);    // [16][2]
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    float* dst = macc + r16 * D + (4 * kg + i) * C::CB;
+    float* dst = macc + r16 * C::MROW + (4 * kg + i) * C::CB;
 #pragma unroll
     for (int c4 = 0; c4 < C::CB / 4; ++c4)
       *(f32x4*)(dst + 4 * c4) = f32x4{acc[4 * c4][i], acc[4 * c4 + 1][i], acc[4 * c4 + 2][i],
@@ -486,15 +490,15 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
     float mw[WAVES], m = kNegBig;
 #pragma unroll
     for (int w = 0; w < WAVES; ++w) {
-      mw[w] = ((const float*)(lds + w * C::WAVE_LDS + 16 * D * 4))[head * 2];
+      mw[w] = ((const float*)(lds + w * C::WAVE_LDS + C::MML))[head * 2];
       m = fmaxf(m, mw[w]);
     }
     float lsum = 0.f, a = 0.f;
 #pragma unroll
     for (int w = 0; w < WAVES; ++w) {
       const float wgt = __builtin_amdgcn_exp2f(mw[w] - m);
-      lsum = fmaf(wgt, ((const float*)(lds + w * C::WAVE_LDS + 16 * D * 4))[head * 2 + 1], lsum);
-      a = fmaf(wgt, ((const float*)(lds + w * C::WAVE_LDS))[head * D + c], a);
+      lsum = fmaf(wgt, ((const float*)(lds + w * C::WAVE_LDS + C::MML))[head * 2 + 1], lsum);
+      a = fmaf(wgt, ((const float*)(lds + w * C::WAVE_LDS))[head * C::MROW + c], a);
     }
     const size_t hf = (size_t)b * Hq + kvh * R + head;
     if (splits == 1) {
