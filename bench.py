@@ -2,8 +2,9 @@
 """Decode-step benchmark of libstc on one MI355X.
 
 A step is one pass of the whole hot path over one layer's cache: Quest page
-selection (stc_select_pages) followed by routed attention over the selected
-pages (stc_decode_attention), for every stream of the batch.  Inputs are
+selection followed by routed attention over the selected pages, for every
+stream of the batch, through stc_decode_step (the same results bit for bit as
+stc_select_pages followed by stc_decode_attention; that form is timed too).  Inputs are
 synthetic, resident in HBM before the timed region; the step rotates over
 several independent cache replicas and uses a fresh query every step so that
 no step is served from the 256 MB last-level cache.
@@ -13,7 +14,9 @@ Prints ONE JSON line:
   step_us_per_step_events  median / p10 / p90 of the same steps timed one by one
   hbm_GBps / hbm_frac  algorithmic bytes of the step / step time, against 8 TB/s
   calls                the same for stc_select_pages, stc_decode_attention and stc_score_pages
-                       alone (each timed over --steps back-to-back launches)
+                       alone, and for the step as two calls (each timed over --steps
+                       back-to-back launches)
+With --rows: one JSON line of per-call figures for every other entry point instead.
   roofline             the dominant kernel (page scoring: it streams every page bound)
   cpu_baseline         the CPU oracle on a bounded sample of the same workload
 """
