@@ -364,6 +364,7 @@ class RoutedCache:
     def _alloc_step(self):
         """Workspace of stc_decode_step.  The page scores are at its front: page_score is a view
         of them, so that both forms of step() leave the scores there."""
+        self._step_cache = None
         if self.tail_cap:
             self._ws_step = self._ws(STC_WS_STEP_TAIL, self.k_eff + (self.tail_cap + 15) // 16)
         else:
@@ -387,6 +388,7 @@ class RoutedCache:
             self.K[:, :, :self.N].copy_(K)
         else:
             self.K = K
+        self._step_cache = None
         stc_build_page_bounds(self.shape, self.K, self.bounds)
         mode = STC_ROUTE_MASK if mask_in is not None else STC_ROUTE_TOPK
         if global_k is not None:
@@ -445,21 +447,38 @@ class RoutedCache:
         stc_decode_attention(self.shape, q, self.K, self.vpacked, self.mask, self.tok_off,
                              page_idx, self.k_eff, self.out, self._ws_attn)
 
+    def _step_args(self):
+        """C arguments of the one-call step for this cache's own tensors, validated once;
+        step() fills in the query, the tail length and the stream."""
+        if self._step_cache is None:
+            fixed = [ctypes.byref(self.shape), None, _ptr(self.bounds, torch.bfloat16, "bounds"),
+                     _ptr(self.K, torch.bfloat16, "K"), _ptr(self.vpacked, torch.bfloat16, "vpacked"),
+                     _ptr(self.mask, _U16, "mask"), _ptr(self.tok_off, _U32, "tok_off"),
+                     int(self.k_eff)]
+            if self.tail_cap:
+                fixed += [_ptr(self.K_tail, torch.bfloat16, "K_tail"),
+                          _ptr(self.V_tail, torch.bfloat16, "V_tail"), 0, int(self.tail_cap)]
+            fixed += [_ptr(self.page_idx, torch.int32, "page_idx"),
+                      _ptr(self.out, torch.float32, "out"), _ptr(self._ws_step, None, "ws"),
+                      _nbytes(self._ws_step), None]
+            lib = load_library()
+            self._step_cache = (lib.stc_decode_step_tail if self.tail_cap else lib.stc_decode_step,
+                                fixed)
+        return self._step_cache
+
     def step(self, q, one_call=True):
         """One decode step: page selection, then routed attention.  When every page is kept
         there is nothing to select: the attention call takes "all pages" as a missing list.
         one_call: through stc_decode_step (the page scores then stay in its workspace)
         instead of stc_select_pages + stc_decode_attention."""
         if self.k_pages < self.NP:
-            if one_call and self.tail_cap:
-                stc_decode_step_tail(self.shape, q, self.bounds, self.K, self.vpacked, self.mask,
-                                     self.tok_off, self.k_eff, self.K_tail, self.V_tail,
-                                     self.n_tail, self.tail_cap, self.page_idx, self.out,
-                                     self._ws_step)
-                return self.out
             if one_call:
-                stc_decode_step(self.shape, q, self.bounds, self.K, self.vpacked, self.mask,
-                                self.tok_off, self.k_eff, self.page_idx, self.out, self._ws_step)
+                fn, args = self._step_args()
+                args[1] = _ptr(q, torch.bfloat16, "q")
+                if self.tail_cap:
+                    args[10] = int(self.n_tail)
+                args[-1] = _stream()
+                _check(fn(*args), "stc_decode_step")
                 return self.out
             self.select(q)
         self.attend(q)
