@@ -763,6 +763,54 @@ def test_steps_are_deterministic():
     assert torch.equal(c.page_idx, first[0]) and torch.equal(c.out, first[1])
 
 
+def test_decode_steps_replayed_from_a_hip_graph():
+    """The step calls allocate nothing and clear nothing through the runtime, so a caller may
+    capture them: three caches (selection inside the attention kernel, selection as its own
+    launch, a cache with an uncompressed tail) captured into one graph, replayed four times
+    with fresh queries and eager work in between; every replay gives the eager bits."""
+    dev = "cuda:0"
+    g = torch.Generator(device=dev)
+    g.manual_seed(77)
+    specs = [(4, 14, 2, 128, 5000, 8, 40, 0), (1, 8, 8, 64, 40000, 4, 300, 0),
+             (2, 8, 2, 128, 3000, 8, 24, 40)]
+    caches, qbufs = [], []
+    for (B, Hq, Hkv, D, N, G, k, tail) in specs:
+        K = torch.randn(B, Hkv, N, D, device=dev, generator=g).bfloat16()
+        V = torch.randn(B, Hkv, N, D, device=dev, generator=g).bfloat16()
+        lg = torch.randn(B, Hkv, N, G, device=dev, generator=g)
+        c = stc.RoutedCache(B, Hq, Hkv, D, N, G, k, device=dev, tail_cap=tail)
+        c.build(K, V, logits=lg, fixed_k=G // 2)
+        if tail:
+            c.K_tail.copy_(torch.randn(c.K_tail.shape, device=dev, generator=g))
+            c.V_tail.copy_(torch.randn(c.V_tail.shape, device=dev, generator=g))
+            c.n_tail = tail - 3
+        caches.append(c)
+        qbufs.append(torch.randn(B, Hq, D, device=dev, generator=g).bfloat16())
+    for c, q in zip(caches, qbufs):            # eager first: one-time set-up of the launches
+        c.step(q)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for c, q in zip(caches, qbufs):
+                c.step(q)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        want = []
+        for c, q in zip(caches, qbufs):
+            q.copy_(torch.randn(q.shape, device=dev, generator=g))
+            c.step(q)                           # eager
+            want.append((c.page_idx.clone(), c.out.clone()))
+            c.page_idx.fill_(-1)
+            c.out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for c, (wi, wo) in zip(caches, want):
+            assert torch.equal(c.page_idx, wi) and torch.equal(c.out, wo), rep
+
+
 @pytest.mark.parametrize("N,k", [(3000, 20), (40000, 100)])
 def test_workspaces_are_reusable_without_clearing(N, k):
     """Alternating two queries on one cache: nothing a call leaves in the selection or
