@@ -98,6 +98,7 @@ __device__ __forceinline__ void topk_block(const float* __restrict__ sc, int NP,
   __shared__ uint32_t s_prefix;
   __shared__ int s_remaining, s_cand, s_ncand;
   __shared__ uint32_t cand[64];
+  __shared__ int s_gt[64], s_ge[64];  // per candidate: candidates above it / not below it
   const int tid = threadIdx.x;
   const int i0 = tid * IPT;
   int flip = 0;  // which buffer of `waves` the next scan uses
@@ -121,6 +122,7 @@ __device__ __forceinline__ void topk_block(const float* __restrict__ sc, int NP,
     for (int j = 0; j < IPT; ++j) key[j] = i0 + j < NP ? float_key(sc[i0 + j]) : 0u;
   }
   if (tid < 256) hist[tid] = 0;
+  if (tid < 64) s_gt[tid] = 0, s_ge[tid] = 0;
 
   // Bits above the highest bit in which two keys differ are common to all keys and
   // need no pass; starting at that bit also spreads the first histogram over many
@@ -177,16 +179,30 @@ __device__ __forceinline__ void topk_block(const float* __restrict__ sc, int NP,
       for (int j = 0; j < IPT; ++j)
         if (i0 + j < NP && (key[j] & decided) == prefix) cand[atomicAdd(&s_ncand, 1)] = key[j];
       __syncthreads();
-      if (tid < c) {
-        const uint32_t mine = cand[tid];
-        int gt = 0, ge = 0;
-        for (int i = 0; i < c; ++i) {
-          const uint32_t o = cand[i];
-          gt += o > mine;
-          ge += o >= mine;
+      // rank of every candidate among the candidates: wavefront w compares all of them with
+      // its share of the list, the partial counts meet in shared memory
+      {
+        constexpr int PER = (64 + NW - 1) / NW;
+        const int ci = tid & 63, j0 = (tid >> 6) * PER;
+        if (ci < c && j0 < c) {
+          const uint32_t mine = cand[ci];
+          int gt = 0, ge = 0;
+#pragma unroll
+          for (int j = 0; j < PER; ++j) {
+            const uint32_t o = cand[min(j0 + j, 63)];
+            const bool in = j0 + j < c;
+            gt += in && o > mine;
+            ge += in && o >= mine;
+          }
+          if (gt) atomicAdd(&s_gt[ci], gt);
+          if (ge) atomicAdd(&s_ge[ci], ge);
         }
+      }
+      __syncthreads();
+      if (tid < c) {
+        const int gt = s_gt[tid], ge = s_ge[tid];
         if (gt < remaining && remaining <= ge) {  // equal keys all write the same pair
-          s_prefix = mine;
+          s_prefix = cand[tid];
           s_remaining = remaining - gt;
         }
       }
