@@ -174,7 +174,7 @@ __device__ __forceinline__ void topk_block(const float* __restrict__ sc, int NP,
     if (shift == 0) break;
     const int c = s_cand;
     if (c <= 64) {
-      // Few keys are left: list them, and let one wavefront rank them directly.
+      // Few keys are left: list them and rank them directly.
 #pragma unroll
       for (int j = 0; j < IPT; ++j)
         if (i0 + j < NP && (key[j] & decided) == prefix) cand[atomicAdd(&s_ncand, 1)] = key[j];
