@@ -5,41 +5,51 @@
 
 namespace stc {
 
-// Routing mask of one token: bit g set iff group g is among the c largest of its G logits
-// (equal logits: the lower group first).
 // The G logits of one token (16-byte loads when G is a multiple of 4: the row is then
-// 16-byte aligned); entries at and beyond G are 0.
-__device__ __forceinline__ void load_token_logits(const float* __restrict__ lp, int G,
-                                                  float (&a)[16]) {
-  if ((G & 3) == 0) {
+// 16-byte aligned).
+template <int G>
+__device__ __forceinline__ void load_token_logits(const float* __restrict__ lp, float (&a)[G]) {
+  if constexpr ((G & 3) == 0) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (4 * q < G) v = *(const float4*)(lp + 4 * q);
+    for (int q = 0; q < G / 4; ++q) {
+      const float4 v = *(const float4*)(lp + 4 * q);
       a[4 * q] = v.x, a[4 * q + 1] = v.y, a[4 * q + 2] = v.z, a[4 * q + 3] = v.w;
     }
   } else {
 #pragma unroll
-    for (int g = 0; g < 16; ++g) a[g] = g < G ? lp[g] : 0.f;
+    for (int g = 0; g < G; ++g) a[g] = lp[g];
   }
 }
 
-__device__ __forceinline__ uint32_t rank_mask(const float* __restrict__ lp, int c, int G) {
-  float a[16];
-  load_token_logits(lp, G, a);
+// Routing mask of one token: bit g set iff group g is among the c largest of its G logits
+// (equal logits: the lower group first).
+template <int G>
+__device__ __forceinline__ uint32_t rank_mask_g(const float* __restrict__ lp, int c) {
+  float a[G];
+  load_token_logits<G>(lp, a);
   uint32_t m = 0;
 #pragma unroll
-  for (int g = 0; g < 16; ++g) {
-    if (g < G) {
-      int ahead = 0;  // groups ranked before g: larger logit, or equal with lower index
+  for (int g = 0; g < G; ++g) {
+    int ahead = 0;  // groups ranked before g: larger logit, or equal with lower index
 #pragma unroll
-      for (int g2 = 0; g2 < 16; ++g2) {
-        if (g2 < G && g2 != g) ahead += (a[g2] > a[g]) || (g2 < g && a[g2] == a[g]);
-      }
-      if (ahead < c) m |= 1u << g;
-    }
+    for (int g2 = 0; g2 < G; ++g2)
+      if (g2 != g) ahead += (a[g2] > a[g]) || (g2 < g && a[g2] == a[g]);
+    if (ahead < c) m |= 1u << g;
   }
   return m;
+}
+
+// The same for a group count known at run time (a power of two up to 16, uniform over the
+// launch: the switch is a scalar branch).
+__device__ __forceinline__ uint32_t rank_mask(const float* __restrict__ lp, int c, int G) {
+  switch (G) {
+    case 1: return rank_mask_g<1>(lp, c);
+    case 2: return rank_mask_g<2>(lp, c);
+    case 4: return rank_mask_g<4>(lp, c);
+    case 8: return rank_mask_g<8>(lp, c);
+    case 16: return rank_mask_g<16>(lp, c);
+    default: return 0u;
+  }
 }
 
 // Minimum and maximum of 8 adjacent channels over `ntok` token rows (row stride D*2 bytes,

@@ -233,35 +233,34 @@ __global__ __launch_bounds__(256) void global_eq_scan_kernel(uint32_t* chunk_eq,
 // Masks of a chunk of 256 tokens from the stream's key: pairs above it, and the first
 // `remaining` pairs equal to it in (token, group) order.  Also the chunk's number of kept
 // groups, as route_mask_kernel writes it.  budget == 0 keeps nothing.
+template <int G>
 __global__ __launch_bounds__(kChunk) void global_mask_kernel(
     const float* __restrict__ logits, const GlobalState* __restrict__ state,
     const uint32_t* __restrict__ chunk_eq, uint16_t* __restrict__ mask,
-    uint32_t* __restrict__ chunk_sum, int N, int G, int nchunks, int Ncap, uint32_t budget) {
+    uint32_t* __restrict__ chunk_sum, int N, int nchunks, int Ncap, uint32_t budget) {
   __shared__ int red[4];
   const int stream = blockIdx.y;
   const int t = blockIdx.x * kChunk + threadIdx.x;
   const GlobalState gs = state[stream];
   const uint32_t prefix = gs.prefix, remaining = gs.remaining;
   const bool ranked = budget > 0 && !gs.take_all;  // equal pairs are taken in order
-  float lg[16];
-  load_token_logits(logits + ((size_t)stream * N + min(t, N - 1)) * G, G, lg);
-  uint32_t key[16];
+  float lg[G];
+  load_token_logits<G>(logits + ((size_t)stream * N + min(t, N - 1)) * G, lg);
+  uint32_t key[G];
   int eq = 0;
 #pragma unroll
-  for (int g = 0; g < 16; ++g) {
-    key[g] = (g < G && t < N) ? logit_key(lg[g]) : 0u;
-    eq += (g < G && t < N && ranked) && key[g] == prefix;
+  for (int g = 0; g < G; ++g) {
+    key[g] = t < N ? logit_key(lg[g]) : 0u;
+    eq += (t < N && ranked) && key[g] == prefix;
   }
   uint32_t e = (ranked ? chunk_eq[(size_t)stream * nchunks + blockIdx.x] : 0u) +
                (uint32_t)block_exscan_256(eq, red, nullptr);
   uint32_t m = 0;
-  if (budget > 0) {
+  if (budget > 0 && t < N) {
 #pragma unroll
-    for (int g = 0; g < 16; ++g) {
-      if (g < G && t < N) {
-        if (key[g] > prefix) m |= 1u << g;
-        else if (key[g] == prefix && (!ranked || e++ < remaining)) m |= 1u << g;
-      }
+    for (int g = 0; g < G; ++g) {
+      if (key[g] > prefix) m |= 1u << g;
+      else if (key[g] == prefix && (!ranked || e++ < remaining)) m |= 1u << g;
     }
   }
   if (t < N) mask[(size_t)stream * Ncap + t] = (uint16_t)m;
@@ -406,8 +405,21 @@ int launch_route_pack(const stc_shape_t& s, int mode, const void* V, const float
       global_eq_kernel<<<grid, kChunk, 0, st>>>(logits, state, chunk_eq, s.N, s.G, nchunks);
       global_eq_scan_kernel<<<streams, 256, 0, st>>>(chunk_eq, state, nchunks);
     }
-    global_mask_kernel<<<grid, kChunk, 0, st>>>(logits, state, chunk_eq, mask, chunk, s.N, s.G,
-                                                nchunks, Ncap, budget);
+#define STC_GLOBAL_MASK(GG)                                                                   \
+  case GG:                                                                                    \
+    global_mask_kernel<GG><<<grid, kChunk, 0, st>>>(logits, state, chunk_eq, mask, chunk, s.N, \
+                                                    nchunks, Ncap, budget);                   \
+    break;
+    switch (s.G) {
+      STC_GLOBAL_MASK(1)
+      STC_GLOBAL_MASK(2)
+      STC_GLOBAL_MASK(4)
+      STC_GLOBAL_MASK(8)
+      STC_GLOBAL_MASK(16)
+      default:
+        return -1;
+    }
+#undef STC_GLOBAL_MASK
   } else {
     route_mask_kernel<<<grid, kChunk, 0, st>>>(mode, logits, kcount, fixed_k, mask_in, mask, chunk,
                                                s.N, s.G, nchunks, Ncap, s.N);
