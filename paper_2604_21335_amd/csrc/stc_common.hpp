@@ -40,42 +40,12 @@ __host__ __device__ constexpr int bounds_tile_unit(int D, int pt, int c) {
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-// DPP lane moves inside a row of 16 lanes.  Control codes of the gfx9 DPP
-// encoding: quad_perm = 2 bits per lane of the quad; 0x140 row_mirror
-// (lane i <- lane 15-i); 0x141 row_half_mirror (lane i <- lane 7-i in each half).
-constexpr int kDppXor1 = 0xB1;       // quad_perm [1,0,3,2]
-constexpr int kDppXor2 = 0x4E;       // quad_perm [2,3,0,1]
-constexpr int kDppHalfMirror = 0x141;
-constexpr int kDppMirror = 0x140;
-
+// DPP lane move inside a row of 16 lanes (control codes of the gfx9 DPP encoding; lanes
+// without a source read 0).
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float x) {
   return __int_as_float(
       __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
-}
-
-// Sum over an aligned block of LANES (2..16) lanes; every lane of the block
-// ends with the same bits.  Pairs are combined in xor-butterfly order
-// (distance 1, 2, 4, 8), i.e. as a balanced tree over adjacent lanes.  For
-// distances 4 and 8 the mirrored partner holds the same value as the xor
-// partner because the value is already uniform over quads / halves.
-template <int LANES>
-__device__ __forceinline__ float row_tree_sum(float x) {
-  static_assert(LANES == 2 || LANES == 4 || LANES == 8 || LANES == 16, "row of 16");
-  x = x + dpp_f32<kDppXor1>(x);
-  if (LANES >= 4) x = x + dpp_f32<kDppXor2>(x);
-  if (LANES >= 8) x = x + dpp_f32<kDppHalfMirror>(x);
-  if (LANES >= 16) x = x + dpp_f32<kDppMirror>(x);
-  return x;
-}
-
-template <int LANES>
-__device__ __forceinline__ float row_max(float x) {
-  x = fmaxf(x, dpp_f32<kDppXor1>(x));
-  if (LANES >= 4) x = fmaxf(x, dpp_f32<kDppXor2>(x));
-  if (LANES >= 8) x = fmaxf(x, dpp_f32<kDppHalfMirror>(x));
-  if (LANES >= 16) x = fmaxf(x, dpp_f32<kDppMirror>(x));
-  return x;
 }
 
 // Rows 0,1 and rows 2,3 (of 16 lanes) exchange values: every lane gets the sum of its own
@@ -86,8 +56,9 @@ __device__ __forceinline__ float row_pair_sum(float u) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// Sum over the 8 chunk lanes of a page (lane bits 2, 3, 4), continuing the balanced tree:
-// chunks (0,1)(2,3).. first.  row_ror:n makes lane i read lane i-n of its row, so after the
+// Sum over the 8 lanes that share lane bits 0, 1 and 5 (lane bits 2, 3, 4 count the chunks of
+// a page, or the pieces of a token's channel chunk), continuing the balanced tree: chunks
+// (0,1)(2,3).. first.  row_ror:n makes lane i read lane i-n of its row, so after the
 // two rotations the lanes with bit 2 set hold ((c0+c1)+(c2+c3)) of their row; the row
 // exchange adds chunks 4..7.  Valid in lanes with (lane & 0x1c) == 4.
 __device__ __forceinline__ float chunk_tree_sum(float u) {
@@ -95,12 +66,7 @@ __device__ __forceinline__ float chunk_tree_sum(float u) {
   u += dpp_f32<0x128>(u);  // row_ror:8
   return row_pair_sum(u);
 }
-constexpr int kChunkSumLanes = 4;  // (lane & 0x1c) of the lanes that hold the page's sum
-
-// Value of lane `src_lane` (wave-uniform index) as a scalar.
-__device__ __forceinline__ float readlane_f32(float x, int src_lane) {
-  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), src_lane));
-}
+constexpr int kChunkSumLanes = 4;  // (lane & 0x1c) of the lanes that hold the sum
 
 // Order-preserving map of float bits to unsigned keys (finite inputs).
 __device__ __forceinline__ uint32_t float_key(float f) {
