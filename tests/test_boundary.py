@@ -248,3 +248,22 @@ def test_workload_generator_is_counter_based_and_seeded():
     ti = vlm["token_idx"]
     assert ti.shape == (2, 208) and bool((ti[:, 1:] > ti[:, :-1]).all())
     assert int(ti[:, 143].max()) < 576 and int(ti[0, 144]) == 576
+
+
+def test_header_is_plain_c_and_links(tmp_path):
+    """include/stc.h compiles as C99 with warnings as errors, and a C program linked against
+    libstc.so gets version, status strings, sizes and argument errors without a GPU."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    libdir = os.path.join(root, "paper_2604_21335_amd")
+    exe = str(tmp_path / "c_abi_check")
+    subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror",
+                    "-I", os.path.join(root, "include"),
+                    os.path.join(root, "tests", "c_abi_check.c"), "-o", exe,
+                    "-L", libdir, "-lstc", "-Wl,-rpath," + libdir], check=True)
+    out = subprocess.run([exe], capture_output=True, text=True)
+    assert out.returncode == 0, out.stdout + out.stderr
