@@ -61,20 +61,29 @@ def algorithmic_bytes(w, mean_kept):
             "parts": {"bounds": bounds, "K": Kb, "V": Vb, "meta": meta}}
 
 
+def cache_inputs(stc, W, w, dev, layer):
+    """K and V of one layer's cache ([B, Hkv, N, D]; the VLM prefix compacted to its retained
+    tokens) and the routing inputs that go with them."""
+    import torch
+    inp = W.make_cache_inputs(w, dev, layer=layer)
+    K, V = inp["K"], inp["V"]
+    if w.routing == "vlm":
+        n_src = w.n_visual + w.n_text
+        Kc = torch.empty(w.B, w.Hkv, w.N, w.D, dtype=torch.bfloat16, device=dev)
+        Vc = torch.empty_like(Kc)
+        stc.stc_compact_tokens(K, inp["token_idx"], Kc, w.B, w.Hkv, n_src, w.N, w.D)
+        stc.stc_compact_tokens(V, inp["token_idx"], Vc, w.B, w.Hkv, n_src, w.N, w.D)
+        K, V = Kc, Vc
+    return K, V, inp
+
+
 def build_replicas(stc, W, w, n_rep, dev):
     import torch
     caches = []
     kept = 0
     for r in range(n_rep * w.layers):
-        inp = W.make_cache_inputs(w, dev, layer=r)
-        K, V, logits = inp["K"], inp["V"], inp["logits"]
-        if w.routing == "vlm":
-            n_src = w.n_visual + w.n_text
-            Kc = torch.empty(w.B, w.Hkv, w.N, w.D, dtype=torch.bfloat16, device=dev)
-            Vc = torch.empty_like(Kc)
-            stc.stc_compact_tokens(K, inp["token_idx"], Kc, w.B, w.Hkv, n_src, w.N, w.D)
-            stc.stc_compact_tokens(V, inp["token_idx"], Vc, w.B, w.Hkv, n_src, w.N, w.D)
-            K, V = Kc, Vc
+        K, V, inp = cache_inputs(stc, W, w, dev, r)
+        logits = inp["logits"]
         c = stc.RoutedCache(w.B, w.Hq, w.Hkv, w.D, w.N, w.G, w.k_pages, device=dev,
                             keep_scores=False)
         c.build(K, V, logits=logits, kcount=inp["kcount"], mask_in=inp["mask_in"])
@@ -170,8 +179,10 @@ def bench_rows(stc, W, w, dev, n):
             rows[name]["note"] = note
 
     streams, gd, R = w.streams, w.D // w.G, w.R
-    inp = W.make_cache_inputs(w, dev, layer=0)
-    K, V, logits, kcount = inp["K"], inp["V"], inp["logits"], inp["kcount"]
+    K, V, inp = cache_inputs(stc, W, w, dev, 0)
+    logits, kcount, mask_in = inp["logits"], inp["kcount"], inp["mask_in"]
+    if logits is None:                 # a workload routed by given masks: logits for the
+        logits = torch.randn(w.B, w.Hkv, w.N, w.G, device=dev)      # routing rows only
     c = stc.RoutedCache(w.B, w.Hq, w.Hkv, w.D, w.N, w.G, w.k_pages, device=dev, keep_scores=False)
     kv_bytes = streams * w.N * w.D * 2
     # a1, a2, f1: cache construction
@@ -183,14 +194,14 @@ def bench_rows(stc, W, w, dev, n):
         stc.stc_route_and_pack_values(c.shape, mode, V, logits, kc, fixed, None, c.mask, c.tok_off,
                                       c.vpacked, c.dev_status, c._ws_route)
     for name, mode, kc, fixed in (("stc_route_and_pack_values(top-k per token)",
-                                   stc.STC_ROUTE_TOPK, kcount, 0),
+                                   stc.STC_ROUTE_TOPK, kcount, 0 if kcount is not None else w.G // 2),
                                   ("stc_route_and_pack_values(global budget N*4)",
                                    stc.STC_ROUTE_GLOBAL, None, w.G // 2)):
         ms = timed(lambda i: route(mode, kc, fixed), n, torch)
         kept = int(c.tok_off[..., -1].to(torch.int64).sum().item())
         row(name, ms, kv_bytes + logits.numel() * 4 + (kcount.numel() if kc is not None else 0)
             + meta + kept * gd * 2)
-    c.build(K, V, logits=logits, kcount=kcount)
+    c.build(K, V, logits=inp["logits"], kcount=kcount, mask_in=mask_in)
     mean_kept = int(c.tok_off[..., -1].to(torch.int64).sum().item()) / float(streams * w.N)
     ab = algorithmic_bytes(w, mean_kept)
     # f4: the router's projection (hidden size of the 7B models of the paper's LLM setting)
@@ -209,13 +220,13 @@ def bench_rows(stc, W, w, dev, n):
     for r in range(3):
         t = stc.RoutedCache(w.B, w.Hq, w.Hkv, w.D, w.N, w.G, w.k_pages, device=dev,
                             keep_scores=False, tail_cap=128, n_cap=w.N + 2048)
-        ri = W.make_cache_inputs(w, dev, layer=r + 1)
-        t.build(ri["K"], ri["V"], logits=ri["logits"], kcount=ri["kcount"])
+        rK, rV, ri = cache_inputs(stc, W, w, dev, r + 1)
+        t.build(rK, rV, logits=ri["logits"], kcount=ri["kcount"], mask_in=ri["mask_in"])
         t.K_tail.copy_(torch.randn_like(t.K_tail, dtype=torch.float32))
         t.V_tail.copy_(torch.randn_like(t.V_tail, dtype=torch.float32))
         t.n_tail = 100
         tails.append(t)
-        del ri
+        del ri, rK, rV
     tail_bytes = streams * 100 * w.D * 2 * 2
     for i in range(20):
         tails[i % 3].step(qs[i % 8])
@@ -254,10 +265,10 @@ def bench_rows(stc, W, w, dev, n):
     for r in range(2):
         t = stc.RoutedCache(w.B, w.Hq, w.Hkv, w.D, w.N, w.G, w.k_pages, device=dev,
                             keep_scores=False)
-        ri = W.make_cache_inputs(w, dev, layer=r + 4)
-        t.build(ri["K"], ri["V"], logits=ri["logits"], kcount=ri["kcount"])
+        rK, rV, ri = cache_inputs(stc, W, w, dev, r + 4)
+        t.build(rK, rV, logits=ri["logits"], kcount=ri["kcount"], mask_in=ri["mask_in"])
         ph.append(t)
-        del ri
+        del ri, rK, rV
     idx = torch.empty(w.B, w.Hq, k, dtype=torch.int32, device=dev)
 
     def ws(which, kk):
