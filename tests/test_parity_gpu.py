@@ -242,7 +242,9 @@ def test_scores_for_every_head_group_size(Hq, Hkv, D):
 
 
 @pytest.mark.parametrize("N,G,D,gk", [(1000, 8, 128, 3), (2500, 4, 64, 1), (777, 16, 128, 5),
-                                      (4096, 8, 128, 0), (300, 4, 64, 4), (1024, 1, 64, 1)])
+                                      (4096, 8, 128, 0), (300, 4, 64, 4), (1024, 1, 64, 1),
+                                      (999, 2, 64, 1), (333, 1, 64, 1),   # N*G not a multiple of 4
+                                      (40000, 8, 128, 5)])                # several histogram slices
 def test_global_budget_routing(N, G, D, gk):
     """Global token-group budget: masks (tokens with no group included), offsets and packed
     values bit for bit; exactly N*K groups kept; attention over the result within the bar."""
