@@ -445,7 +445,8 @@ def test_union_pages_long_streams_and_long_lists(B, Hkv, R, NP, k):
 
 @pytest.mark.parametrize("B,Hkv,N,dm,G,with_bias", [(2, 2, 301, 512, 8, True), (1, 3, 64, 128, 4, False),
                                                      (1, 1, 1000, 3584, 8, True),
-                                                     (2, 1, 77, 256, 16, False), (1, 2, 50, 384, 1, True)])
+                                                     (2, 1, 77, 256, 16, False), (1, 2, 50, 384, 1, True),
+                                                     (1, 1, 130, 256, 2, True)])
 def test_router_logits_bits_and_routing(B, Hkv, N, dm, G, with_bias):
     """The router's projection bit for bit (the order of its float additions is part of the
     definition), replicated over the KV heads; masks routed from it equal the oracle's."""
