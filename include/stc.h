@@ -36,7 +36,8 @@
  *   - bf16 tensors are passed as void* (2 bytes per element).
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
  *     the default stream).  No call synchronises, allocates, frees or keeps
- *     state between calls.
+ *     state between calls (the library only remembers, per device, that it has
+ *     raised the LDS limit of its own kernels).
  *   - Return value: STC_OK (0) or a negative STC_ERR_* code.  On error nothing
  *     has been enqueued.  Inputs are expected to be finite (no NaN/Inf).
  *   - Ties in every top-k are broken towards the lowest index.

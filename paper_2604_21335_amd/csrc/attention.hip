@@ -620,10 +620,10 @@ template <int D, int PAIRS, int WAVES, bool TAIL, int SELECT_IPT>
 int attn_go(const AttnArgs& a) {
   // workgroups of 8 wavefronts at D = 128 need more than the default 64 KiB of LDS
   constexpr int lds_bytes = WAVES * AttnCfg<D>::WAVE_LDS;
-  static const hipError_t attr = hipFuncSetAttribute(
-      (const void*)attn_mfma_kernel<D, PAIRS, WAVES, TAIL, SELECT_IPT>,
-      hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-  if (attr != hipSuccess) return -1;
+  static std::atomic<uint64_t> allowed{0};
+  if (!allow_dynamic_lds((const void*)attn_mfma_kernel<D, PAIRS, WAVES, TAIL, SELECT_IPT>,
+                         lds_bytes, allowed))
+    return -1;
   attn_mfma_kernel<D, PAIRS, WAVES, TAIL, SELECT_IPT><<<a.grid, 64 * WAVES, lds_bytes, a.st>>>(
       a.q, a.K, a.vpacked, a.mask, a.tok_off, a.page_idx, a.partial, a.out, a.Hq, a.Hkv, a.N, a.NP,
       a.G, a.cap, a.k_pages, a.splits, a.K_tail, a.V_tail, a.n_tail, a.tail_cap, a.kv_div,

@@ -177,9 +177,8 @@ int launch_union_pages(const stc_shape_t& s, const int32_t* page_idx_per_head, i
   const int R = s.Hq / s.Hkv;
   const size_t lds = (size_t)R * k_pages * sizeof(int32_t);
   // up to 64 KiB of lists next to the 16 KiB of head sets: beyond the default LDS limit
-  static const hipError_t attr = hipFuncSetAttribute(
-      (const void*)union_pages_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
-  if (attr != hipSuccess) return -1;
+  static std::atomic<uint64_t> allowed{0};
+  if (!allow_dynamic_lds((const void*)union_pages_kernel, 65536, allowed)) return -1;
   union_pages_kernel<<<s.B * s.Hkv, 256, lds, st>>>(page_idx_per_head, union_idx, union_heads, NP,
                                                     R, k_pages, U);
   return hipGetLastError() == hipSuccess ? 0 : -1;

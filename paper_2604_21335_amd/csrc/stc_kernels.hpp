@@ -6,6 +6,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/stc.h"
 
 namespace stc {
@@ -16,6 +18,19 @@ constexpr int kBoundsTilePages = 8;  // pages per tile of the bounds layout
 inline int token_cap(const stc_shape_t& s) { return s.N_cap ? s.N_cap : s.N; }
 __host__ __device__ inline int bounds_tiles(int tokens) {
   return ((tokens + 15) / 16 + kBoundsTilePages - 1) / kBoundsTilePages;
+}
+
+// Raises a kernel's limit of dynamic LDS, once per device of the process (`done` holds one bit
+// per device: the attribute belongs to the device's copy of the kernel).  False if the runtime
+// refuses.  The only thing the library remembers between calls.
+inline bool allow_dynamic_lds(const void* kernel, int bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+  if ((done.load(std::memory_order_acquire) >> dev) & 1u) return true;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
+    return false;
+  done.fetch_or(1ull << dev, std::memory_order_release);
+  return true;
 }
 
 int launch_bounds(const stc_shape_t& s, const void* K, void* bounds, hipStream_t st);
