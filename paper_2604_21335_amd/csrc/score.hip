@@ -20,6 +20,7 @@
 // of chunk (l/4)%8; the 16 blocks of the MFMA are the 16 (page group, chunk) pairs.
 #include "stc_common.hpp"
 #include "stc_kernels.hpp"
+#include "topk_block.hpp"
 
 namespace stc {
 
@@ -39,16 +40,24 @@ __device__ __forceinline__ bf16x4 as_bf16x4(uint32_t w0, uint32_t w1) {
 
 // PER_HEAD: every query head's own score is written ([B, Hq, NP]) instead of the maximum
 // over the heads of the KV head ([B, Hkv, NP]).
-template <int D, int R, bool PER_HEAD>
-__global__ __launch_bounds__(256) __attribute__((STC_SCORE_WAVES_PER_SIMD))
+// SELECT: one workgroup of 8 wavefronts scores a whole stream (NP <= 2048) into LDS and then
+// selects the stream's k pages itself (`score` is then an optional copy of the scores): the
+// form for many streams of few pages each, where a stream per workgroup still fills the chip
+// and the selection needs no launch of its own.
+constexpr int kScoreSelectPages = 2048;
+template <int D, int R, bool PER_HEAD, bool SELECT>
+__global__ __launch_bounds__(SELECT ? 512 : 256) __attribute__((STC_SCORE_WAVES_PER_SIMD))
 void score_mfma_kernel(const u32x4* __restrict__ tiles, const uint16_t* __restrict__ q,
                        float* __restrict__ score, int NP, int Hq, int Hkv, int tiles_per_block,
-                       int tiles_cap) {
+                       int tiles_cap, int32_t* __restrict__ page_idx, int k_pages) {
+  static_assert(!(SELECT && PER_HEAD), "one list per KV head");
   constexpr int CH = D / 8;        // channels per lane
   constexpr int NJ = CH / 4;       // 16-byte units per lane and tile
   constexpr int NG = (R + 3) / 4;  // groups of 4 query heads (MFMA rows)
   constexpr int T16 = NJ * 64;     // 16-byte units per tile
-  const int stream = blockIdx.y;
+  constexpr int WAVES = SELECT ? 8 : 4;
+  __shared__ __align__(16) float s_score[SELECT ? kScoreSelectPages : 4];
+  const int stream = SELECT ? blockIdx.x : blockIdx.y;
   const int b = stream / Hkv, kvh = stream % Hkv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row = lane & 3, e = (lane >> 2) & 7;
@@ -70,9 +79,10 @@ void score_mfma_kernel(const u32x4* __restrict__ tiles, const uint16_t* __restri
     }
   }
 
-  const int t0 = blockIdx.x * tiles_per_block, t1 = min(t0 + tiles_per_block, ntiles);
+  const int t0 = SELECT ? 0 : blockIdx.x * tiles_per_block;
+  const int t1 = SELECT ? ntiles : min(t0 + tiles_per_block, ntiles);
   const u32x4* base = tiles + (size_t)stream * tiles_cap * T16 + lane;  // capacity stride
-  float* out = score + (size_t)stream * (PER_HEAD ? R : 1) * NP;
+  float* out = SELECT ? s_score : score + (size_t)stream * (PER_HEAD ? R : 1) * NP;
   const int tlast = t1 - 1;
 
   // tile index past the block's range: its last tile is fetched again (never stored)
@@ -124,17 +134,25 @@ void score_mfma_kernel(const u32x4* __restrict__ tiles, const uint16_t* __restri
   int t = t0 + wave;
   u32x4 d0[NJ], d1[NJ];
   STC_LOAD_TILE(d0, t);
-  STC_LOAD_TILE(d1, t + 4);
-  for (; t < t1; t += 8) {
+  STC_LOAD_TILE(d1, t + WAVES);
+  for (; t < t1; t += 2 * WAVES) {
     STC_SCORE_TILE(d0, t);
-    STC_LOAD_TILE(d0, t + 8);
-    if (t + 4 < t1) {
-      STC_SCORE_TILE(d1, t + 4);
-      STC_LOAD_TILE(d1, t + 12);
+    STC_LOAD_TILE(d0, t + 2 * WAVES);
+    if (t + WAVES < t1) {
+      STC_SCORE_TILE(d1, t + WAVES);
+      STC_LOAD_TILE(d1, t + 3 * WAVES);
     }
   }
 #undef STC_LOAD_TILE
 #undef STC_SCORE_TILE
+  if constexpr (SELECT) {
+    __syncthreads();
+    if (score)
+      for (int i = threadIdx.x; i < NP; i += 64 * WAVES) score[(size_t)stream * NP + i] = s_score[i];
+    int32_t* list = page_idx + (size_t)stream * k_pages;
+    topk_block<kScoreSelectPages / (64 * WAVES), 64 * WAVES>(
+        s_score, NP, k_pages, [list](int pos, int page) { list[pos] = page; });
+  }
 }
 
 // Any number of query heads per KV head (up to 16), one head at a time on the VALU: the
@@ -199,14 +217,14 @@ static void launch_score_d(const stc_shape_t& s, const void* q, const void* boun
   dim3 grid((ntiles + tpb - 1) / tpb, streams);
   const u32x4* t4 = (const u32x4*)bounds;
   const uint16_t* q16 = (const uint16_t*)q;
-#define STC_SCORE_CASE(RR)                                                                  \
-  case RR:                                                                                  \
-    if (per_head)                                                                           \
-      score_mfma_kernel<D, RR, true><<<grid, 256, 0, st>>>(t4, q16, score, NP, s.Hq, s.Hkv, \
-                                                           tpb, tcap);                      \
-    else                                                                                    \
-      score_mfma_kernel<D, RR, false><<<grid, 256, 0, st>>>(t4, q16, score, NP, s.Hq,       \
-                                                            s.Hkv, tpb, tcap);              \
+#define STC_SCORE_CASE(RR)                                                                    \
+  case RR:                                                                                    \
+    if (per_head)                                                                             \
+      score_mfma_kernel<D, RR, true, false><<<grid, 256, 0, st>>>(t4, q16, score, NP, s.Hq,   \
+                                                                  s.Hkv, tpb, tcap, nullptr, 0); \
+    else                                                                                      \
+      score_mfma_kernel<D, RR, false, false><<<grid, 256, 0, st>>>(t4, q16, score, NP, s.Hq,  \
+                                                                   s.Hkv, tpb, tcap, nullptr, 0); \
     break;
   switch (R) {
     STC_SCORE_CASE(1)
@@ -222,6 +240,49 @@ static void launch_score_d(const stc_shape_t& s, const void* q, const void* boun
                                                 per_head ? 1 : 0, tcap);
   }
 #undef STC_SCORE_CASE
+}
+
+// Scoring and selection of a whole stream by one workgroup (see SELECT above).
+template <int D>
+static int launch_score_select_d(const stc_shape_t& s, const void* q, const void* bounds,
+                                 float* score, int32_t* page_idx, int k_pages, int NP,
+                                 hipStream_t st) {
+  const int streams = s.B * s.Hkv;
+  const int tcap = bounds_tiles(token_cap(s));
+  const u32x4* t4 = (const u32x4*)bounds;
+  const uint16_t* q16 = (const uint16_t*)q;
+#define STC_SCORE_SELECT_CASE(RR)                                                            \
+  case RR:                                                                                   \
+    score_mfma_kernel<D, RR, false, true><<<streams, 512, 0, st>>>(t4, q16, score, NP, s.Hq, \
+                                                                   s.Hkv, 0, tcap, page_idx, \
+                                                                   k_pages);                 \
+    break;
+  switch (s.Hq / s.Hkv) {
+    STC_SCORE_SELECT_CASE(1)
+    STC_SCORE_SELECT_CASE(2)
+    STC_SCORE_SELECT_CASE(3)
+    STC_SCORE_SELECT_CASE(4)
+    STC_SCORE_SELECT_CASE(5)
+    STC_SCORE_SELECT_CASE(6)
+    STC_SCORE_SELECT_CASE(7)
+    STC_SCORE_SELECT_CASE(8)
+    default:
+      return -1;
+  }
+#undef STC_SCORE_SELECT_CASE
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+bool score_can_select(const stc_shape_t& s, int k_pages) {
+  const int NP = (s.N + kPage - 1) / kPage;
+  return k_pages < NP && NP <= kScoreSelectPages && s.Hq / s.Hkv <= 8 && s.B * s.Hkv >= 192;
+}
+
+int launch_score_select(const stc_shape_t& s, const void* q, const void* bounds, float* score,
+                        int32_t* page_idx, int k_pages, hipStream_t st) {
+  const int NP = (s.N + kPage - 1) / kPage;
+  return s.D == 128 ? launch_score_select_d<128>(s, q, bounds, score, page_idx, k_pages, NP, st)
+                    : launch_score_select_d<64>(s, q, bounds, score, page_idx, k_pages, NP, st);
 }
 
 int launch_score(const stc_shape_t& s, const void* q, const void* bounds, float* score,

@@ -99,6 +99,8 @@ int launch_select(const stc_shape_t& s, const void* q, const void* bounds, int k
     iota_pages_kernel<<<(total + 255) / 256, 256, 0, st>>>(page_idx, NP, total);
     return hipGetLastError() == hipSuccess ? 0 : -1;
   }
+  if (!per_head && score_can_select(s, k_pages))
+    return launch_score_select(s, q, bounds, score, page_idx, k_pages, st);
   if (launch_score(s, q, bounds, score, per_head, st)) return -1;
   // keys per thread; streams of more than 1024 pages use 512 threads (measured: faster than
   // both 256 threads with more keys each and 1024 threads with longer barriers)

@@ -44,6 +44,11 @@ int launch_route_pack(const stc_shape_t& s, int mode, const void* V, const float
 // per_head: one score row per query head ([B, Hq, NP]) instead of one per KV head
 int launch_score(const stc_shape_t& s, const void* q, const void* bounds, float* score,
                  bool per_head, hipStream_t st);
+// One workgroup per stream scores the stream and selects its pages (many streams of at most
+// 2048 pages); `score` may be nullptr.  Only if score_can_select().
+bool score_can_select(const stc_shape_t& s, int k_pages);
+int launch_score_select(const stc_shape_t& s, const void* q, const void* bounds, float* score,
+                        int32_t* page_idx, int k_pages, hipStream_t st);
 int launch_select(const stc_shape_t& s, const void* q, const void* bounds, int k_pages,
                   int32_t* page_idx, float* score, bool per_head, hipStream_t st);
 

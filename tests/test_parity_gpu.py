@@ -40,6 +40,9 @@ CASES = [
     (2, 2, 2, 128, 16, 8, 1),          # a single page
     (1, 1, 1, 64, 5, 4, 1),            # fewer tokens than a page
     (1, 16, 1, 128, 640, 4, 12),       # 16 query heads on one KV head
+    (48, 4, 4, 64, 600, 4, 9),         # 192 streams: a workgroup scores and selects a stream
+    (49, 28, 4, 128, 1000, 8, 20),     # the same with 7 heads per KV head
+    (64, 6, 3, 128, 20, 8, 1),         # 192 streams of two pages
 ]
 
 
@@ -163,6 +166,36 @@ def test_decode_step_is_the_two_calls_in_one(B, Hkv, R, N, k):
     b, h = B - 1, Hkv - 1
     sc = O.page_scores(W.bf16_bits(q[b, h * R:(h + 1) * R]), O.page_bounds(W.bf16_bits(K[b, h])))
     assert np.array_equal(idx[b, h].cpu().numpy(), O.select_pages(sc, k))
+
+
+def test_many_streams_of_2048_pages_select_in_the_scoring_workgroup():
+    """192 streams of exactly 2048 pages (the most a scoring workgroup orders by itself) and of
+    2049 (one more: separate launches): lists against the oracle on sampled streams, and the
+    scores bit for bit."""
+    dev = "cuda:0"
+    for N in (32768, 32769):
+        B, Hq, Hkv, D, G, k = 48, 8, 4, 64, 2, 100
+        g = torch.Generator(device=dev)
+        g.manual_seed(N)
+        K = torch.randn(B, Hkv, N, D, device=dev, generator=g).bfloat16()
+        q = torch.randn(B, Hq, D, device=dev, generator=g).bfloat16()
+        shape = stc.make_shape(B, Hq, Hkv, D, N, G, N * G)
+        bounds = torch.empty(stc.stc_bounds_bytes(shape) // 2, dtype=torch.bfloat16, device=dev)
+        stc.stc_build_page_bounds(shape, K, bounds)
+        NP = (N + 15) // 16
+        idx = torch.full((B, Hkv, k), -1, dtype=torch.int32, device=dev)
+        score = torch.full((B, Hkv, NP), float("nan"), dtype=torch.float32, device=dev)
+        stc.stc_select_pages(shape, q, bounds, k, idx, score, None)
+        idx2 = torch.full_like(idx, -1)
+        ws = torch.empty(stc.stc_workspace_bytes(shape, stc.STC_WS_SELECT, k), dtype=torch.uint8,
+                         device=dev)
+        stc.stc_select_pages(shape, q, bounds, k, idx2, None, ws)      # scores in the workspace
+        torch.cuda.synchronize()
+        assert torch.equal(idx, idx2)
+        for (b, h) in ((0, 0), (47, 3), (20, 1)):
+            sc = O.page_scores(W.bf16_bits(q[b, 2 * h:2 * h + 2]), O.page_bounds(W.bf16_bits(K[b, h])))
+            assert np.array_equal(score[b, h].cpu().numpy().view(np.uint32), sc.view(np.uint32))
+            assert np.array_equal(idx[b, h].cpu().numpy(), O.select_pages(sc, k))
 
 
 def test_parity_very_long_stream():
