@@ -41,9 +41,9 @@ REPLICAS = {"tiny": 8, "llama2_7b_4k": 4, "qwen25_7b_32k": 6, "llava15_7b_prefix
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs of this file
 # (FETCH_SIZE and WRITE_SIZE, scaled by what the same counters read for a copy of known
 # size); see profiles/.  None where it has not been measured.
-MEASURED_TRAFFIC = {("qwen25_7b_32k", "score_mfma_kernel"): 68624568,
-                    ("llama2_7b_4k", "attn_mfma_kernel"): 111303501,
-                    ("llava15_7b_prefix", "attn_mfma_kernel"): 175606590}
+MEASURED_TRAFFIC = {("qwen25_7b_32k", "score_mfma_kernel"): 68624809,
+                    ("llama2_7b_4k", "attn_mfma_kernel"): 111302928,
+                    ("llava15_7b_prefix", "attn_mfma_kernel"): 175606606}
 
 
 def algorithmic_bytes(w, mean_kept):
