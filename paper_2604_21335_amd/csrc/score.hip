@@ -273,9 +273,15 @@ static int launch_score_select_d(const stc_shape_t& s, const void* q, const void
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
+// Where the single workgroup per stream wins (measured on 64..512 streams of 256..2048 pages
+// against scoring and selection as two launches): always on short streams, where both forms
+// are bound by their launches; with few heads per KV head (registers for two workgroups per
+// CU) from 128 streams on; with many heads once every CU has a stream.
 bool score_can_select(const stc_shape_t& s, int k_pages) {
   const int NP = (s.N + kPage - 1) / kPage;
-  return k_pages < NP && NP <= kScoreSelectPages && s.Hq / s.Hkv <= 8 && s.B * s.Hkv >= 192;
+  const int R = s.Hq / s.Hkv, streams = s.B * s.Hkv;
+  if (k_pages >= NP || NP > kScoreSelectPages || R > 8) return false;
+  return NP <= 256 || (R <= 4 && streams >= 128) || streams >= 256;
 }
 
 int launch_score_select(const stc_shape_t& s, const void* q, const void* bounds, float* score,
