@@ -789,6 +789,58 @@ def test_global_budget_at_full_llm_size():
         assert np.abs(got - want).max() <= PT.TIGHT
 
 
+def test_router_at_full_llm_size_sampled_tokens():
+    """The router's projection on the headline shape (16 x 32768 tokens of width 3584, 8 groups,
+    as the benchmark times it): sampled tokens bit for bit, the copies for all KV heads equal."""
+    dev = "cuda:0"
+    B, N, dm, G, Hkv = 16, 32768, 3584, 8, 4
+    g = torch.Generator(device=dev)
+    g.manual_seed(3584)
+    h = torch.randn(B, N, dm, device=dev, generator=g).bfloat16()
+    Wr = (torch.randn(G, dm, device=dev, generator=g) / dm ** 0.5).bfloat16()
+    bias = torch.randn(G, device=dev, generator=g)
+    logits = torch.full((B, Hkv, N, G), float("nan"), dtype=torch.float32, device=dev)
+    stc.stc_router_logits(h, Wr, bias, logits, Hkv)
+    torch.cuda.synchronize()
+    assert torch.equal(logits[:, 0], logits[:, Hkv - 1])
+    rng = np.random.default_rng(5)
+    Wb, bb = W.bf16_bits(Wr), bias.cpu().numpy()
+    for b in (0, 7, B - 1):
+        ts = np.concatenate([[0, N - 1], rng.integers(0, N, size=30)])
+        want = O.router_logits(W.bf16_bits(h[b, ts]), Wb, bb)
+        got = logits[b, 1, ts].cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+
+
+def test_decode_step_with_tail_at_full_llm_size_sampled_streams():
+    """The headline shape with 100 recent tokens in the uncompressed tail, through the one-call
+    step as the benchmark's --rows times it: sampled streams against the oracle."""
+    w = W.WORKLOADS["qwen25_7b_32k"]
+    dev = "cuda:0"
+    inp = W.make_cache_inputs(w, dev, 0)
+    c = stc.RoutedCache(w.B, w.Hq, w.Hkv, w.D, w.N, w.G, w.k_pages, device=dev, tail_cap=128)
+    c.build(inp["K"], inp["V"], logits=inp["logits"], kcount=inp["kcount"])
+    g = torch.Generator(device=dev)
+    g.manual_seed(9)
+    c.K_tail.copy_(torch.randn(c.K_tail.shape, device=dev, generator=g))
+    c.V_tail.copy_(torch.randn(c.V_tail.shape, device=dev, generator=g))
+    c.n_tail = 100
+    q = W.make_query(w, 3, dev)
+    c.step(q)
+    torch.cuda.synchronize()
+    qb = W.bf16_bits(q)
+    for (b, h) in [(0, 0), (w.B - 1, w.Hkv - 1), (5, 2)]:
+        K, V = W.bf16_bits(inp["K"][b, h]), W.bf16_bits(inp["V"][b, h])
+        m = O.route_mask(inp["logits"][b, h].cpu().numpy(), inp["kcount"][b, h].cpu().numpy())
+        qh = qb[b, h * w.R:(h + 1) * w.R]
+        idx = O.select_pages(O.page_scores(qh, O.page_bounds(K)), w.k_pages)
+        assert np.array_equal(c.page_idx[b, h].cpu().numpy(), idx)
+        want = O.decode_attention(qh, K, V, m, idx, w.G, K_tail=W.bf16_bits(c.K_tail[b, h, :100]),
+                                  V_tail=W.bf16_bits(c.V_tail[b, h, :100]))
+        got = c.out[b, h * w.R:(h + 1) * w.R].cpu().numpy()
+        assert np.abs(got - want).max() <= PT.TIGHT
+
+
 def test_steps_are_deterministic():
     w = W.shrink(W.WORKLOADS["qwen25_7b_32k"], B=2, N=8192, k_pages=64)
     c, t = _run_workload(w)
