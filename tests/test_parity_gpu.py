@@ -841,6 +841,55 @@ def test_decode_step_with_tail_at_full_llm_size_sampled_streams():
         assert np.abs(got - want).max() <= PT.TIGHT
 
 
+def test_per_head_and_union_forms_at_full_llm_size_sampled_heads():
+    """The headline shape with one page list per query head, and with the lists of a KV head
+    merged: lists, union and outputs of sampled heads against the oracle; the two forms agree."""
+    w = W.WORKLOADS["qwen25_7b_32k"]
+    dev = "cuda:0"
+    inp = W.make_cache_inputs(w, dev, 0)
+    c = stc.RoutedCache(w.B, w.Hq, w.Hkv, w.D, w.N, w.G, w.k_pages, device=dev)
+    c.build(inp["K"], inp["V"], logits=inp["logits"], kcount=inp["kcount"])
+    q = W.make_query(w, 1, dev)
+    k, R, NP = w.k_pages, w.R, w.NP
+
+    def ws(which, kk):
+        return torch.empty(max(16, stc.stc_workspace_bytes(c.shape, which, kk)), dtype=torch.uint8,
+                           device=dev)
+    idx = torch.full((w.B, w.Hq, k), -1, dtype=torch.int32, device=dev)
+    out = torch.full((w.B, w.Hq, w.D), float("nan"), dtype=torch.float32, device=dev)
+    stc.stc_select_pages_per_head(c.shape, q, c.bounds, k, idx, None,
+                                  ws(stc.STC_WS_SELECT_PER_HEAD, k))
+    stc.stc_decode_attention_per_head(c.shape, q, c.K, c.vpacked, c.mask, c.tok_off, idx, k, out,
+                                      ws(stc.STC_WS_ATTENTION_PER_HEAD, k))
+    U = min(NP, R * k)
+    uidx = torch.full((w.B, w.Hkv, U), -5, dtype=torch.int32, device=dev)
+    uheads = torch.full((w.B, w.Hkv, U), -1, dtype=torch.int16, device=dev)
+    out_u = torch.full_like(out, float("nan"))
+    stc.stc_union_pages(c.shape, idx, k, uidx, uheads)
+    stc.stc_decode_attention_union(c.shape, q, c.K, c.vpacked, c.mask, c.tok_off, uidx, uheads,
+                                   out_u, ws(stc.STC_WS_ATTENTION, U))
+    torch.cuda.synchronize()
+    assert float((out - out_u).abs().max()) <= 2 * PT.TIGHT
+    qb = W.bf16_bits(q)
+    for (b, h) in [(0, 0), (w.B - 1, w.Hkv - 1)]:
+        K, V = W.bf16_bits(inp["K"][b, h]), W.bf16_bits(inp["V"][b, h])
+        m = O.route_mask(inp["logits"][b, h].cpu().numpy(), inp["kcount"][b, h].cpu().numpy())
+        bounds = O.page_bounds(K)
+        lists = []
+        for r in (0, R // 2, R - 1):
+            j = h * R + r
+            want_idx = O.select_pages(O.page_scores(qb[b, j:j + 1], bounds), k)
+            assert np.array_equal(idx[b, j].cpu().numpy(), want_idx)
+            want = O.decode_attention(qb[b, j:j + 1], K, V, m, want_idx, w.G)
+            assert np.abs(out[b, j:j + 1].cpu().numpy() - want).max() <= PT.TIGHT
+            assert np.abs(out_u[b, j:j + 1].cpu().numpy() - want).max() <= PT.TIGHT
+        pages, heads = O.union_pages(idx[b, h * R:(h + 1) * R].cpu().numpy(), NP)
+        n = len(pages)
+        assert np.array_equal(uidx[b, h, :n].cpu().numpy(), pages)
+        assert np.array_equal(PT.host_u16(uheads[b, h])[:n], heads)
+        assert (uidx[b, h, n:] == -1).all()
+
+
 def test_steps_are_deterministic():
     w = W.shrink(W.WORKLOADS["qwen25_7b_32k"], B=2, N=8192, k_pages=64)
     c, t = _run_workload(w)
