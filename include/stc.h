@@ -19,7 +19,8 @@
  *                        (token-level compaction helper)
  *   decode step          stc_select_pages (+ stc_score_pages: its scoring half alone),
  *                        stc_decode_attention; stc_decode_step does both in one call
- *                        (stc_decode_step_tail: with the uncompressed tail)
+ *                        (stc_decode_step_tail: with the uncompressed tail;
+ *                        stc_decode_step_static: without a caller-provided workspace)
  *   recent tokens        stc_append_tail, stc_decode_attention_tail (uncompressed tail),
  *                        stc_flush_tail (tail tokens into the compressed cache, in place)
  *   per-query-head form  stc_select_pages_per_head, stc_decode_attention_per_head,
@@ -222,6 +223,27 @@ int stc_decode_step(const stc_shape_t *shape, const void *q, const void *bounds,
                     const void *vpacked, const uint16_t *mask, const uint32_t *tok_off,
                     int k_pages, int32_t *page_idx, float *out, void *ws, size_t ws_bytes,
                     void *stream);
+
+/*
+ * stc_decode_step for callers that cannot allocate device memory or pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same
+ * kernels and the same results bit for bit; the page scores and split partials live in a
+ * scratch array that is part of the library's device image (STC_STATIC_SCRATCH_BYTES per GPU
+ * the library runs on, held until the process ends).  The call allocates and frees nothing;
+ * its first call on a device looks the array's address up (make that call outside a graph
+ * capture).
+ *   arguments as stc_decode_step, without ws / ws_bytes
+ *   STC_ERR_WORKSPACE if stc_workspace_bytes(shape, STC_WS_STEP, k_pages) exceeds
+ *   STC_STATIC_SCRATCH_BYTES (nothing is enqueued); STC_ERR_LAUNCH if the address look-up fails.
+ * All calls on one GPU share that GPU's array: two calls whose work overlaps in time (different
+ * streams, or threads) race on it; calls on one stream are ordered and safe.  Nothing in the
+ * array needs to start at zero: every byte a step reads it has written before.
+ */
+#define STC_STATIC_SCRATCH_BYTES (8 * 1024 * 1024)
+int stc_decode_step_static(const stc_shape_t *shape, const void *q, const void *bounds,
+                           const void *K, const void *vpacked, const uint16_t *mask,
+                           const uint32_t *tok_off, int k_pages, int32_t *page_idx, float *out,
+                           void *stream);
 
 /*
  * Routed decode attention with an uncompressed tail of recent tokens: the tokens generated

@@ -26,7 +26,8 @@ EXPORTS = ["stc_version", "stc_status_string", "stc_workspace_bytes", "stc_bound
            "stc_route_and_pack_values", "stc_select_pages", "stc_score_pages", "stc_decode_attention", "stc_decode_attention_tail", "stc_append_tail",
            "stc_select_pages_per_head", "stc_decode_attention_per_head", "stc_router_logits",
            "stc_union_pages", "stc_decode_attention_union", "stc_flush_tail",
-           "stc_compact_tokens", "stc_decode_step", "stc_decode_step_tail"]
+           "stc_compact_tokens", "stc_decode_step", "stc_decode_step_tail",
+           "stc_decode_step_static"]
 
 
 class StcError(RuntimeError):
@@ -98,6 +99,8 @@ def load_library():
                                               ctypes.c_int, ctypes.c_int, vp, vp, sz, vp]
     lib.stc_decode_step.restype = ctypes.c_int
     lib.stc_decode_step.argtypes = [shp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp, vp, sz, vp]
+    lib.stc_decode_step_static.restype = ctypes.c_int
+    lib.stc_decode_step_static.argtypes = [shp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp, vp]
     lib.stc_decode_step_tail.restype = ctypes.c_int
     lib.stc_decode_step_tail.argtypes = [shp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp,
                                          ctypes.c_int, ctypes.c_int, vp, vp, vp, sz, vp]
@@ -265,6 +268,19 @@ def stc_decode_step(shape, q, bounds, K, vpacked, mask, tok_off, k_pages, page_i
         _ptr(mask, _U16, "mask"), _ptr(tok_off, _U32, "tok_off"), int(k_pages),
         _ptr(page_idx, torch.int32, "page_idx"), _ptr(out, torch.float32, "out"),
         _ptr(ws, None, "ws"), _nbytes(ws), _stream()), "stc_decode_step")
+
+
+STC_STATIC_SCRATCH_BYTES = 8 * 1024 * 1024
+
+
+def stc_decode_step_static(shape, q, bounds, K, vpacked, mask, tok_off, k_pages, page_idx, out):
+    """stc_decode_step over the library's own static scratch array: no workspace argument."""
+    _check(load_library().stc_decode_step_static(
+        ctypes.byref(shape), _ptr(q, torch.bfloat16, "q"), _ptr(bounds, torch.bfloat16, "bounds"),
+        _ptr(K, torch.bfloat16, "K"), _ptr(vpacked, torch.bfloat16, "vpacked"),
+        _ptr(mask, _U16, "mask"), _ptr(tok_off, _U32, "tok_off"), int(k_pages),
+        _ptr(page_idx, torch.int32, "page_idx"), _ptr(out, torch.float32, "out"), _stream()),
+        "stc_decode_step_static")
 
 
 def stc_decode_step_tail(shape, q, bounds, K, vpacked, mask, tok_off, k_pages, K_tail, V_tail,

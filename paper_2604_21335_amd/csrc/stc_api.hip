@@ -37,11 +37,30 @@ size_t step_score_bytes(const stc_shape_t* s, int k_pages) {
   return (select_ws_bytes(s) + 255) & ~(size_t)255;
 }
 
+// Scratch memory of stc_decode_step_static: one copy per GPU, held until the process ends.
+// In host code the array's name is only a handle; its address on the current device comes
+// from hipGetSymbolAddress (static_scratch below) and is what the kernels are given.
+static __device__ __align__(256) unsigned char scratch[STC_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device, looked up once per device.
+void* static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p) return p;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+  g_scratch_ptr[dev].store(p, std::memory_order_release);
+  return p;
+}
+
 }  // namespace
 
 extern "C" {
 
-int stc_version(void) { return 1; }
+int stc_version(void) { return 2; }
 
 const char* stc_status_string(int status) {
   switch (status) {
@@ -307,6 +326,23 @@ int stc_decode_step_tail(const stc_shape_t* shape, const void* q, const void* bo
   return decode_step_impl(shape, q, bounds, K, vpacked, mask, tok_off, k_pages, K_tail, V_tail,
                           n_tail, tail_cap, page_idx, out, ws, ws_bytes,
                           step_score_bytes(shape, 0), stream);
+}
+
+int stc_decode_step_static(const stc_shape_t* shape, const void* q, const void* bounds,
+                           const void* K, const void* vpacked, const uint16_t* mask,
+                           const uint32_t* tok_off, int k_pages, int32_t* page_idx, float* out,
+                           void* stream) {
+  if (!shape) return STC_ERR_NULL;
+  if (!shape_ok(shape) || k_pages < 1 || k_pages > num_pages(shape)) return STC_ERR_SHAPE;
+  const size_t score_bytes = step_score_bytes(shape, k_pages);
+  const size_t need = score_bytes + stc::attention_ws_bytes(*shape, k_pages);
+  if (need > (size_t)STC_STATIC_SCRATCH_BYTES) return STC_ERR_WORKSPACE;
+  void* ws = static_scratch();
+  if (!ws) return STC_ERR_LAUNCH;
+  // every byte of the scratch region that a kernel of the step reads (page scores, split
+  // partials) has been written earlier in the same step, so nothing needs clearing
+  return decode_step_impl(shape, q, bounds, K, vpacked, mask, tok_off, k_pages, nullptr, nullptr,
+                          0, 0, page_idx, out, ws, STC_STATIC_SCRATCH_BYTES, score_bytes, stream);
 }
 
 int stc_flush_tail(const stc_shape_t* shape, const void* K_tail, const void* V_tail, int n_flush,
