@@ -48,6 +48,12 @@ Readings where the paper is silent:
     balanced adjacent-pair tree, the chunk sums accumulated left to right; an
     optional float32 bias is added last.  (Masks are integer decisions taken on
     these logits, so the order is part of the definition.)
+  * page scores and router logits take a bf16 input that is subnormal (exponent
+    field 0, |x| < 2^-126) as a zero: the paper fixes no arithmetic, the library
+    forms these products on matrix cores that read such inputs as zero, and a
+    key, query or hidden-state channel of that magnitude carries no signal.
+    Page bounds, masks and packed values keep subnormal bit patterns as they
+    are (they are compared and copied, never multiplied).
   * GQA: one page set per KV head; its score is the max over the query heads of
     that group.  Ties in every top-k go to the lowest index.  A zero score is +0.
   * the selected pages are listed in ascending page order.
@@ -74,6 +80,13 @@ def bf16_to_f32(bits):
     """uint16 bf16 bit patterns -> float32 (exact)."""
     bits = np.asarray(bits, dtype=np.uint16)
     return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def bf16_to_f32_daz(bits):
+    """bf16 bit patterns -> float32 with subnormal inputs read as zero."""
+    b = np.asarray(bits, dtype=np.uint16)
+    x = bf16_to_f32(b)
+    return np.where((b & np.uint16(0x7F80)) == 0, np.float32(0.0), x).astype(np.float32)
 
 
 def _f32_to_bf16_bits_exact(x):
@@ -127,8 +140,8 @@ def page_bounds(K_bits, P=16):
 def router_logits(h_bits, W_bits, bias=None):
     """h_bits[N, d_model], W_bits[G, d_model] (bf16 bits), bias[G] float32 or None
     -> logits[N, G] float32 = h W^T (+ bias), in the order stated in the header."""
-    h = bf16_to_f32(h_bits)                                   # [N, dm]
-    W = bf16_to_f32(W_bits)                                   # [G, dm]
+    h = bf16_to_f32_daz(h_bits)                               # [N, dm]
+    W = bf16_to_f32_daz(W_bits)                               # [G, dm]
     N, dm = h.shape
     G = W.shape[0]
     assert dm % 128 == 0, "d_model must be a multiple of 128"
@@ -237,8 +250,8 @@ def head_page_bounds_score(q_bits, bounds_bits):
     U_h[p] = sum_c max(q_h[c]*mn[p,c], q_h[c]*mx[p,c]); float32 terms summed by
     the balanced adjacent-pair tree.  D must be a power of two.
     """
-    q = bf16_to_f32(q_bits)                       # [R, D]
-    b = bf16_to_f32(bounds_bits)                  # [NP, 2, D]
+    q = bf16_to_f32_daz(q_bits)                   # [R, D]
+    b = bf16_to_f32_daz(bounds_bits)              # [NP, 2, D]
     mn, mx = b[:, 0, :], b[:, 1, :]
     term = np.maximum(q[:, None, :] * mn[None, :, :],
                       q[:, None, :] * mx[None, :, :]).astype(np.float32)

@@ -674,3 +674,94 @@ def test_union_pages_is_the_set_union_with_membership():
         own = O.decode_attention(q[r:r + 1], K, V, mask, [p for p in lists[r] if p >= 0], G)
         via = O.decode_attention(q[r:r + 1], K, V, mask, pages[(heads >> r) & 1 == 1], G)
         assert np.abs(own - via).max() < 1e-6
+
+
+# --------------------------------------------------------------------------- #
+# Subnormal bf16 inputs of the two multiply-and-sum routines count as zero
+# --------------------------------------------------------------------------- #
+def _with_subnormals(rng, bits, frac=0.15):
+    """A copy of bf16 bit patterns with a share of entries replaced by subnormal patterns
+    (exponent field 0, non-zero mantissa, either sign), and the same copy with zeros there."""
+    sub = bits.copy()
+    zero = bits.copy()
+    hit = rng.random(bits.shape) < frac
+    mant = rng.integers(1, 128, size=bits.shape).astype(np.uint16)
+    sign = (rng.integers(0, 2, size=bits.shape).astype(np.uint16) << np.uint16(15))
+    sub[hit] = (sign | mant)[hit]
+    zero[hit] = 0
+    return sub, zero
+
+
+def test_subnormal_inputs_are_zeros_for_page_scores():
+    """Closed form of the reading: scores with subnormal queries/bounds equal the scores of the
+    inputs with those entries set to zero; normal inputs are untouched (the float32 widening of
+    a subnormal bf16 is itself non-zero, so a dropped flush would change low-order bits when
+    the partner is large)."""
+    rng = np.random.default_rng(77)
+    K = randn_bf16(rng, (160, 64))
+    bounds = O.page_bounds(K)
+    q = randn_bf16(rng, (3, 64), 2.0 ** 100)              # large queries: sub * q is a normal float
+    b_sub, b_zero = _with_subnormals(rng, bounds)
+    q_sub, q_zero = _with_subnormals(rng, q)
+    want = O.head_page_bounds_score(q_zero, b_zero)
+    got = O.head_page_bounds_score(q_sub, b_sub)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    # the flush matters: plain IEEE arithmetic on the same bits gives other scores
+    plain_q, plain_b = bits_to_f64(q_sub), bits_to_f64(b_sub)
+    ieee = np.maximum(plain_q[:, None, :] * plain_b[None, :, 0, :],
+                      plain_q[:, None, :] * plain_b[None, :, 1, :]).sum(-1)
+    assert np.abs(ieee - want.astype(np.float64)).max() > 0
+    # the smallest normal bf16 is not flushed
+    one_q = np.zeros((1, 64), np.uint16)
+    one_q[0, 5] = 0x3F80                                   # 1.0
+    one_b = np.zeros((1, 2, 64), np.uint16)
+    one_b[0, :, 5] = 0x0080                                # 2^-126 in both bounds
+    assert O.head_page_bounds_score(one_q, one_b)[0, 0] == np.float32(2.0 ** -126)
+    one_b[0, :, 5] = 0x007F                                # largest subnormal
+    assert O.head_page_bounds_score(one_q, one_b)[0, 0] == 0.0
+
+
+def test_subnormal_inputs_are_zeros_for_router_logits():
+    rng = np.random.default_rng(78)
+    h = randn_bf16(rng, (40, 256), 2.0 ** 90)
+    Wb = randn_bf16(rng, (8, 256))
+    h_sub, h_zero = _with_subnormals(rng, h)
+    W_sub, W_zero = _with_subnormals(rng, Wb)
+    got, want = O.router_logits(h_sub, W_sub), O.router_logits(h_zero, W_zero)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    assert not np.array_equal(want, O.router_logits(h_zero, Wb))      # the zeros do change it
+
+
+# --------------------------------------------------------------------------- #
+# Router: the fixed float32 order decides the same masks as the exact product
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("dm,G", [(512, 8), (3584, 8), (1024, 16)])
+def test_masks_from_float32_router_logits_equal_masks_from_the_exact_product(dm, G):
+    """Validity of fixing a float32 summation order for the router: wherever the exact
+    (float64) logits separate the kept groups from the dropped ones by more than the float32
+    summation error can move them, top-K routing of the chunked float32 logits gives the mask
+    of the exact logits.  Bound used: 1e-5 * sum_c |h_c W_gc| per logit (float32 tree and chain
+    sums of d_model terms stay well inside it)."""
+    rng = np.random.default_rng(dm + G)
+    N = 600
+    h = randn_bf16(rng, (N, dm))
+    Wb = randn_bf16(rng, (G, dm), 1.0 / math.sqrt(dm))
+    bias = rng.standard_normal(G).astype(np.float32)
+    lg32 = O.router_logits(h, Wb, bias)
+    hf, Wf = bits_to_f64(h), bits_to_f64(Wb)
+    lg64 = hf @ Wf.T + bias.astype(np.float64)
+    slack = 1e-5 * (np.abs(hf) @ np.abs(Wf).T + np.abs(bias)[None, :])      # [N, G]
+    assert np.all(np.abs(lg32 - lg64) <= slack)
+    kcount = rng.integers(1, G, size=N).astype(np.uint8)                    # 1 .. G-1 kept
+    m32 = O.route_mask(lg32, kcount)
+    order = np.argsort(-lg64, axis=1, kind="stable")
+    m64 = np.zeros(N, dtype=np.uint16)                       # top-K of the exact logits
+    for t in range(N):
+        for g in order[t, :kcount[t]]:
+            m64[t] |= np.uint16(1 << int(g))
+    srt = np.take_along_axis(lg64, order, axis=1)
+    cut = kcount.astype(np.int64)
+    gap = srt[np.arange(N), cut - 1] - srt[np.arange(N), cut]               # margin at the cut
+    clear = gap > 2 * slack.max(axis=1)
+    assert clear.mean() > 0.9                                               # the check has teeth
+    assert np.array_equal(m32[clear], m64[clear])
