@@ -243,10 +243,10 @@ def bench_rows(stc, W, w, dev, n):
     evs = []
     for i in range(min(n, 24)):                     # N grows by 64 per flush: 24 * 64 <= 2048
         t = tails[i % 3]
-        t.n_tail = 64
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
-        stc.stc_flush_tail(t.shape, t.K_tail, t.V_tail, 64, t.tail_cap, stc.STC_ROUTE_TOPK, fl, None,
+        stc.stc_flush_tail(t.shape, t.K_tail, t.V_tail, 64, 100, t.tail_cap, stc.STC_ROUTE_TOPK, fl,
+                           None,
                            w.G // 2, None, t.K, t.bounds, t.mask, t.tok_off, t.vpacked,
                            t.dev_status)
         b.record()

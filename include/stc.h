@@ -163,9 +163,8 @@ int stc_route_and_pack_values(const stc_shape_t *shape, int mode, const void *V,
  *   score[p] = max over the query heads of the stream's KV head; -0 becomes +0.
  *   The k_eff = min(k_pages, NP) pages of largest score (ties: lowest p) are
  *   written in ascending order of p.
- *   Bit-exact for queries and bounds that are zero or normal finite bf16 values whose
- *   products stay finite in float (the matrix cores form the products; they treat
- *   subnormal bf16 inputs as zero).
+ *   A query or bound that is subnormal as bf16 (|x| < 2^-126) counts as zero; products must
+ *   stay finite in float.
  *   q          [B, Hq, D] bf16, in
  *   bounds     as written by stc_build_page_bounds, in (not read when k_pages >= NP)
  *   page_idx   [B, Hkv, k_eff] int32, out
@@ -308,15 +307,17 @@ int stc_decode_attention_per_head(const stc_shape_t *shape, const void *q, const
  * the call; N + n_flush <= N_cap).  Keys are copied, values are routed and packed behind the
  * stream's packed store, tok_off[N+1 .. N+n_flush] continue from tok_off[N], and the bounds of
  * every page holding a new token are recomputed.  The arrays then equal, bit for bit, what
- * cache construction over all N + n_flush tokens writes; the caller continues with
- * shape->N + n_flush and drops the moved rows from its tail.
- *   K_tail, V_tail [B, Hkv, tail_cap, D] bf16, in: rows 0 .. n_flush-1 are moved
+ * cache construction over all N + n_flush tokens writes.  The rows that stay in the tail
+ * (n_flush .. n_tail-1) are moved to its front; the caller continues with shape->N + n_flush
+ * cached and n_tail - n_flush tail tokens.
+ *   K_tail, V_tail [B, Hkv, tail_cap, D] bf16, in/out: rows 0 .. n_flush-1 are moved into the
+ *            cache, rows n_flush .. n_tail-1 to rows 0 .. (1 <= n_flush <= n_tail <= tail_cap)
  *   mode     STC_ROUTE_MASK (mask_in [B, Hkv, n_flush]) or STC_ROUTE_TOPK (logits
  *            [B, Hkv, n_flush, G], kcount [B, Hkv, n_flush] or fixed_k), as in
  *            stc_route_and_pack_values; a global budget cannot be continued
  *   K, bounds, mask, tok_off, vpacked, dev_status: the cache arrays, updated in place
  */
-int stc_flush_tail(const stc_shape_t *shape, const void *K_tail, const void *V_tail, int n_flush,
+int stc_flush_tail(const stc_shape_t *shape, void *K_tail, void *V_tail, int n_flush, int n_tail,
                    int tail_cap, int mode, const float *logits, const uint8_t *kcount,
                    int fixed_k, const uint16_t *mask_in, void *K, void *bounds, uint16_t *mask,
                    uint32_t *tok_off, void *vpacked, int32_t *dev_status, void *stream);
@@ -354,8 +355,8 @@ int stc_decode_attention_union(const stc_shape_t *shape, const void *q, const vo
  *   W      [G, d_model] bf16, in; G in {1, 2, 4, 8, 16}
  *   bias   [G] float, in, may be NULL
  *   logits [B, Hkv, N, G] float, out
- * h and W hold zeros or normal bf16 numbers (a subnormal bf16 input counts as zero), and their
- * products stay in the normal float range.
+ * An element of h or W that is subnormal as bf16 (|x| < 2^-126) counts as zero; products must
+ * stay finite in float.
  */
 int stc_router_logits(int32_t B, int32_t Hkv, int32_t N, int32_t d_model, int32_t G,
                       const void *h, const void *W, const float *bias, float *logits,

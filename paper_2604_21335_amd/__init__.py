@@ -87,7 +87,8 @@ def load_library():
     lib.stc_decode_attention_per_head.restype = ctypes.c_int
     lib.stc_decode_attention_per_head.argtypes = lib.stc_decode_attention.argtypes
     lib.stc_flush_tail.restype = ctypes.c_int
-    lib.stc_flush_tail.argtypes = [shp, vp, vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp,
+    lib.stc_flush_tail.argtypes = [shp, vp, vp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                   ctypes.c_int, vp, vp,
                                    ctypes.c_int, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.stc_union_pages.restype = ctypes.c_int
     lib.stc_union_pages.argtypes = [shp, vp, ctypes.c_int, vp, vp, ctypes.c_int, vp]
@@ -230,11 +231,11 @@ def stc_decode_attention_per_head(shape, q, K, vpacked, mask, tok_off, page_idx,
         "stc_decode_attention_per_head")
 
 
-def stc_flush_tail(shape, K_tail, V_tail, n_flush, tail_cap, mode, logits, kcount, fixed_k, mask_in,
+def stc_flush_tail(shape, K_tail, V_tail, n_flush, n_tail, tail_cap, mode, logits, kcount, fixed_k, mask_in,
                    K, bounds, mask, tok_off, vpacked, dev_status):
     _check(load_library().stc_flush_tail(
         ctypes.byref(shape), _ptr(K_tail, torch.bfloat16, "K_tail"),
-        _ptr(V_tail, torch.bfloat16, "V_tail"), int(n_flush), int(tail_cap), int(mode),
+        _ptr(V_tail, torch.bfloat16, "V_tail"), int(n_flush), int(n_tail), int(tail_cap), int(mode),
         _ptr(logits, torch.float32, "logits"), _ptr(kcount, torch.uint8, "kcount"), int(fixed_k),
         _ptr(mask_in, _U16, "mask_in"), _ptr(K, torch.bfloat16, "K"),
         _ptr(bounds, torch.bfloat16, "bounds"), _ptr(mask, _U16, "mask"),
@@ -335,8 +336,8 @@ def stc_compact_tokens(src, token_idx, dst, B, Hkv, N_src, n_keep, D, dev_status
 class RoutedCache:
     """Device buffers of one layer's compressed cache plus per-step outputs.
 
-    Allocation (through torch) and nothing else: every computation is one of the
-    stc_* calls above.
+    Allocation (through torch, all of it in the constructor, sized for the token capacity) and
+    nothing else: every computation is one of the stc_* calls above.
     """
 
     def __init__(self, B, Hq, Hkv, D, N, G, k_pages, v_cap_groups=None, device="cuda:0",
@@ -347,26 +348,22 @@ class RoutedCache:
         self.B, self.Hq, self.Hkv, self.D, self.N, self.G = B, Hq, Hkv, D, N, G
         self.n_cap = n_cap
         self.keep_scores = keep_scores
-        self.NP = (N + 15) // 16
         self.k_pages = k_pages
-        self.k_eff = min(k_pages, self.NP)
         cap = (n_cap or N) * G if v_cap_groups is None else v_cap_groups
         self.shape = make_shape(B, Hq, Hkv, D, N, G, cap, N_cap=n_cap)
         dev = self.device
-        N = n_cap or N                      # strides of mask and tok_off
+        Nc = n_cap or N                     # strides of mask and tok_off; most tokens ever held
+        NPc = (Nc + 15) // 16
+        k_max = min(k_pages, NPc)
+        tail_pages = (tail_cap + 15) // 16
         self.bounds = torch.empty(stc_bounds_bytes(self.shape) // 2, dtype=torch.bfloat16,
                                   device=dev)
-        self.mask = torch.empty(B, Hkv, N, dtype=torch.int16, device=dev)
-        self.tok_off = torch.empty(B, Hkv, N + 1, dtype=torch.int32, device=dev)
+        self.mask = torch.empty(B, Hkv, Nc, dtype=torch.int16, device=dev)
+        self.tok_off = torch.empty(B, Hkv, Nc + 1, dtype=torch.int32, device=dev)
         self.vpacked = torch.empty(B, Hkv, cap, D // G, dtype=torch.bfloat16, device=dev)
         self.dev_status = torch.zeros(1, dtype=torch.int32, device=dev)
-        self.page_idx = torch.empty(B, Hkv, self.k_eff, dtype=torch.int32, device=dev)
-        if k_pages >= self.NP:      # every page is kept: the list never changes
-            self.page_idx.copy_(torch.arange(self.NP, dtype=torch.int32, device=dev))
+        self._page_idx_buf = torch.empty(B * Hkv * k_max, dtype=torch.int32, device=dev)
         self.out = torch.empty(B, Hq, D, dtype=torch.float32, device=dev)
-        self._ws_route = self._ws(STC_WS_ROUTE, 0)
-        self._ws_select = self._ws(STC_WS_SELECT, k_pages)
-        self._ws_attn = self._ws(STC_WS_ATTENTION, self.k_eff)
         self.K = (torch.empty(B, Hkv, n_cap, D, dtype=torch.bfloat16, device=dev)
                   if n_cap else None)
         # uncompressed tail of recent tokens (tail_cap = 0: none)
@@ -374,27 +371,40 @@ class RoutedCache:
         if tail_cap:
             self.K_tail = torch.empty(B, Hkv, tail_cap, D, dtype=torch.bfloat16, device=dev)
             self.V_tail = torch.empty_like(self.K_tail)
-            self._ws_attn = self._ws(STC_WS_ATTENTION_TAIL, self.k_eff + (tail_cap + 15) // 16)
-        self._alloc_step()
+        # workspaces for the largest shape the cache can reach (sizes grow with N and k)
+        big = make_shape(B, Hq, Hkv, D, Nc, G, cap, N_cap=n_cap)
 
-    def _alloc_step(self):
-        """Workspace of stc_decode_step.  The page scores are at its front: page_score is a view
-        of them, so that both forms of step() leave the scores there."""
+        def ws(which, k):
+            return torch.empty(max(stc_workspace_bytes(big, which, k), 16), dtype=torch.uint8,
+                               device=dev)
+        self._ws_route = ws(STC_WS_ROUTE, 0)
+        self._ws_select = ws(STC_WS_SELECT, 1)
+        self._ws_attn = ws(STC_WS_ATTENTION_TAIL if tail_cap else STC_WS_ATTENTION,
+                           k_max + tail_pages)
+        self._ws_step = ws(STC_WS_STEP_TAIL, k_max + tail_pages)
+        self._scores_all = (torch.empty(B * Hkv * NPc, dtype=torch.float32, device=dev)
+                            if keep_scores else None)    # scores when every page is kept
+        self._resize()
+
+    def _resize(self):
+        """Views for the current token count (no allocation): page list, page scores."""
+        self.NP = (self.N + 15) // 16
+        self.k_eff = min(self.k_pages, self.NP)
+        B, Hkv = self.B, self.Hkv
+        self.page_idx = self._page_idx_buf[:B * Hkv * self.k_eff].view(B, Hkv, self.k_eff)
+        if self.k_pages >= self.NP:      # every page is kept: the list is 0 .. NP-1
+            stc_select_pages(self.shape, None, None, self.k_pages, self.page_idx, None, None)
         self._step_cache = None
-        if self.tail_cap:
-            self._ws_step = self._ws(STC_WS_STEP_TAIL, self.k_eff + (self.tail_cap + 15) // 16)
-        else:
-            self._ws_step = self._ws(STC_WS_STEP, self.k_eff)
+        # the page scores sit at the front of the workspace of stc_decode_step: page_score is a
+        # view of them, so that both forms of step() leave the scores there
         self.page_score = None
         if self.keep_scores:
-            n = self.B * self.Hkv * self.NP
-            src = (self._ws_step if self.k_pages < self.NP or self.tail_cap else
-                   torch.empty(4 * n, dtype=torch.uint8, device=self.device))
-            self.page_score = src[:4 * n].view(torch.float32).view(self.B, self.Hkv, self.NP)
-
-    def _ws(self, which, k):
-        n = stc_workspace_bytes(self.shape, which, k)
-        return torch.empty(max(n, 16), dtype=torch.uint8, device=self.device)
+            n = B * Hkv * self.NP
+            if self.k_pages < self.NP or self.tail_cap:
+                src = self._ws_step[:4 * n].view(torch.float32)
+            else:
+                src = self._scores_all[:n]
+            self.page_score = src.view(B, Hkv, self.NP)
 
     def build(self, K, V, logits=None, kcount=None, fixed_k=0, mask_in=None, global_k=None):
         """Cache construction: page bounds of K, routing mask + packed store of V.  The mask
@@ -430,28 +440,16 @@ class RoutedCache:
 
     def flush(self, n, logits=None, kcount=None, fixed_k=0, mask_in=None):
         """Move the oldest n tail tokens into the compressed cache (routing them by mask_in,
-        or by the top kcount[t] / fixed_k of logits) and shift the rest of the tail down."""
+        or by the top kcount[t] / fixed_k of logits); the call moves the rest of the tail to
+        its front."""
         mode = STC_ROUTE_MASK if mask_in is not None else STC_ROUTE_TOPK
-        stc_flush_tail(self.shape, self.K_tail, self.V_tail, n, self.tail_cap, mode, logits, kcount,
-                       fixed_k, mask_in, self.K, self.bounds, self.mask, self.tok_off,
-                       self.vpacked, self.dev_status)
-        rest = self.n_tail - n
-        if rest:
-            self.K_tail[:, :, :rest] = self.K_tail[:, :, n:self.n_tail].clone()
-            self.V_tail[:, :, :rest] = self.V_tail[:, :, n:self.n_tail].clone()
-        self.n_tail = rest
+        stc_flush_tail(self.shape, self.K_tail, self.V_tail, n, self.n_tail, self.tail_cap, mode,
+                       logits, kcount, fixed_k, mask_in, self.K, self.bounds, self.mask,
+                       self.tok_off, self.vpacked, self.dev_status)
+        self.n_tail -= n
         self.N += n
         self.shape.N = self.N
-        self.NP = (self.N + 15) // 16
-        self.k_eff = min(self.k_pages, self.NP)
-        dev = self.device
-        self.page_idx = torch.empty(self.B, self.Hkv, self.k_eff, dtype=torch.int32, device=dev)
-        if self.k_pages >= self.NP:
-            self.page_idx.copy_(torch.arange(self.NP, dtype=torch.int32, device=dev))
-        self._ws_select = self._ws(STC_WS_SELECT, self.k_pages)
-        self._ws_attn = self._ws(STC_WS_ATTENTION_TAIL,
-                                 self.k_eff + (self.tail_cap + 15) // 16)
-        self._alloc_step()
+        self._resize()
 
     def attend(self, q):
         page_idx = self.page_idx if self.k_pages < self.NP else None

@@ -42,12 +42,11 @@ def build_library(verbose=False):
     """Compile every source and link libstc.so; always recompiles."""
     os.makedirs(BUILD_DIR, exist_ok=True)
     hipcc = _hipcc()
-    extra = os.environ.get("STC_HIPCC_EXTRA", "").split()   # e.g. -DSTC_TUNE for tuning builds
     objs = [os.path.join(BUILD_DIR, s.replace(".hip", ".o")) for s in SOURCES]
 
     def one(pair):
         src, obj = pair
-        out = _run([hipcc, *HIPCC_FLAGS, *FILE_FLAGS.get(src, []), *extra, "-c",
+        out = _run([hipcc, *HIPCC_FLAGS, *FILE_FLAGS.get(src, []), "-c",
                     os.path.join(CSRC, src), "-o", obj])
         if verbose and out.strip():
             print(out)

@@ -13,8 +13,6 @@
 // registers.  Each weight is split into two bf16 parts (p = hi + lo) so the
 // product with V carries ~2^-17 relative error instead of bf16's 2^-9.
 // Both K and the routed (zero-filled) V of a page pass through a dense LDS tile.
-#include <stdlib.h>
-
 #include "stc_common.hpp"
 #include "stc_kernels.hpp"
 #include "topk_block.hpp"
@@ -72,20 +70,6 @@ struct AttnCfg {
 // 16 zero bytes in device memory: where lanes beyond the end of a packed run read
 __device__ u32x4 stc_zero16 = {0u, 0u, 0u, 0u};  // never written
 
-#ifdef STC_TUNE
-// tuning builds only: per-workgroup phase timestamps (100 MHz counter) of wave 0
-__device__ long long* stc_dbg_ptr = nullptr;
-#define STC_MARK(slot, dep)                                                                  \
-  do {                                                                                       \
-    if (dbg && wave == 0) {                                                                  \
-      unsigned long long t_;                                                                 \
-      asm volatile("s_memrealtime %0\n s_waitcnt lgkmcnt(0)" : "=s"(t_) : "v"(dep) : "memory"); \
-      if (lane == 0) dbg[(blockIdx.y * gridDim.x + blockIdx.x) * 16 + (slot)] = (long long)t_; \
-    }                                                                                        \
-  } while (0)
-#else
-#define STC_MARK(slot, dep) do {} while (0)
-#endif
 
 // One wavefront walks 2*PAIRS page slots of one stream, two at a time (PAIRS = 1 in regular
 // builds); the WAVES wavefronts of a workgroup then merge their partial results in LDS.
@@ -138,10 +122,6 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
   const float scale = kLog2e / sqrtf((float)D);
 
   unsigned char* wl = lds + wave * C::WAVE_LDS;
-#ifdef STC_TUNE
-  long long* dbg = stc_dbg_ptr;
-#endif
-  STC_MARK(0, lane);
   if (lane < 4) *(uint32_t*)(wl + C::ZERO + lane * 4) = 0;
 
   // per-stream bases (wave-uniform); everything below is addressed with 32-bit byte offsets.
@@ -290,15 +270,12 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
   for (int cb = 0; cb < C::CB; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
   float m_run = kNegBig, l_part = 0.f;
 
-  STC_MARK(1, my_pg);
   // The scheduling fences keep the request order stated above.
 #pragma unroll
   for (int it = 0; it < PAIRS; ++it) issue_meta(it);
   __builtin_amdgcn_sched_barrier(0);
-  STC_MARK(12, lane);
   issue_k(0);
   __builtin_amdgcn_sched_barrier(0);
-  STC_MARK(13, lane);
 
   // B operand of the QK product: this lane's 8 channels of head r16 for every 32-channel step
   u32x4 qreg[C::KC];
@@ -310,7 +287,6 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
       qreg[j] = *(const u32x4*)(qs + (qo + 64 * j));  // columns >= R repeat head 0, never used
   }
   __builtin_amdgcn_sched_barrier(0);
-  STC_MARK(7, lane);
 
   // logits of a pair, online softmax; leaves the weights of the pair in phi/plo
   u32x4 phi, plo;
@@ -425,7 +401,6 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
   }
 
   if (npairs > 0) {
-    STC_MARK(2, mk[0] ^ off[0] ^ run1[0][0] ^ run1[0][1]);
     // The value requests of a pair are held back until its masks/offsets have arrived:
     // a wavefront then has one pair of K pages or one pair of V runs plus the next K
     // pages outstanding, which keeps the chip-wide volume of outstanding requests near
@@ -444,21 +419,13 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
       STC_ISSUE_V(1, vregB);
       __builtin_amdgcn_sched_barrier(0);
     }
-    STC_MARK(3, kreg[0][0][0].x ^ kreg[0][1][C::NLD - 1].w);
     qk_softmax(0);
     __builtin_amdgcn_sched_barrier(0);
-    STC_MARK(4, phi.x ^ plo.w);
-    STC_MARK(5, vregA[0][0].x ^ vregA[1][C::NLD - 1].w);
     STC_PV(0, vregA);
-    STC_MARK(6, acc[0][0]);
     if constexpr (PAIRS > 1) {
       if (npairs > 1) {
-        STC_MARK(8, kreg[1][0][0].x ^ kreg[1][1][C::NLD - 1].w);
         qk_softmax(1);
-        STC_MARK(9, phi.x ^ plo.w);
-        STC_MARK(10, vregB[0][0].x ^ vregB[1][C::NLD - 1].w);
         STC_PV(1, vregB);
-        STC_MARK(11, acc[0][0]);
       }
     }
   }
@@ -484,7 +451,6 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
     mml[r16 * 2 + 1] = l;
   }
   __syncthreads();
-  STC_MARK(14, lane);
   for (int i = threadIdx.x; i < R * D; i += 64 * WAVES) {
     const int head = i / D, c = i % D;
     float mw[WAVES], m = kNegBig;
@@ -562,16 +528,6 @@ struct AttnPlan {
 static AttnPlan attention_plan(const stc_shape_t& s, int k_pages) {
   const int streams = s.B * s.Hkv;
   AttnPlan p{8, 2, 0};
-#ifdef STC_TUNE
-  const char* ew = getenv("STC_ATTN_WAVES");
-  const char* ep = getenv("STC_ATTN_PPW");
-  if (ew || ep) {
-    p.waves = ew && atoi(ew) >= 8 ? 8 : 4;
-    p.ppw = ep && atoi(ep) >= 4 ? 4 : 2;
-    p.splits = (k_pages + p.waves * p.ppw - 1) / (p.waves * p.ppw);
-    return p;
-  }
-#endif
   if (k_pages <= 8 || (long long)streams * ((k_pages + 15) / 16) < 256) p.waves = 4;
   p.splits = (k_pages + p.waves * p.ppw - 1) / (p.waves * p.ppw);
   return p;
@@ -587,9 +543,12 @@ static stc_shape_t launch_shape(const stc_shape_t& s, bool per_head) {
   return t;
 }
 
+// Room for the split partials of any launch over at most k_pages page slots: the plan with
+// the most workgroups per stream (4 wavefronts of 2 pages each), so that the size never
+// shrinks when k_pages grows and a buffer sized for the largest count serves every smaller one.
 size_t attention_ws_bytes(const stc_shape_t& s0, int k_pages, bool per_head) {
   const stc_shape_t s = launch_shape(s0, per_head);
-  const int splits = attention_splits(s, k_pages);
+  const int splits = (k_pages + 7) / 8;
   if (splits <= 1) return 0;
   return (size_t)s.B * s.Hq * splits * partial_stride(s.D) * sizeof(float);
 }
@@ -638,13 +597,6 @@ int attn_dispatch(const AttnArgs& a, const AttnPlan& plan, bool tail, bool selec
       return tail ? attn_go<D, 1, 8, true, 4>(a) : attn_go<D, 1, 8, false, 4>(a);
     return tail ? attn_go<D, 1, 4, true, 8>(a) : attn_go<D, 1, 4, false, 8>(a);
   }
-#ifdef STC_TUNE
-  if (plan.ppw == 4) {
-    if (plan.waves == 8)
-      return tail ? attn_go<D, 2, 8, true, 0>(a) : attn_go<D, 2, 8, false, 0>(a);
-    return tail ? attn_go<D, 2, 4, true, 0>(a) : attn_go<D, 2, 4, false, 0>(a);
-  }
-#endif
   if (plan.waves == 8) return tail ? attn_go<D, 1, 8, true, 0>(a) : attn_go<D, 1, 8, false, 0>(a);
   return tail ? attn_go<D, 1, 4, true, 0>(a) : attn_go<D, 1, 4, false, 0>(a);
 }
@@ -678,17 +630,6 @@ int launch_attention(const stc_shape_t& s0, const void* q, const void* K, const 
              tail_cap, per_head ? s0.Hq / s0.Hkv : 1, page_heads, token_cap(s), sel_score,
              sel_list, dim3(plan.splits, streams), st};
   if (sel_score && (NP > 2048 || per_head || page_heads)) return -1;
-#ifdef STC_TUNE
-  {
-    long long* p = nullptr;
-    if (const char* e = getenv("STC_DBG_PTR")) p = (long long*)strtoull(e, nullptr, 0);
-    static long long* last = (long long*)-1;
-    if (p != last) {
-      (void)hipMemcpyToSymbol(HIP_SYMBOL(stc_dbg_ptr), &p, sizeof(p));
-      last = p;
-    }
-  }
-#endif
   const int rc = s.D == 128 ? attn_dispatch<128>(a, plan, tail_pages > 0, sel_score != nullptr)
                             : attn_dispatch<64>(a, plan, tail_pages > 0, sel_score != nullptr);
   if (rc) return -1;

@@ -56,7 +56,7 @@ __device__ __forceinline__ uint32_t rank_mask(const float* __restrict__ lp, int 
 // `row` points at the 16-byte piece of the first row); w[i] = min | max << 16 as bf16 bits,
 // -0 ordered below +0.  ntok <= 0 gives zeros.
 template <int D>
-__device__ __forceinline__ void page_bounds_words(const uint4* __restrict__ row, int ntok,
+__device__ __forceinline__ void page_bounds_words(const uint4* row, int ntok,
                                                   uint32_t (&w)[8]) {
   constexpr int LPP = D / 8;
   int mn[8], mx[8];

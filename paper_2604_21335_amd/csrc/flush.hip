@@ -4,6 +4,7 @@
 // store, the offsets are continued from tok_off[N], and the bounds of every page that holds
 // one of them are recomputed (the first such page may already hold older tokens).  The
 // result is, bit for bit, the cache that construction from scratch over all N+n tokens gives.
+// The rows that stay in the tail are then moved to its front.
 #include "build_helpers.hpp"
 #include "stc_common.hpp"
 #include "stc_kernels.hpp"
@@ -13,9 +14,9 @@ namespace stc {
 // One 256-thread workgroup per stream (cache construction, not the decode path).
 template <int D>
 __global__ __launch_bounds__(256) void flush_tail_kernel(
-    const uint4* __restrict__ K_tail, const uint4* __restrict__ V_tail, int n, int tail_cap,
+    uint4* K_tail, uint4* V_tail, int n, int n_tail, int tail_cap,
     int mode, const float* __restrict__ logits, const uint8_t* __restrict__ kcount, int fixed_k,
-    const uint16_t* __restrict__ mask_in, uint4* __restrict__ K, uint4* __restrict__ bounds,
+    const uint16_t* __restrict__ mask_in, uint4* K, uint4* __restrict__ bounds,
     uint16_t* __restrict__ mask, uint32_t* __restrict__ tok_off, uint4* __restrict__ vpacked,
     int32_t* dev_status, int N, int Ncap, int G, long long cap) {
   constexpr int PPT = D / 8;  // 16-byte pieces per token row
@@ -26,8 +27,8 @@ __global__ __launch_bounds__(256) void flush_tail_kernel(
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   uint4* Ks = K + (size_t)stream * Ncap * PPT;
-  const uint4* Kt = K_tail + (size_t)stream * tail_cap * PPT;
-  const uint4* Vt = V_tail + (size_t)stream * tail_cap * PPT;
+  uint4* Kt = K_tail + (size_t)stream * tail_cap * PPT;
+  uint4* Vt = V_tail + (size_t)stream * tail_cap * PPT;
   uint16_t* mk = mask + (size_t)stream * Ncap;
   uint32_t* off = tok_off + (size_t)stream * (Ncap + 1);
   const int ppg = PPT / G;  // 16-byte pieces per group
@@ -101,16 +102,38 @@ __global__ __launch_bounds__(256) void flush_tail_kernel(
     const uint32_t zeros[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     store_bounds_units<D>(tiles, pad0 + w / PPT, w % PPT, zeros);
   }
+
+  // The rows that stay in the tail (n .. n_tail-1) move to its front, 16 bytes per work item.
+  // Source and destination overlap, so the rows go in ascending chunks, each read completely
+  // before any of it is written: a chunk's destination holds sources of this and of earlier
+  // chunks only (the rows moved into the cache above have been read: barrier above).
+  constexpr int U = 4;
+  const int total = (n_tail - n) * PPT, shift = n * PPT;
+  for (int base = 0; base < total; base += 256 * U) {
+    uint4 kv[U], vv[U];
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+      const int e = base + j * 256 + tid;
+      if (e < total) kv[j] = Kt[e + shift], vv[j] = Vt[e + shift];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+      const int e = base + j * 256 + tid;
+      if (e < total) Kt[e] = kv[j], Vt[e] = vv[j];
+    }
+    __syncthreads();
+  }
 }
 
-int launch_flush_tail(const stc_shape_t& s, const void* K_tail, const void* V_tail, int n,
+int launch_flush_tail(const stc_shape_t& s, void* K_tail, void* V_tail, int n, int n_tail,
                       int tail_cap, int mode, const float* logits, const uint8_t* kcount,
                       int fixed_k, const uint16_t* mask_in, void* K, void* bounds, uint16_t* mask,
                       uint32_t* tok_off, void* vpacked, int32_t* dev_status, hipStream_t st) {
   const int streams = s.B * s.Hkv;
 #define STC_FLUSH(DD)                                                                           \
   flush_tail_kernel<DD><<<streams, 256, 0, st>>>(                                               \
-      (const uint4*)K_tail, (const uint4*)V_tail, n, tail_cap, mode, logits, kcount, fixed_k,   \
+      (uint4*)K_tail, (uint4*)V_tail, n, n_tail, tail_cap, mode, logits, kcount, fixed_k,   \
       mask_in, (uint4*)K, (uint4*)bounds, mask, tok_off, (uint4*)vpacked, dev_status, s.N,      \
       token_cap(s), s.G, (long long)s.v_cap_groups)
   if (s.D == 128)

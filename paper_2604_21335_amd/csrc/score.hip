@@ -155,6 +155,12 @@ void score_mfma_kernel(const u32x4* __restrict__ tiles, const uint16_t* __restri
   }
 }
 
+// A bf16 value widened to float, with subnormal inputs read as zero (what the matrix cores do
+// with the operands of the kernel above).
+__device__ __forceinline__ float daz(float x) {
+  return (__float_as_uint(x) & 0x7f800000u) ? x : 0.f;
+}
+
 // Any number of query heads per KV head (up to 16), one head at a time on the VALU: the
 // same tiles, the same lane assignment and the same order of additions.
 template <int D>
@@ -187,8 +193,8 @@ __global__ __launch_bounds__(256) void score_any_kernel(const u32x4* __restrict_
       float v[CH];
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
-        const float qc = __uint_as_float((uint32_t)qp[c] << 16);
-        v[c] = fmaxf(qc * bf16_lo(w[c]), qc * bf16_hi(w[c]));
+        const float qc = daz(__uint_as_float((uint32_t)qp[c] << 16));
+        v[c] = fmaxf(qc * daz(bf16_lo(w[c])), qc * daz(bf16_hi(w[c])));
       }
 #pragma unroll
       for (int s = 1; s < CH; s *= 2)

@@ -345,13 +345,13 @@ int stc_decode_step_static(const stc_shape_t* shape, const void* q, const void* 
                           0, 0, page_idx, out, ws, STC_STATIC_SCRATCH_BYTES, score_bytes, stream);
 }
 
-int stc_flush_tail(const stc_shape_t* shape, const void* K_tail, const void* V_tail, int n_flush,
+int stc_flush_tail(const stc_shape_t* shape, void* K_tail, void* V_tail, int n_flush, int n_tail,
                    int tail_cap, int mode, const float* logits, const uint8_t* kcount, int fixed_k,
                    const uint16_t* mask_in, void* K, void* bounds, uint16_t* mask,
                    uint32_t* tok_off, void* vpacked, int32_t* dev_status, void* stream) {
   if (!shape || !K_tail || !V_tail || !K || !bounds || !mask || !tok_off || !vpacked)
     return STC_ERR_NULL;
-  if (!shape_ok(shape) || n_flush < 1 || n_flush > tail_cap ||
+  if (!shape_ok(shape) || n_flush < 1 || n_flush > n_tail || n_tail > tail_cap ||
       (long long)shape->N + n_flush > stc::token_cap(*shape))
     return STC_ERR_SHAPE;
   if (mode == STC_ROUTE_TOPK) {
@@ -366,7 +366,7 @@ int stc_flush_tail(const stc_shape_t* shape, const void* K_tail, const void* V_t
       !aligned16(mask) || !aligned16(tok_off) || !aligned16(vpacked) ||
       (logits && !aligned16(logits)) || (mask_in && !aligned16(mask_in)))
     return STC_ERR_ALIGN;
-  return stc::launch_flush_tail(*shape, K_tail, V_tail, n_flush, tail_cap, mode, logits, kcount,
+  return stc::launch_flush_tail(*shape, K_tail, V_tail, n_flush, n_tail, tail_cap, mode, logits, kcount,
                                 fixed_k, mask_in, K, bounds, mask, tok_off, vpacked, dev_status,
                                 (hipStream_t)stream)
              ? STC_ERR_LAUNCH

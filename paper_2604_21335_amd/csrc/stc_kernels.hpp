@@ -67,7 +67,7 @@ bool attention_can_select(const stc_shape_t& s, int k_pages, int tail_pages);
 // the heads that selected each page.
 int launch_union_pages(const stc_shape_t& s, const int32_t* page_idx_per_head, int k_pages,
                        int32_t* union_idx, uint16_t* union_heads, int U, hipStream_t st);
-int launch_flush_tail(const stc_shape_t& s, const void* K_tail, const void* V_tail, int n,
+int launch_flush_tail(const stc_shape_t& s, void* K_tail, void* V_tail, int n, int n_tail,
                       int tail_cap, int mode, const float* logits, const uint8_t* kcount,
                       int fixed_k, const uint16_t* mask_in, void* K, void* bounds, uint16_t* mask,
                       uint32_t* tok_off, void* vpacked, int32_t* dev_status, hipStream_t st);

@@ -146,12 +146,14 @@ def test_null_alignment_and_workspace_errors():
     # flush of tail tokens into the cache: needs room (N_cap) and a routing input
     sc = _shape(N_cap=140)
     rc = ctypes.byref(sc)
-    fl = lambda shp, n, mode, logits, mask_in, K=FAKE: lib.stc_flush_tail(  # noqa: E731
-        shp, FAKE, FAKE, n, 64, mode, logits, None, 2, mask_in, K, FAKE, FAKE, FAKE, FAKE, None,
-        None)
+    fl = lambda shp, n, mode, logits, mask_in, K=FAKE, n_tail=64: lib.stc_flush_tail(  # noqa: E731
+        shp, FAKE, FAKE, n, n_tail, 64, mode, logits, None, 2, mask_in, K, FAKE, FAKE, FAKE, FAKE,
+        None, None)
     assert fl(r, 8, stc.STC_ROUTE_TOPK, FAKE, None) == stc.STC_ERR_SHAPE        # no capacity
     assert fl(rc, 41, stc.STC_ROUTE_TOPK, FAKE, None) == stc.STC_ERR_SHAPE      # 100 + 41 > 140
     assert fl(rc, 0, stc.STC_ROUTE_TOPK, FAKE, None) == stc.STC_ERR_SHAPE
+    assert fl(rc, 8, stc.STC_ROUTE_TOPK, FAKE, None, n_tail=7) == stc.STC_ERR_SHAPE   # more than the tail holds
+    assert fl(rc, 8, stc.STC_ROUTE_TOPK, FAKE, None, n_tail=65) == stc.STC_ERR_SHAPE  # beyond tail_cap
     assert fl(rc, 8, stc.STC_ROUTE_GLOBAL, FAKE, None) == stc.STC_ERR_SHAPE
     assert fl(rc, 8, stc.STC_ROUTE_TOPK, None, None) == stc.STC_ERR_NULL
     assert fl(rc, 8, stc.STC_ROUTE_MASK, None, None) == stc.STC_ERR_NULL
@@ -267,3 +269,24 @@ def test_header_is_plain_c_and_links(tmp_path):
                     "-L", libdir, "-lstc", "-Wl,-rpath," + libdir], check=True)
     out = subprocess.run([exe], capture_output=True, text=True)
     assert out.returncode == 0, out.stdout + out.stderr
+
+
+@pytest.mark.parametrize("which", ["STC_WS_ATTENTION", "STC_WS_ATTENTION_TAIL", "STC_WS_STEP_TAIL",
+                                   "STC_WS_ATTENTION_PER_HEAD"])
+@pytest.mark.parametrize("B,Hq,Hkv", [(8, 28, 4), (1, 8, 8), (16, 28, 4), (2, 32, 32)])
+def test_attention_workspace_never_shrinks_when_the_page_count_grows(which, B, Hq, Hkv):
+    """A buffer sized for the largest number of page slots (selected pages plus tail pages)
+    must serve every smaller number: the launch plan changes with the count, the size bound
+    may not."""
+    s = stc.make_shape(B=B, Hq=Hq, Hkv=Hkv, D=128, N=16 * 400, G=8, v_cap_groups=16 * 400 * 8)
+    sizes = [stc.stc_workspace_bytes(s, getattr(stc, which), k) for k in range(1, 401)]
+    assert all(b >= a for a, b in zip(sizes, sizes[1:])), which
+    assert sizes[-1] > 0
+
+
+def test_static_scratch_limit_is_checked_on_the_host():
+    s = stc.make_shape(B=256, Hq=32, Hkv=32, D=128, N=4096, G=8, v_cap_groups=4096 * 8)
+    assert stc.stc_workspace_bytes(s, stc.STC_WS_STEP, 128) > stc.STC_STATIC_SCRATCH_BYTES
+    rc = stc.load_library().stc_decode_step_static(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE,
+                                                   FAKE, 128, FAKE, FAKE, None)
+    assert rc == stc.STC_ERR_WORKSPACE

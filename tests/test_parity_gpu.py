@@ -506,6 +506,63 @@ def test_router_logits_bits_and_routing(B, Hkv, N, dm, G, with_bias):
                 assert np.array_equal(hip["mask"][b, kvh], m)
 
 
+def _plant_subnormals(rng, bits, frac=0.12):
+    """bf16 bit patterns with a share of entries replaced by subnormal patterns of either sign."""
+    out = bits.copy()
+    hit = rng.random(bits.shape) < frac
+    mant = rng.integers(1, 128, size=bits.shape).astype(np.uint16)
+    sign = rng.integers(0, 2, size=bits.shape).astype(np.uint16) << np.uint16(15)
+    out[hit] = (sign | mant)[hit]
+    return out
+
+
+@pytest.mark.parametrize("R,D,scale", [(7, 128, 1.0), (4, 64, 1.0), (9, 128, 1.0), (7, 128, 2.0 ** 90),
+                                       (2, 128, 2.0 ** -70)])
+def test_subnormal_inputs_count_as_zero_in_page_scores(R, D, scale):
+    """Keys and queries that are subnormal as bf16 are zeros for the page scores (bounds keep
+    their bit patterns): matrix-core kernel and the one-head-at-a-time kernel against the
+    oracle, bit for bit.  With large queries the products of subnormal inputs would be ordinary
+    floats, so a kernel that multiplied them would differ in many bits; with tiny queries the
+    products of normal inputs lie in the subnormal float range and must come out exact."""
+    rng = np.random.default_rng(400 + R + D)
+    B, Hkv, N, G = 2, 2, 16 * 37 + 5, 8
+    Hq = Hkv * R
+    K = _plant_subnormals(rng, randn_bf16(rng, (B, Hkv, N, D), 1.0 if scale >= 1 else scale))
+    q = _plant_subnormals(rng, randn_bf16(rng, (B, Hq, D), scale))
+    V = randn_bf16(rng, (B, Hkv, N, D))
+    dev = "cuda:0"
+    c = stc.RoutedCache(B, Hq, Hkv, D, N, G, 5, device=dev)
+    c.build(PT.to_dev_bf16(K), PT.to_dev_bf16(V), mask_in=PT.to_dev_u16(
+        np.full((B, Hkv, N), 0xFF, dtype=np.uint16)))
+    sc = torch.full((B, Hkv, c.NP), float("nan"), dtype=torch.float32, device=dev)
+    c.score(PT.to_dev_bf16(q), sc)
+    c.select(PT.to_dev_bf16(q))
+    torch.cuda.synchronize()
+    got, rows, idx = sc.cpu().numpy(), PT.host_bf16(c.bounds_rows()), c.page_idx.cpu().numpy()
+    for b in range(B):
+        for h in range(Hkv):
+            bounds = O.page_bounds(K[b, h])
+            assert np.array_equal(rows[b, h], bounds)          # subnormal patterns survive
+            want = O.page_scores(q[b, h * R:(h + 1) * R], bounds)
+            assert np.array_equal(got[b, h].view(np.uint32), want.view(np.uint32)), (b, h)
+            assert np.array_equal(idx[b, h], O.select_pages(want, 5))
+
+
+def test_subnormal_inputs_count_as_zero_in_router_logits():
+    rng = np.random.default_rng(410)
+    B, Hkv, N, dm, G = 2, 2, 300, 512, 8
+    h = _plant_subnormals(rng, randn_bf16(rng, (B, N, dm), 2.0 ** 80))
+    Wr = _plant_subnormals(rng, randn_bf16(rng, (G, dm)))
+    dev = "cuda:0"
+    logits = torch.full((B, Hkv, N, G), float("nan"), dtype=torch.float32, device=dev)
+    stc.stc_router_logits(PT.to_dev_bf16(h), PT.to_dev_bf16(Wr), None, logits, Hkv)
+    torch.cuda.synchronize()
+    got = logits.cpu().numpy()
+    for b in range(B):
+        want = O.router_logits(h[b], Wr, None)
+        assert np.array_equal(got[b, 1].view(np.uint32), want.view(np.uint32))
+
+
 def _cache_equals_full_build(c, K_all, V_all, logits_all, kcount_all, G):
     """Every array of cache `c` (N tokens so far, capacity strides) against construction from
     scratch over the same N tokens by the oracle."""
@@ -754,6 +811,67 @@ def test_workload_full_size_sampled_streams(name):
     streams = sorted({(0, 0), (w.B - 1, w.Hkv - 1), (w.B // 2, w.Hkv // 3)})
     worst = _check_streams(w, c, t, streams)
     assert worst <= PT.TIGHT
+
+
+@pytest.mark.parametrize("name", ["llama2_7b_4k", "qwen25_7b_32k"])
+def test_workload_full_size_every_stream_selection(name):
+    """Full size, the benchmark's launch configuration: page bounds, page-score bits and the
+    selected page list of EVERY stream against the oracle; the attention output on 8 streams
+    spread over the batch (the oracle's attention is the slow part)."""
+    w = W.WORKLOADS[name]
+    c, t = _run_workload(w)
+    assert int(c.dev_status.item()) == 0
+    q = W.bf16_bits(t["q"])
+    rows = c.bounds_rows()
+    got_idx = c.page_idx.cpu().numpy()
+    got_score = c.page_score.cpu().numpy().view(np.uint32)
+    R = w.R
+    for b in range(w.B):
+        Kb, rb = W.bf16_bits(t["K"][b]), W.bf16_bits(rows[b])
+        for h in range(w.Hkv):
+            bounds = O.page_bounds(Kb[h])
+            assert np.array_equal(rb[h], bounds), (b, h)
+            score = O.page_scores(q[b, h * R:(h + 1) * R], bounds)
+            assert np.array_equal(got_score[b, h], score.view(np.uint32)), (b, h)
+            assert np.array_equal(got_idx[b, h], O.select_pages(score, w.k_pages)), (b, h)
+    streams = sorted({(i * w.B // 8, (3 * i) % w.Hkv) for i in range(8)})
+    assert len(streams) == 8
+    worst = _check_streams(w, c, t, streams)
+    assert worst <= PT.TIGHT
+
+
+@pytest.mark.parametrize("B,k_pages,tail_cap", [(8, 108, 128), (2, 60, 96)])
+def test_tail_decode_across_the_launch_plan_switch(B, k_pages, tail_cap):
+    """Buffers sized once for the full tail must serve every tail length: with few streams the
+    attention launch changes its plan (wavefronts per workgroup, hence splits) while the tail
+    grows.  The step is run at tail lengths on both sides of the switch, with one workspace."""
+    Hq, Hkv, D, G, N = 28, 4, 128, 8, 16 * 140
+    K, V, q, logits, kcount = _rand_case(300 + B, B, Hq, Hkv, D, N, G)
+    rng = np.random.default_rng(301)
+    Kt, Vt = randn_bf16(rng, (B, Hkv, tail_cap, D)), randn_bf16(rng, (B, Hkv, tail_cap, D))
+    dev = "cuda:0"
+    c = stc.RoutedCache(B, Hq, Hkv, D, N, G, k_pages, device=dev, tail_cap=tail_cap)
+    c.build(PT.to_dev_bf16(K), PT.to_dev_bf16(V), logits=torch.from_numpy(logits).to(dev),
+            kcount=torch.from_numpy(kcount).to(dev))
+    c.K_tail.copy_(PT.to_dev_bf16(Kt))
+    c.V_tail.copy_(PT.to_dev_bf16(Vt))
+    R = Hq // Hkv
+    for n_tail in (0, 1, 40, 64, 65, tail_cap):
+        c.n_tail = n_tail
+        for one_call in (True, False):
+            c.out.fill_(float("nan"))
+            c.step(PT.to_dev_bf16(q), one_call=one_call)
+            torch.cuda.synchronize()
+            got, idx = c.out.cpu().numpy(), c.page_idx.cpu().numpy()
+            for (b, h) in [(0, 0), (B - 1, Hkv - 1)]:
+                m = O.route_mask(logits[b, h], kcount[b, h])
+                qh = q[b, h * R:(h + 1) * R]
+                want_idx = O.select_pages(O.page_scores(qh, O.page_bounds(K[b, h])), k_pages)
+                assert np.array_equal(idx[b, h], want_idx)
+                want = O.decode_attention(qh, K[b, h], V[b, h], m, want_idx, G,
+                                          K_tail=Kt[b, h, :n_tail], V_tail=Vt[b, h, :n_tail])
+                err = np.abs(got[b, h * R:(h + 1) * R] - want).max()
+                assert err < PT.TIGHT, (n_tail, one_call, b, h, err)
 
 
 def test_global_budget_at_full_llm_size():
