@@ -38,12 +38,29 @@ METRIC = "decode-attention us/step + achieved HBM GB/s (% of peak), Qwen2.5-7B 3
 REPLICAS = {"tiny": 8, "llama2_7b_4k": 4, "qwen25_7b_32k": 6, "llava15_7b_prefix": 4,
             "qwen25_7b_128k": 1}
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs of this file
-# (FETCH_SIZE and WRITE_SIZE, scaled by what the same counters read for a copy of known
-# size); see profiles/.  None where it has not been measured.
-MEASURED_TRAFFIC = {("qwen25_7b_32k", "score_mfma_kernel"): 68624809,
-                    ("llama2_7b_4k", "attn_mfma_kernel"): 111302928,
-                    ("llava15_7b_prefix", "attn_mfma_kernel"): 175606606}
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes from the committed rocprofv3 --pmc summary of this workload
+    (profiles/<workload>_hbm_traffic.txt: FETCH_SIZE and WRITE_SIZE per dispatch, scaled by what
+    the same counters read for a copy of known size).  Nothing here is measured by this run:
+    the figures are read from the file, with the source revision the file names.  Returns
+    (bytes per launch of `kernel`, bytes per whole step, source) with None where absent."""
+    path = os.path.join(ROOT, "profiles", "%s_hbm_traffic.txt" % workload)
+    per_kernel = per_step = commit = None
+    try:
+        with open(path) as f:
+            for line in f:
+                t = line.split()
+                if line.startswith("commit:") and len(t) > 1:
+                    commit = t[1]
+                elif line.startswith("hbm_bytes_per_step:") and len(t) > 1:
+                    per_step = int(float(t[1]))
+                elif line.startswith("stc::" + kernel) and per_kernel is None:
+                    per_kernel = int(float(t[-1]))
+    except OSError:
+        return None, None, None
+    return per_kernel, per_step, "profiles/%s_hbm_traffic.txt @ %s" % (workload, commit)
 
 
 def algorithmic_bytes(w, mean_kept):
@@ -122,46 +139,139 @@ def per_step_times(fn, n, torch):
     return sorted(ev[i].elapsed_time(ev[i + 1]) * 1e3 for i in range(n))
 
 
-def cpu_baseline(W, w, dev, budget_s=12.0):
-    """The oracle, as it stands, on a bounded sample of streams of the same workload
-    (per-step part only: page scores, selection, attention).  Single-threaded numpy."""
+def _cpu_worker(args):
+    """One process of the CPU baseline: builds (untimed) the oracle's cache of the streams of
+    batch element 0, then runs the oracle's decode step (page scores, selection, attention)
+    on them in turn for budget_s seconds, on one thread.  Returns (stream-steps done, seconds,
+    digest of the first result of every stream)."""
+    name, budget_s = args
+    import hashlib
+
     import numpy as np
+    import torch
+    from threadpoolctl import threadpool_limits
 
     from oracle import stc_oracle as O
-    w1 = W.shrink(w, B=1)
-    inp = W.make_cache_inputs(w1, dev, layer=0)                    # batch element 0 only
-    q = W.bf16_bits(W.make_query(w1, 0, dev))
-    R = w.R
-    prepared = []
-    for h in range(min(w.Hkv, 4)):                                 # oracle-built cache (untimed)
-        K, V = W.bf16_bits(inp["K"][0, h]), W.bf16_bits(inp["V"][0, h])
-        if w.routing == "vlm":
-            ti = inp["token_idx"][0].cpu().numpy()
-            K, V = K[ti], V[ti]
-        if inp["mask_in"] is not None:
-            m = W.u16_numpy(inp["mask_in"][0, h]) & np.uint16((1 << w.G) - 1)
-        else:
-            m = O.route_mask(inp["logits"][0, h].cpu().numpy(), inp["kcount"][0, h].cpu().numpy())
-        prepared.append((K, V, m, O.page_bounds(K), q[0, h * R:(h + 1) * R]))
-    t0 = time.perf_counter()
-    done = 0
-    while True:
-        K, V, m, bounds, qh = prepared[done % len(prepared)]
-        if w.k_pages < w.NP:
-            idx = O.select_pages(O.page_scores(qh, bounds), w.k_pages)
-        else:
-            idx = np.arange(w.NP, dtype=np.int32)
-        O.decode_attention(qh, K, V, m, idx, w.G)
-        done += 1
-        el = time.perf_counter() - t0
-        if el > budget_s:
-            break
-    per_stream = el / done
-    return {"value": per_stream * w.streams * w.layers * 1e6, "unit": "us/step", "cores": 1,
-            "kind": "oracle",
-            "sample": "%d stream-steps of %s (oracle page scores + selection + attention on "
-                      "streams of batch element 0, %.1f s of CPU), scaled to the %d streams x %d "
-                      "layer(s) of a step" % (done, w.name, el, w.streams, w.layers)}
+    from paper_2604_21335_amd import workloads as W
+    torch.set_num_threads(1)
+    w = W.WORKLOADS[name]
+    with threadpool_limits(limits=1):
+        w1 = W.shrink(w, B=1)
+        inp = W.make_cache_inputs(w1, "cpu", layer=0)                  # batch element 0 only
+        q = W.bf16_bits(W.make_query(w1, 0, "cpu"))
+        R = w.R
+        prepared = []
+        for h in range(min(w.Hkv, 4)):                                 # oracle-built cache
+            K, V = W.bf16_bits(inp["K"][0, h]), W.bf16_bits(inp["V"][0, h])
+            if w.routing == "vlm":
+                ti = inp["token_idx"][0].numpy()
+                K, V = K[ti], V[ti]
+            if inp["mask_in"] is not None:
+                m = W.u16_numpy(inp["mask_in"][0, h]) & np.uint16((1 << w.G) - 1)
+            else:
+                m = O.route_mask(inp["logits"][0, h].numpy(), inp["kcount"][0, h].numpy())
+            prepared.append((K, V, m, O.page_bounds(K), q[0, h * R:(h + 1) * R]))
+        digest = hashlib.sha256()
+        t0 = time.perf_counter()
+        done = 0
+        while True:
+            K, V, m, bounds, qh = prepared[done % len(prepared)]
+            if w.k_pages < w.NP:
+                idx = O.select_pages(O.page_scores(qh, bounds), w.k_pages)
+            else:
+                idx = np.arange(w.NP, dtype=np.int32)
+            out = O.decode_attention(qh, K, V, m, idx, w.G)
+            if done < len(prepared):
+                digest.update(np.ascontiguousarray(idx).tobytes())
+                digest.update(np.ascontiguousarray(out).tobytes())
+            done += 1
+            el = time.perf_counter() - t0
+            if el > budget_s and done >= len(prepared):
+                break
+    return done, el, digest.hexdigest()
+
+
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(w, budget_s=10.0):
+    """The oracle, as it stands, on a bounded sample of streams of the same workload: once in
+    one process on one thread, once with one such process per host core over independent
+    streams (the processes' results are checked to be identical).  Runs in forked children
+    before this process touches the GPU; the children never do."""
+    import multiprocessing as mp
+    try:
+        avail = len(os.sched_getaffinity(0))
+    except AttributeError:
+        avail = os.cpu_count() or 1
+    cores = max(1, min(avail, 16))                 # a one-GPU box's share of host cores
+    ctx = mp.get_context("fork")
+    with ctx.Pool(1) as pool:
+        (n1, t1, d1), = pool.map(_cpu_worker, [(w.name, budget_s)])
+    with ctx.Pool(cores) as pool:
+        many = pool.map(_cpu_worker, [(w.name, budget_s)] * cores)
+    assert all(d == d1 for _, _, d in many), "oracle results differ between processes"
+    per_step = w.streams * w.layers                # stream-steps in one decode step
+    v1 = t1 / n1 * per_step * 1e6
+    rate = sum(n / t for n, t, _ in many)          # stream-steps per second, all processes
+    vall = per_step / rate * 1e6
+    return {"value": vall, "unit": "us/step", "cores": cores, "kind": "oracle",
+            "value_1core": v1, "value_allcores": vall, "nproc": avail, "cpu_model": cpu_model(),
+            "sample": "%d stream-steps of %s on one core in %.1f s, then %d on %d cores (one "
+                      "process each) in %.1f s: oracle page scores + selection + attention on the "
+                      "streams of batch element 0, scaled to the %d streams x %d layer(s) of a "
+                      "step" % (n1, w.name, t1, sum(n for n, _, _ in many), cores,
+                                max(t for _, t, _ in many), w.streams, w.layers)}
+
+
+# launch shape of the streaming-read kernel (workgroups, loads in flight per lane, contiguous
+# piece per workgroup): the fastest of a sweep on the box
+STREAM_READ_CFG = (0, 8, 0)
+
+
+def stream_read_ceiling(torch, dev):
+    """Plain streaming read of HBM on this machine (bench-only kernel in libstc_bench.so): GB/s of
+    1 GiB launches over a 2 GiB buffer, and of 64 MiB launches (the size of the scoring
+    kernel's traffic) walking the same buffer, so no launch finds its bytes in the 256 MB
+    last-level cache."""
+    import ctypes
+
+    from paper_2604_21335_amd.build import BENCH_LIB_PATH
+    lib = ctypes.CDLL(BENCH_LIB_PATH)
+    lib.stcb_stream_read.restype = ctypes.c_int
+    lib.stcb_stream_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                                     ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    gib = 1 << 30
+    buf = torch.empty(2 * gib, dtype=torch.uint8, device=dev)
+    buf.view(torch.int32).fill_(0x01020304)
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    base = buf.data_ptr()
+
+    def run(nbytes, count):
+        chunks = (2 * gib) // nbytes
+        def one(i):
+            rc = lib.stcb_stream_read(ctypes.c_void_p(base + (i % chunks) * nbytes), nbytes,
+                                      ctypes.c_void_p(sink.data_ptr()), *STREAM_READ_CFG, st)
+            assert rc == 0
+        for i in range(4):
+            one(i)
+        ms = timed(one, count, torch)
+        return nbytes / (ms * 1e-3) / 1e9, ms * 1e3
+    big, big_us = run(gib, 12)
+    small, small_us = run(64 << 20, 96)
+    del buf
+    return {"stream_read_GBps": big, "stream_read_1GiB_us": big_us,
+            "stream_read_64MiB_GBps": small, "stream_read_64MiB_us": small_us,
+            "stream_read_frac_of_peak": big / HBM_PEAK_GBPS}
 
 
 def bench_rows(stc, W, w, dev, n):
@@ -330,10 +440,14 @@ def main():
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
+    from paper_2604_21335_amd import workloads as W
+    cpu = None
+    if not args.no_cpu_baseline and not args.rows:
+        cpu = cpu_baseline(W.WORKLOADS[args.workload])    # in child processes, before any GPU use
+
     import torch
 
     import paper_2604_21335_amd as stc
-    from paper_2604_21335_amd import workloads as W
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -411,11 +525,13 @@ def main():
         dom, kernel, entry = "score", "score_mfma_kernel", "stc_score_pages"
     else:
         dom, kernel, entry = "attention", "attn_mfma_kernel", "stc_decode_attention"
+    traffic, step_traffic, traffic_src = measured_traffic(w.name, kernel)
     roofline = {"bound": "hbm", "kernel": kernel, "entry_point": entry,
                 "achieved": calls[dom]["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": calls[dom]["frac"], "traffic": MEASURED_TRAFFIC.get((w.name, kernel)),
+                "frac": calls[dom]["frac"], "traffic": traffic, "traffic_source": traffic_src,
                 "algorithmic_bytes": calls[dom]["bytes"], "avg_us": calls[dom]["us"],
                 "launches": args.steps}
+    ceiling = stream_read_ceiling(torch, dev)
     out = {
         "metric": METRIC, "value": ms_step * 1e3, "unit": "us/step", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
@@ -427,10 +543,14 @@ def main():
         "step_us_per_step_events": {"median": pct(0.5), "p10": pct(0.1), "p90": pct(0.9)},
         "hbm_GBps": step_gbps, "hbm_frac": step_gbps / HBM_PEAK_GBPS,
         "algorithmic_bytes_per_step": ab["step"] * L, "bytes_parts": ab["parts"],
+        "hbm_bytes_per_step_measured": step_traffic,
+        "hbm_bytes_per_step_measured_source": traffic_src,
         "calls": calls, "roofline": roofline,
     }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(W, w, dev)
+    out.update(ceiling)
+    out["hbm_frac_of_stream_read"] = step_gbps / ceiling["stream_read_GBps"]
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
     print(json.dumps(out))
 
 

@@ -7,6 +7,7 @@ from concurrent.futures import ThreadPoolExecutor
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libstc.so")
+BENCH_LIB_PATH = os.path.join(PKG_DIR, "libstc_bench.so")   # benchmark-only helpers (bench.py)
 BUILD_DIR = os.path.join(PKG_DIR, "_build")
 
 SOURCES = ["stc_api.hip", "bounds.hip", "router.hip", "route_pack.hip", "flush.hip",
@@ -54,6 +55,8 @@ def build_library(verbose=False):
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         list(ex.map(one, zip(SOURCES, objs)))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs])
+    _run([hipcc, *HIPCC_FLAGS, "-shared", "-o", BENCH_LIB_PATH,
+          os.path.join(CSRC, "bench_stream.hip")])
     return LIB_PATH
 
 

@@ -71,8 +71,8 @@ struct AttnCfg {
 __device__ u32x4 stc_zero16 = {0u, 0u, 0u, 0u};  // never written
 
 
-// One wavefront walks 2*PAIRS page slots of one stream, two at a time (PAIRS = 1 in regular
-// builds); the WAVES wavefronts of a workgroup then merge their partial results in LDS.
+// One wavefront takes one pair of page slots of one stream; the WAVES wavefronts of a workgroup
+// then merge their partial results in LDS.
 // Page slots are the selected pages of the compressed cache followed, with TAIL, by the pages
 // of the uncompressed tail; kv_div query-head streams may share one KV head's cache.
 //
@@ -89,29 +89,59 @@ __device__ u32x4 stc_zero16 = {0u, 0u, 0u, 0u};  // never written
 //      kept ones) or takes zeros if the group was dropped, reads it, transposes the
 //      8x8 block in registers with byte permutes and feeds MFMA row m of block cb
 //      <-> channel m*CB + cb.  The accumulators of a lane cover channels 32*kg...
-// Request order: page indices; masks/offsets of every page and the K rows of the
-// first pair; then, as soon as the offsets are there, the pair's V runs and the
-// next pair's K rows.  All loads are unconditional (addresses of absent pages or
+// Request order: page indices; masks/offsets and the K rows of the pair; then, as soon as
+// the offsets are there, the pair's V runs.  All loads are unconditional (addresses of absent pages or
 // tokens collapse to one valid location and the result is discarded) so that they
 // stay in flight across the arithmetic.
 // SELECT_IPT > 0: no page list is given; every workgroup first selects the stream's k pages
 // from the page scores itself (the same selection as the stand-alone kernel, SELECT_IPT keys
 // per thread), keeps the ones of its own split and writes them to the list.  Tail pages keep
 // their slots behind the k selected ones.
-template <int D, int PAIRS, int WAVES, bool TAIL, int SELECT_IPT>
-__global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
-    const uint16_t* __restrict__ q, const uint16_t* __restrict__ K,
-    const unsigned char* __restrict__ vpacked, const uint16_t* __restrict__ mask,
-    const uint32_t* __restrict__ tok_off, const int32_t* __restrict__ page_idx,
-    float* __restrict__ partial, float* __restrict__ out, int Hq, int Hkv, int N, int NP, int G,
-    uint32_t cap, int k_pages, int splits, const uint16_t* __restrict__ K_tail,
-    const uint16_t* __restrict__ V_tail, int n_tail, int tail_cap, int kv_div,
-    const uint16_t* __restrict__ page_heads, int Ncap, const float* __restrict__ sel_score,
-    int32_t* __restrict__ sel_list) {
+// Arguments of the attention kernels (one struct, passed by value).
+struct AttnParams {
+  const uint16_t *q, *K;
+  const unsigned char* vpacked;
+  const uint16_t* mask;
+  const uint32_t* tok_off;
+  const int32_t* page_idx;
+  float *partial, *out;
+  int Hq, Hkv, N, NP, G;
+  uint32_t cap;
+  int k_pages, splits;
+  const uint16_t *K_tail, *V_tail;
+  int n_tail, tail_cap, kv_div;
+  const uint16_t* page_heads;
+  int Ncap;
+  const float* sel_score;
+  int32_t* sel_list;
+};
+
+// The work of one workgroup: split `split` of stream `stream`.  `lds` = WAVES * WAVE_LDS bytes
+// of shared memory.  COHERENT: the page scores were written earlier in the same launch by
+// workgroups that may sit on another XCD; they are then read past the non-coherent caches.
+template <int D, int WAVES, bool TAIL, int SELECT_IPT, bool COHERENT>
+__device__ __forceinline__ void attn_block(const AttnParams& P, const int stream, const int split,
+                                           unsigned char* lds) {
   using C = AttnCfg<D>;
-  constexpr int ppw = 2 * PAIRS;  // pages per wavefront
-  extern __shared__ __align__(16) unsigned char lds[];  // WAVES * C::WAVE_LDS bytes
-  const int stream = blockIdx.y, split = blockIdx.x;
+  constexpr int ppw = 2;  // pages per wavefront
+  const uint16_t* __restrict__ q = P.q;
+  const uint16_t* __restrict__ K = P.K;
+  const unsigned char* __restrict__ vpacked = P.vpacked;
+  const uint16_t* __restrict__ mask = P.mask;
+  const uint32_t* __restrict__ tok_off = P.tok_off;
+  const int32_t* __restrict__ page_idx = P.page_idx;
+  float* __restrict__ partial = P.partial;
+  float* __restrict__ out = P.out;
+  const int Hq = P.Hq, Hkv = P.Hkv, N = P.N, NP = P.NP, G = P.G;
+  const uint32_t cap = P.cap;
+  const int k_pages = P.k_pages, splits = P.splits;
+  const uint16_t* __restrict__ K_tail = P.K_tail;
+  const uint16_t* __restrict__ V_tail = P.V_tail;
+  const int n_tail = P.n_tail, tail_cap = P.tail_cap, kv_div = P.kv_div;
+  const uint16_t* __restrict__ page_heads = P.page_heads;
+  const int Ncap = P.Ncap;
+  const float* __restrict__ sel_score = P.sel_score;
+  int32_t* __restrict__ sel_list = P.sel_list;
   const int b = stream / Hkv, kvh = stream % Hkv;
   const int R = Hq / Hkv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -160,7 +190,7 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
     __syncthreads();
     const int lo = split * WAVES * ppw;  // first list position of this workgroup
     int32_t* list = sel_list + (size_t)stream * k_pages;
-    topk_block<SELECT_IPT, 64 * WAVES>(sel_score + (size_t)stream * NP, NP, k_pages,
+    topk_block<SELECT_IPT, 64 * WAVES, COHERENT>(sel_score + (size_t)stream * NP, NP, k_pages,
                                        [&](int pos, int page) {
                                          const unsigned r = (unsigned)(pos - lo);
                                          if (r < (unsigned)(WAVES * ppw)) {
@@ -180,10 +210,10 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
   const uint32_t u_within = (unit - (u_g << lg_upg)) * 16 + ((D == 128) ? 0 : (r16 & 1) * 8);
 
   // lanes 0..15 carry the tokens of the pair's first page, 16..31 of its second page
-  uint32_t mk[PAIRS], off[PAIRS], run0[PAIRS][2], run1[PAIRS][2];
-  bool mvalid[PAIRS];
-  u32x4 kreg[PAIRS][2][C::NLD];
-  int pgs[PAIRS][2];
+  uint32_t mk, off, run0[2], run1[2];
+  bool mvalid;
+  u32x4 kreg[2][C::NLD];
+  int pgs[2];
 
   // Lanes 0..15 fetch mask and offset of the tokens of the pair's first page, lanes
   // 16..31 of its second page; lanes 32 and 33 fetch the offset just past each page
@@ -193,43 +223,43 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
   auto is_tail = [&](int pg) { return TAIL && pg >= kTailPage; };  // never, if no tail is given
   auto page_no = [&](int pg) { return pg & (kTailPage - 1); };
   auto tok_lim = [&](int pg) { return (uint32_t)(is_tail(pg) ? n_tail : N); };
-  uint32_t moi[PAIRS];   // token index behind off[] (tail pages derive their offsets from it)
-  bool mtail[PAIRS];     // this lane's meta words belong to a tail page
-  auto issue_meta = [&](int it) {
+  uint32_t moi;   // token index behind off[] (tail pages derive their offsets from it)
+  bool mtail;     // this lane's meta words belong to a tail page
+  auto issue_meta = [&]() {
 #pragma unroll
-    for (int x = 0; x < 2; ++x) pgs[it][x] = __builtin_amdgcn_readlane(my_pg, 2 * it + x);
-    const int pg = (lane & 1) ? pgs[it][1] : pgs[it][0];          // lanes 32, 33
-    const int pgt = (lane & 16) ? pgs[it][1] : pgs[it][0];        // token lanes
+    for (int x = 0; x < 2; ++x) pgs[x] = __builtin_amdgcn_readlane(my_pg, x);
+    const int pg = (lane & 1) ? pgs[1] : pgs[0];          // lanes 32, 33
+    const int pgt = (lane & 16) ? pgs[1] : pgs[0];        // token lanes
     const uint32_t t = (pgt < 0 ? 0 : page_no(pgt) * kPage) + r16;
     const bool tv = lane < 32 && pgt >= 0 && t < tok_lim(pgt);
     const uint32_t tend =
         pg < 0 ? 0u : min((uint32_t)page_no(pg) * kPage + kPage, tok_lim(pg));
     const uint32_t oi = tv ? t : ((lane == 32 || lane == 33) ? tend : 0u);
     const bool tl = lane < 32 ? (pgt >= 0 && is_tail(pgt)) : (pg >= 0 && is_tail(pg));
-    mvalid[it] = tv;
-    moi[it] = oi;
-    mtail[it] = tl;
+    mvalid = tv;
+    moi = oi;
+    mtail = tl;
     // tail lanes read word 0 of the stream's arrays and replace the result later
-    mk[it] = *(const uint16_t*)(mask_s + ((tv && !tl) ? t : 0u) * 2);  // discarded if !tv
-    off[it] = *(const uint32_t*)(off_s + (tl ? 0u : oi) * 4);
+    mk = *(const uint16_t*)(mask_s + ((tv && !tl) ? t : 0u) * 2);  // discarded if !tv
+    off = *(const uint32_t*)(off_s + (tl ? 0u : oi) * 4);
   };
   // start and end of the packed runs of a pair (wave-uniform), once the offsets are there.
   // A tail token keeps every group and its G groups sit at token index * G.
-  auto finish_meta = [&](int it) {
-    if (mtail[it]) {
-      mk[it] = full_mask;
-      off[it] = moi[it] * G;
+  auto finish_meta = [&]() {
+    if (mtail) {
+      mk = full_mask;
+      off = moi * G;
     }
 #pragma unroll
     for (int x = 0; x < 2; ++x) {
-      run0[it][x] = __builtin_amdgcn_readlane(off[it], 16 * x);  // token 0 of a page is valid
-      run1[it][x] = __builtin_amdgcn_readlane(off[it], 32 + x);
+      run0[x] = __builtin_amdgcn_readlane(off, 16 * x);  // token 0 of a page is valid
+      run1[x] = __builtin_amdgcn_readlane(off, 32 + x);
     }
   };
-  auto issue_k = [&](int it) {
+  auto issue_k = [&]() {
 #pragma unroll
     for (int x = 0; x < 2; ++x) {
-      const int pg = pgs[it][x];
+      const int pg = pgs[x];
       const uint32_t t0 = pg < 0 ? 0 : page_no(pg) * kPage;
       const uint32_t lim = tok_lim(pg);
       const unsigned char* kb = (pg >= 0 && is_tail(pg)) ? Kts : Ks;  // wave-uniform
@@ -239,24 +269,24 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
         const bool tv = pg >= 0 && (t0 + tok < lim);
         // rows of absent tokens read the store's first bytes: their logits are discarded
         const uint32_t ko = tv ? t0 * (D * 2) + (j * 64 + lane) * 16 : 0;
-        kreg[it][x][j] = *(const u32x4*)(kb + ko);
+        kreg[x][j] = *(const u32x4*)(kb + ko);
       }
     }
   };
   // Groups of a page present in the store (wave-uniform).
-  auto run_groups = [&](int it, int x) -> uint32_t {
-    const uint32_t r0 = run0[it][x];
-    const uint32_t store = is_tail(pgs[it][x]) ? (uint32_t)tail_cap * G : cap;
-    const uint32_t r1 = pgs[it][x] < 0 ? 0u : min(run1[it][x], store);
+  auto run_groups = [&](int x) -> uint32_t {
+    const uint32_t r0 = run0[x];
+    const uint32_t store = is_tail(pgs[x]) ? (uint32_t)tail_cap * G : cap;
+    const uint32_t r1 = pgs[x] < 0 ? 0u : min(run1[x], store);
     const uint32_t rg = r1 > r0 ? r1 - r0 : 0u;
     return min(rg, (uint32_t)(kPage * G));
   };
   // Packed V runs of a pair, flat; lanes past the end of a run read the zero line.
-#define STC_ISSUE_V(it, vreg)                                                                  \
+#define STC_ISSUE_V(vreg)                                                                      \
   static_for<0, 2>([&](auto x) {                                                               \
-    const uint32_t rbytes = run_groups(it, x) * gbytes + vgate;                                \
+    const uint32_t rbytes = run_groups(x) * gbytes + vgate;                                \
     const unsigned char* vrun =                                                                \
-        ((pgs[it][x] >= 0 && is_tail(pgs[it][x])) ? vts : vs) + (size_t)run0[it][x] * gbytes;  \
+        ((pgs[x] >= 0 && is_tail(pgs[x])) ? vts : vs) + (size_t)run0[x] * gbytes;  \
     static_for<0, C::NLD>([&](auto j) {                                                        \
       const uint32_t bo = (j * 64 + lane) * 16;                                                \
       /* one address computed with integer selects, so that it stays a single request */      \
@@ -271,10 +301,9 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
   float m_run = kNegBig, l_part = 0.f;
 
   // The scheduling fences keep the request order stated above.
-#pragma unroll
-  for (int it = 0; it < PAIRS; ++it) issue_meta(it);
+  issue_meta();
   __builtin_amdgcn_sched_barrier(0);
-  issue_k(0);
+  issue_k();
   __builtin_amdgcn_sched_barrier(0);
 
   // B operand of the QK product: this lane's 8 channels of head r16 for every 32-channel step
@@ -290,14 +319,14 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
 
   // logits of a pair, online softmax; leaves the weights of the pair in phi/plo
   u32x4 phi, plo;
-  auto qk_softmax = [&](int it) {
+  auto qk_softmax = [&]() {
     // K rows of the pair -> LDS tiles (row stride ROW), then back in MFMA operand layout
 #pragma unroll
     for (int x = 0; x < 2; ++x)
 #pragma unroll
       for (int j = 0; j < C::NLD; ++j)
         *(u32x4*)(wl + (x * C::TILE + ((j * 64 + lane) / C::LPR) * C::ROW +
-                        (lane % C::LPR) * 16)) = kreg[it][x][j];
+                        (lane % C::LPR) * 16)) = kreg[x][j];
     wave_lds_sync();
     float s[2][4];
     float mx = kNegBig;
@@ -311,11 +340,11 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
         sv = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), as_bf16x8(qreg[j]), sv, 0, 0, 0);
       }
       // this lane holds tokens 4*kg + i of page x for head r16
-      const int pg = pgs[it][x];
+      const int pg = pgs[x];
       const uint32_t t0 = pg < 0 ? 0 : page_no(pg) * kPage;
       const uint32_t lim = tok_lim(pg);
       // a head that did not select this page gives its tokens no weight
-      const bool mine = (__builtin_amdgcn_readlane(my_heads, 2 * it + x) >> r16) & 1;
+      const bool mine = (__builtin_amdgcn_readlane(my_heads, x) >> r16) & 1;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const bool tv = pg >= 0 && mine && (t0 + 4 * kg + i < lim);
@@ -338,10 +367,6 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
         psum += p[x * 4 + i];
       }
     l_part = l_part * rescale + psum;
-    if (it > 0 && __any(rescale != 1.0f)) {  // wave-uniform: the running maximum moved
-#pragma unroll
-      for (int cb = 0; cb < C::CB; ++cb) acc[cb] *= rescale;
-    }
     // weights as two bf16 parts; contraction index: (kg, e) e<4 page 0, e>=4 page 1
     uint32_t h[4], l[4];
 #pragma unroll
@@ -354,7 +379,7 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
   };
 
   // packed runs of a pair -> LDS, then O^T += V~^T . P^T
-#define STC_PV(it, vreg)                                                                       \
+#define STC_PV(vreg)                                                                           \
   {                                                                                            \
     wave_lds_sync(); /* the K tiles have been read */                                          \
     static_for<0, 2>([&](auto x) {                                                             \
@@ -363,15 +388,15 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
       });                                                                                      \
     });                                                                                        \
     if (lane < 32) { /* token lane: kept-group mask and offset relative to the run */         \
-      const uint32_t r0 = (lane & 16) ? run0[it][1] : run0[it][0];                             \
-      const uint32_t rel = min(off[it] - r0, 0xffffu);                                         \
-      *(uint32_t*)(wl + C::META + lane * 4) = (mvalid[it] ? mk[it] : 0u) | (rel << 16);        \
+      const uint32_t r0 = (lane & 16) ? run0[1] : run0[0];                             \
+      const uint32_t rel = min(off - r0, 0xffffu);                                         \
+      *(uint32_t*)(wl + C::META + lane * 4) = (mvalid ? mk : 0u) | (rel << 16);        \
     }                                                                                          \
     wave_lds_sync();                                                                           \
     /* t[e]: channels r16*CB .. +CB of token e of this lane's k-group (e < 4: page 0) */       \
     uint32_t t[8][C::CB / 2];                                                                  \
     _Pragma("unroll") for (int x = 0; x < 2; ++x) {                                            \
-      const uint32_t rg = run_groups(it, x);                                                   \
+      const uint32_t rg = run_groups(x);                                                   \
       const u32x4 mt = *(const u32x4*)(wl + C::META + x * 64 + kg * 16);                       \
       _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                          \
         const uint32_t m = mt[i] & 0xffffu;                                                    \
@@ -405,29 +430,15 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
     // a wavefront then has one pair of K pages or one pair of V runs plus the next K
     // pages outstanding, which keeps the chip-wide volume of outstanding requests near
     // what the memory system sustains.  (Requesting everything at once is slower.)
-    finish_meta(0);
+    finish_meta();
     uint32_t vgate;
-    asm volatile("v_and_b32 %0, 0, %1" : "=v"(vgate) : "v"(off[0] ^ mk[0]));  // 0, after they arrive
+    asm volatile("v_and_b32 %0, 0, %1" : "=v"(vgate) : "v"(off ^ mk));  // 0, after they arrive
     u32x4 vregA[2][C::NLD];
-    STC_ISSUE_V(0, vregA);
+    STC_ISSUE_V(vregA);
     __builtin_amdgcn_sched_barrier(0);
-    u32x4 vregB[2][C::NLD];
-    if constexpr (PAIRS > 1) {
-      issue_k(1);
-      __builtin_amdgcn_sched_barrier(0);
-      finish_meta(1);
-      STC_ISSUE_V(1, vregB);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    qk_softmax(0);
+    qk_softmax();
     __builtin_amdgcn_sched_barrier(0);
-    STC_PV(0, vregA);
-    if constexpr (PAIRS > 1) {
-      if (npairs > 1) {
-        qk_softmax(1);
-        STC_PV(1, vregB);
-      }
-    }
+    STC_PV(vregA);
   }
 
   // sum of weights of head r16 over this wavefront's tokens
@@ -482,6 +493,12 @@ __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(
 
 #undef STC_ISSUE_V
 #undef STC_PV
+
+template <int D, int WAVES, bool TAIL, int SELECT_IPT>
+__global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(const AttnParams P) {
+  extern __shared__ __align__(16) unsigned char lds[];  // WAVES * AttnCfg<D>::WAVE_LDS bytes
+  attn_block<D, WAVES, TAIL, SELECT_IPT, false>(P, blockIdx.y, blockIdx.x, lds);
+}
 
 // Merge the split partials of one query head in ascending split order.  Each
 // thread owns one channel; partials are fetched 8 splits at a time (one round of
@@ -555,50 +572,33 @@ size_t attention_ws_bytes(const stc_shape_t& s0, int k_pages, bool per_head) {
 
 namespace {
 
-struct AttnArgs {
-  const uint16_t *q, *K;
-  const unsigned char* vpacked;
-  const uint16_t* mask;
-  const uint32_t* tok_off;
-  const int32_t* page_idx;
-  float *partial, *out;
-  int Hq, Hkv, N, NP, G;
-  uint32_t cap;
-  int k_pages, splits;
-  const uint16_t *K_tail, *V_tail;
-  int n_tail, tail_cap, kv_div;
-  const uint16_t* page_heads;
-  int Ncap;
-  const float* sel_score;
-  int32_t* sel_list;
+struct AttnLaunch {
+  AttnParams p;
   dim3 grid;
   hipStream_t st;
 };
 
-template <int D, int PAIRS, int WAVES, bool TAIL, int SELECT_IPT>
-int attn_go(const AttnArgs& a) {
+template <int D, int WAVES, bool TAIL, int SELECT_IPT>
+int attn_go(const AttnLaunch& a) {
   // workgroups of 8 wavefronts at D = 128 need more than the default 64 KiB of LDS
   constexpr int lds_bytes = WAVES * AttnCfg<D>::WAVE_LDS;
   static std::atomic<uint64_t> allowed{0};
-  if (!allow_dynamic_lds((const void*)attn_mfma_kernel<D, PAIRS, WAVES, TAIL, SELECT_IPT>,
-                         lds_bytes, allowed))
+  if (!allow_dynamic_lds((const void*)attn_mfma_kernel<D, WAVES, TAIL, SELECT_IPT>, lds_bytes,
+                         allowed))
     return -1;
-  attn_mfma_kernel<D, PAIRS, WAVES, TAIL, SELECT_IPT><<<a.grid, 64 * WAVES, lds_bytes, a.st>>>(
-      a.q, a.K, a.vpacked, a.mask, a.tok_off, a.page_idx, a.partial, a.out, a.Hq, a.Hkv, a.N, a.NP,
-      a.G, a.cap, a.k_pages, a.splits, a.K_tail, a.V_tail, a.n_tail, a.tail_cap, a.kv_div,
-      a.page_heads, a.Ncap, a.sel_score, a.sel_list);
+  attn_mfma_kernel<D, WAVES, TAIL, SELECT_IPT><<<a.grid, 64 * WAVES, lds_bytes, a.st>>>(a.p);
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 template <int D>
-int attn_dispatch(const AttnArgs& a, const AttnPlan& plan, bool tail, bool select) {
+int attn_dispatch(const AttnLaunch& a, const AttnPlan& plan, bool tail, bool select) {
   if (select) {  // selection inside the kernel: 2048 keys over the workgroup's threads
     if (plan.waves == 8)
-      return tail ? attn_go<D, 1, 8, true, 4>(a) : attn_go<D, 1, 8, false, 4>(a);
-    return tail ? attn_go<D, 1, 4, true, 8>(a) : attn_go<D, 1, 4, false, 8>(a);
+      return tail ? attn_go<D, 8, true, 4>(a) : attn_go<D, 8, false, 4>(a);
+    return tail ? attn_go<D, 4, true, 8>(a) : attn_go<D, 4, false, 8>(a);
   }
-  if (plan.waves == 8) return tail ? attn_go<D, 1, 8, true, 0>(a) : attn_go<D, 1, 8, false, 0>(a);
-  return tail ? attn_go<D, 1, 4, true, 0>(a) : attn_go<D, 1, 4, false, 0>(a);
+  if (plan.waves == 8) return tail ? attn_go<D, 8, true, 0>(a) : attn_go<D, 8, false, 0>(a);
+  return tail ? attn_go<D, 4, true, 0>(a) : attn_go<D, 4, false, 0>(a);
 }
 
 }  // namespace
@@ -624,20 +624,21 @@ int launch_attention(const stc_shape_t& s0, const void* q, const void* K, const 
   const int tail_pages = (n_tail + kPage - 1) / kPage;
   if (tail_pages == 0) K_tail = V_tail = K;  // any valid address: never read
   const AttnPlan plan = attention_plan(s, k_pages + tail_pages);
-  AttnArgs a{(const uint16_t*)q, (const uint16_t*)K, (const unsigned char*)vpacked, mask, tok_off,
-             page_idx, (float*)ws, out, s.Hq, s.Hkv, s.N, NP, s.G, (uint32_t)s.v_cap_groups,
-             k_pages, plan.splits, (const uint16_t*)K_tail, (const uint16_t*)V_tail, n_tail,
-             tail_cap, per_head ? s0.Hq / s0.Hkv : 1, page_heads, token_cap(s), sel_score,
-             sel_list, dim3(plan.splits, streams), st};
+  AttnLaunch a{{(const uint16_t*)q, (const uint16_t*)K, (const unsigned char*)vpacked, mask, tok_off,
+                page_idx, (float*)ws, out, s.Hq, s.Hkv, s.N, NP, s.G, (uint32_t)s.v_cap_groups,
+                k_pages, plan.splits, (const uint16_t*)K_tail, (const uint16_t*)V_tail, n_tail,
+                tail_cap, per_head ? s0.Hq / s0.Hkv : 1, page_heads, token_cap(s), sel_score,
+                sel_list},
+               dim3(plan.splits, streams), st};
   if (sel_score && (NP > 2048 || per_head || page_heads)) return -1;
   const int rc = s.D == 128 ? attn_dispatch<128>(a, plan, tail_pages > 0, sel_score != nullptr)
                             : attn_dispatch<64>(a, plan, tail_pages > 0, sel_score != nullptr);
   if (rc) return -1;
   if (plan.splits > 1) {
     if (s.D == 128)
-      attn_combine_kernel<128><<<s.B * s.Hq, 128, 0, st>>>(a.partial, out, plan.splits);
+      attn_combine_kernel<128><<<s.B * s.Hq, 128, 0, st>>>(a.p.partial, out, plan.splits);
     else
-      attn_combine_kernel<64><<<s.B * s.Hq, 64, 0, st>>>(a.partial, out, plan.splits);
+      attn_combine_kernel<64><<<s.B * s.Hq, 64, 0, st>>>(a.p.partial, out, plan.splits);
     if (hipGetLastError() != hipSuccess) return -1;
   }
   return 0;

@@ -18,6 +18,7 @@
 // requests and every 64-bit register pair it receives is a B operand as it stands.
 // Lane l of a wavefront holds, for page 4*(l/32) + l%4 of the tile, the D/8 channels
 // of chunk (l/4)%8; the 16 blocks of the MFMA are the 16 (page group, chunk) pairs.
+#include "score_tiles.hpp"
 #include "stc_common.hpp"
 #include "stc_kernels.hpp"
 #include "topk_block.hpp"
@@ -155,6 +156,30 @@ void score_mfma_kernel(const u32x4* __restrict__ tiles, const uint16_t* __restri
   }
 }
 
+// The same scores with the query operands in shared memory (score_tiles.hpp): at most 128
+// registers, so four wavefronts per SIMD also for five to eight heads per KV head.
+template <int D, int R, bool PER_HEAD, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(4, 8)))
+void score_lds_kernel(const u32x4* __restrict__ tiles, const uint16_t* __restrict__ q,
+                      float* __restrict__ score, int NP, int Hq, int Hkv, int tiles_per_block,
+                      int tiles_cap) {
+  constexpr int T16 = (D / 32) * 64;
+  __shared__ __align__(16) unsigned char s_q[score_q_lds_bytes<D, R>()];
+  const int stream = blockIdx.y;
+  const int b = stream / Hkv, kvh = stream % Hkv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int ntiles = (NP + kBoundsTilePages - 1) / kBoundsTilePages;
+  const int t0 = blockIdx.x * tiles_per_block;
+  const int t1 = min(t0 + tiles_per_block, ntiles);
+  const uint16_t* qs = q + ((size_t)b * Hq + kvh * R) * D;
+  score_tile_range<D, R, PER_HEAD, WAVES>(
+      (const score_u32x4*)tiles + (size_t)stream * tiles_cap * T16 + lane,
+      score + (size_t)stream * (PER_HEAD ? R : 1) * NP, NP, t0, t1, s_q, wave, lane, [&] {
+        score_fill_q<D, R, 64 * WAVES>(qs, s_q);
+        __syncthreads();
+      });
+}
+
 // A bf16 value widened to float, with subnormal inputs read as zero (what the matrix cores do
 // with the operands of the kernel above).
 __device__ __forceinline__ float daz(float x) {
@@ -223,6 +248,31 @@ static void launch_score_d(const stc_shape_t& s, const void* q, const void* boun
   dim3 grid((ntiles + tpb - 1) / tpb, streams);
   const u32x4* t4 = (const u32x4*)bounds;
   const uint16_t* q16 = (const uint16_t*)q;
+  if (D == 128 && R > 4 && R <= 8) {
+    // query operands in shared memory: four workgroups of four wavefronts per CU
+    constexpr int WV = 4;
+    const int want = max(1, 1024 / streams);
+    int tp = (ntiles + want - 1) / want;
+    tp = (tp + WV - 1) / WV * WV;
+    dim3 g2((ntiles + tp - 1) / tp, streams);
+#define STC_SCORE_LDS_CASE(RR)                                                                 \
+  case RR:                                                                                     \
+    if (per_head)                                                                              \
+      score_lds_kernel<D, RR, true, WV><<<g2, 64 * WV, 0, st>>>(t4, q16, score, NP, s.Hq,      \
+                                                                s.Hkv, tp, tcap);              \
+    else                                                                                       \
+      score_lds_kernel<D, RR, false, WV><<<g2, 64 * WV, 0, st>>>(t4, q16, score, NP, s.Hq,     \
+                                                                 s.Hkv, tp, tcap);             \
+    break;
+    switch (R) {
+      STC_SCORE_LDS_CASE(5)
+      STC_SCORE_LDS_CASE(6)
+      STC_SCORE_LDS_CASE(7)
+      STC_SCORE_LDS_CASE(8)
+    }
+#undef STC_SCORE_LDS_CASE
+    return;
+  }
 #define STC_SCORE_CASE(RR)                                                                    \
   case RR:                                                                                    \
     if (per_head)                                                                             \
