@@ -117,9 +117,8 @@ struct AttnParams {
 };
 
 // The work of one workgroup: split `split` of stream `stream`.  `lds` = WAVES * WAVE_LDS bytes
-// of shared memory.  COHERENT: the page scores were written earlier in the same launch by
-// workgroups that may sit on another XCD; they are then read past the non-coherent caches.
-template <int D, int WAVES, bool TAIL, int SELECT_IPT, bool COHERENT>
+// of shared memory.
+template <int D, int WAVES, bool TAIL, int SELECT_IPT>
 __device__ __forceinline__ void attn_block(const AttnParams& P, const int stream, const int split,
                                            unsigned char* lds) {
   using C = AttnCfg<D>;
@@ -190,7 +189,7 @@ __device__ __forceinline__ void attn_block(const AttnParams& P, const int stream
     __syncthreads();
     const int lo = split * WAVES * ppw;  // first list position of this workgroup
     int32_t* list = sel_list + (size_t)stream * k_pages;
-    topk_block<SELECT_IPT, 64 * WAVES, COHERENT>(sel_score + (size_t)stream * NP, NP, k_pages,
+    topk_block<SELECT_IPT, 64 * WAVES>(sel_score + (size_t)stream * NP, NP, k_pages,
                                        [&](int pos, int page) {
                                          const unsigned r = (unsigned)(pos - lo);
                                          if (r < (unsigned)(WAVES * ppw)) {
@@ -497,7 +496,7 @@ __device__ __forceinline__ void attn_block(const AttnParams& P, const int stream
 template <int D, int WAVES, bool TAIL, int SELECT_IPT>
 __global__ __launch_bounds__(64 * WAVES) void attn_mfma_kernel(const AttnParams P) {
   extern __shared__ __align__(16) unsigned char lds[];  // WAVES * AttnCfg<D>::WAVE_LDS bytes
-  attn_block<D, WAVES, TAIL, SELECT_IPT, false>(P, blockIdx.y, blockIdx.x, lds);
+  attn_block<D, WAVES, TAIL, SELECT_IPT>(P, blockIdx.y, blockIdx.x, lds);
 }
 
 // Merge the split partials of one query head in ascending split order.  Each

@@ -88,9 +88,7 @@ __device__ __forceinline__ uint32_t block_exscan_once(uint32_t v, uint32_t* lds_
 // The selected pages are handed to emit(position in the ascending list, page).  Each radix
 // pass is a shared-memory histogram of one key byte, a block scan over the digits in
 // descending order and a broadcast of the digit that holds the k-th largest key.
-// COHERENT: the scores were written earlier in the same launch, possibly through another L2:
-// they are read with device-scope loads (past the caches that are not coherent).
-template <int IPT, int THREADS, bool COHERENT = false, class Emit>
+template <int IPT, int THREADS, class Emit>
 __device__ __forceinline__ void topk_block(const float* __restrict__ sc, int NP, int k,
                                            Emit emit) {
   constexpr int NW = THREADS / 64;
@@ -107,13 +105,7 @@ __device__ __forceinline__ void topk_block(const float* __restrict__ sc, int NP,
 
   // keys of absent pages (index >= NP) are 0, below the key of any finite float
   uint32_t key[IPT];
-  if constexpr (COHERENT) {
-#pragma unroll
-    for (int j = 0; j < IPT; ++j)
-      key[j] = i0 + j < NP ? float_key(__hip_atomic_load(sc + i0 + j, __ATOMIC_RELAXED,
-                                                         __HIP_MEMORY_SCOPE_AGENT))
-                           : 0u;
-  } else if constexpr (IPT >= 4) {
+  if constexpr (IPT >= 4) {
     if (i0 + IPT <= NP && (NP % 4) == 0) {
 #pragma unroll
       for (int j = 0; j < IPT; j += 4) {
