@@ -113,6 +113,38 @@ def build_replicas(stc, W, w, n_rep, dev):
     return caches, mean_kept
 
 
+def layer_batched(stc, W, w, dev, queries, steps, warmup, torch):
+    """The workload's `layers` independent layer caches as ONE launch set: a single cache whose
+    batch entries are the layers (the memory layout of a batch of caches is exactly that), one
+    stc_decode_step per decode step.  In a model the layers depend on each other, so this is a
+    throughput figure for the same bytes, not the latency of a step; it shows how much of the
+    per-layer time is launch latency."""
+    L = w.layers
+    wb = W.shrink(w, B=w.B * L, layers=1)
+    c = stc.RoutedCache(wb.B, wb.Hq, wb.Hkv, wb.D, wb.N, wb.G, wb.k_pages, device=dev,
+                        keep_scores=False, n_cap=wb.N)       # n_cap: the cache owns its K
+    V = torch.empty(wb.B, wb.Hkv, wb.N, wb.D, dtype=torch.bfloat16, device=dev)
+    logits = torch.empty(wb.B, wb.Hkv, wb.N, wb.G, dtype=torch.float32, device=dev)
+    kcount = torch.empty(wb.B, wb.Hkv, wb.N, dtype=torch.uint8, device=dev)
+    for lay in range(L):
+        K1, V1, inp = cache_inputs(stc, W, w, dev, lay)
+        sl = slice(lay * w.B, (lay + 1) * w.B)
+        c.K[sl].copy_(K1)
+        V[sl].copy_(V1)
+        logits[sl].copy_(inp["logits"])
+        kcount[sl].copy_(inp["kcount"])
+        del K1, V1, inp
+    c.build(c.K, V, logits=logits, kcount=kcount)
+    torch.cuda.synchronize()
+    assert int(c.dev_status.item()) == 0
+    del V, logits, kcount
+    qb = [q.repeat(L, 1, 1).contiguous() for q in queries[:8]]
+    for i in range(warmup):
+        c.step(qb[i % len(qb)])
+    ms = timed(lambda i: c.step(qb[i % len(qb)]), steps, torch)
+    return ms
+
+
 def timed(fn, n, torch):
     """Average milliseconds per call of fn(i) over n back-to-back calls, from HIP events
     recorded on the stream the kernels are launched on (torch's current stream)."""
@@ -547,6 +579,14 @@ def main():
         "hbm_bytes_per_step_measured_source": traffic_src,
         "calls": calls, "roofline": roofline,
     }
+    if L > 1:
+        ms_lb = layer_batched(stc, W, w, dev, queries, min(args.steps, 50), 10, torch)
+        g = gbps(ab["step"] * L, ms_lb)
+        out["layer_batched"] = {
+            "us": ms_lb * 1e3, "GBps": g, "frac": g / HBM_PEAK_GBPS,
+            "note": "the %d layer caches of a step as one launch set (one cache with the layers "
+                    "as batch entries): same bytes, 1/%d of the launches; a throughput figure, "
+                    "the layers of a model depend on each other" % (L, L)}
     out.update(ceiling)
     out["hbm_frac_of_stream_read"] = step_gbps / ceiling["stream_read_GBps"]
     if cpu is not None:
