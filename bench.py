@@ -554,7 +554,9 @@ def main():
     # the dominant kernel is the one that moves the most bytes: page scoring where the bounds
     # outweigh the selected K pages and V runs (the headline workload), else the attention kernel
     if selecting and ab["score"] >= ab["attention"]:
-        dom, kernel, entry = "score", "score_mfma_kernel", "stc_score_pages"
+        # more than four heads per KV head at D = 128: the form with the query operands in LDS
+        kernel = "score_lds_kernel" if (w.D == 128 and 4 < w.R <= 8) else "score_mfma_kernel"
+        dom, entry = "score", "stc_score_pages"
     else:
         dom, kernel, entry = "attention", "attn_mfma_kernel", "stc_decode_attention"
     traffic, step_traffic, traffic_src = measured_traffic(w.name, kernel)
