@@ -311,6 +311,163 @@ def stream_read_ceiling(torch, dev):
                                                      "workgroup"}}
 
 
+def bench_rows(stc, W, w, dev, n):
+    """Every other entry point at the same workload's shape: cache construction, the routing
+    variants, the router, the tail and the per-query-head forms.  One JSON line: per call the
+    mean microseconds over n back-to-back launches (HIP events on the launch stream) and the
+    algorithmic bytes it has to move, against 8 TB/s."""
+    import torch
+    rows = {}
+
+    def row(name, ms, nbytes, note=None):
+        g = nbytes / (ms * 1e-3) / 1e9
+        rows[name] = {"us": ms * 1e3, "bytes": int(nbytes), "GBps": g, "frac": g / HBM_PEAK_GBPS}
+        if note:
+            rows[name]["note"] = note
+
+    streams, gd, R = w.streams, w.D // w.G, w.R
+    K, V, inp = cache_inputs(stc, W, w, dev, 0)
+    logits, kcount, mask_in = inp["logits"], inp["kcount"], inp["mask_in"]
+    if logits is None:                 # a workload routed by given masks: logits for the
+        logits = torch.randn(w.B, w.Hkv, w.N, w.G, device=dev)      # routing rows only
+    c = stc.RoutedCache(w.B, w.Hq, w.Hkv, w.D, w.N, w.G, w.k_pages, device=dev, keep_scores=False)
+    kv_bytes = streams * w.N * w.D * 2
+    # a1, a2, f1: cache construction
+    row("stc_build_page_bounds", timed(lambda i: stc.stc_build_page_bounds(c.shape, K, c.bounds),
+                                        n, torch), kv_bytes + stc.stc_bounds_bytes(c.shape))
+    meta = streams * (w.N * 2 + (w.N + 1) * 4)
+
+    def route(mode, kc, fixed):
+        stc.stc_route_and_pack_values(c.shape, mode, V, logits, kc, fixed, None, c.mask, c.tok_off,
+                                      c.vpacked, c.dev_status, c._ws_route)
+    for name, mode, kc, fixed in (("stc_route_and_pack_values(top-k per token)",
+                                   stc.STC_ROUTE_TOPK, kcount, 0 if kcount is not None else w.G // 2),
+                                  ("stc_route_and_pack_values(global budget N*4)",
+                                   stc.STC_ROUTE_GLOBAL, None, w.G // 2)):
+        ms = timed(lambda i: route(mode, kc, fixed), n, torch)
+        kept = int(c.tok_off[..., -1].to(torch.int64).sum().item())
+        row(name, ms, kv_bytes + logits.numel() * 4 + (kcount.numel() if kc is not None else 0)
+            + meta + kept * gd * 2)
+    c.build(K, V, logits=inp["logits"], kcount=kcount, mask_in=mask_in)
+    mean_kept = int(c.tok_off[..., -1].to(torch.int64).sum().item()) / float(streams * w.N)
+    ab = algorithmic_bytes(w, mean_kept)
+    # f4: the router's projection (hidden size of the 7B models of the paper's LLM setting)
+    d_model = 3584
+    h = torch.randn(w.B, w.N, d_model, device=dev, dtype=torch.bfloat16)
+    Wr = (torch.randn(w.G, d_model, device=dev) / d_model ** 0.5).to(torch.bfloat16)
+    bias = torch.randn(w.G, device=dev)
+    lg = torch.empty(w.B, 1, w.N, w.G, dtype=torch.float32, device=dev)
+    row("stc_router_logits(d_model=3584)",
+        timed(lambda i: stc.stc_router_logits(h, Wr, bias, lg, 1), n, torch),
+        h.numel() * 2 + Wr.numel() * 2 + lg.numel() * 4,
+        "one copy of the logits per batch element (routed with STC_ROUTE_SHARED)")
+
+    def route_shared(i):
+        stc.stc_route_and_pack_values(c.shape, stc.STC_ROUTE_TOPK | stc.STC_ROUTE_SHARED, V, lg,
+                                      None, w.G // 2, None, c.mask, c.tok_off, c.vpacked,
+                                      c.dev_status, c._ws_route)
+    ms = timed(route_shared, n, torch)
+    kept = int(c.tok_off[..., -1].to(torch.int64).sum().item())
+    row("stc_route_and_pack_values(router logits shared by the KV heads, top-4)", ms,
+        kv_bytes + lg.numel() * 4 + meta + kept * gd * 2)
+    c.build(K, V, logits=inp["logits"], kcount=kcount, mask_in=mask_in)    # back to the workload's
+    del h, lg
+    # f2: uncompressed tail (100 of 128 rows in use), append, flush of 64 tokens
+    qs = [W.make_query(w, s_, dev) for s_ in range(8)]
+    tails = []
+    for r in range(3):
+        t = stc.RoutedCache(w.B, w.Hq, w.Hkv, w.D, w.N, w.G, w.k_pages, device=dev,
+                            keep_scores=False, tail_cap=128, n_cap=w.N + 2048)
+        rK, rV, ri = cache_inputs(stc, W, w, dev, r + 1)
+        t.build(rK, rV, logits=ri["logits"], kcount=ri["kcount"], mask_in=ri["mask_in"])
+        t.K_tail.copy_(torch.randn_like(t.K_tail, dtype=torch.float32))
+        t.V_tail.copy_(torch.randn_like(t.V_tail, dtype=torch.float32))
+        t.n_tail = 100
+        tails.append(t)
+        del ri, rK, rV
+    tail_bytes = streams * 100 * w.D * 2 * 2
+    for i in range(20):
+        tails[i % 3].step(qs[i % 8])
+    row("stc_decode_step_tail(n_tail=100)",
+        timed(lambda i: tails[i % 3].step(qs[i % 8]), 4 * n, torch), ab["step"] + tail_bytes)
+    knew = torch.randn(w.B, w.Hkv, w.D, device=dev).to(torch.bfloat16)
+
+    def append(i):
+        t = tails[0]
+        stc.stc_append_tail(t.shape, knew, knew, t.K_tail, t.V_tail, 100 + i % 28, t.tail_cap)
+    row("stc_append_tail", timed(append, 4 * n, torch), 4 * streams * w.D * 2,
+        "latency of one small launch")
+    fl = torch.randn(w.B, w.Hkv, 64, w.G, device=dev)
+    evs = []
+    for i in range(min(n, 24)):                     # N grows by 64 per flush: 24 * 64 <= 2048
+        t = tails[i % 3]
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        stc.stc_flush_tail(t.shape, t.K_tail, t.V_tail, 64, 100, t.tail_cap, stc.STC_ROUTE_TOPK, fl,
+                           None,
+                           w.G // 2, None, t.K, t.bounds, t.mask, t.tok_off, t.vpacked,
+                           t.dev_status)
+        b.record()
+        evs.append((a, b))
+        t.N += 64
+        t.shape.N = t.N
+    torch.cuda.synchronize()
+    ms = sum(a.elapsed_time(b) for a, b in evs[4:]) / len(evs[4:])
+    row("stc_flush_tail(64 tokens)", ms,
+        streams * 64 * (w.D * 2 * 2 + w.D * 2 + w.D // 2 * 2 + w.G * 4) + streams * 5 * 4 * w.D,
+        "one workgroup per stream; timed one launch at a time")
+    del tails
+    # f3: per-query-head selection and attention, and the de-duplicated (union) form
+    k = min(w.k_pages, w.NP)
+    ph = []
+    for r in range(2):
+        t = stc.RoutedCache(w.B, w.Hq, w.Hkv, w.D, w.N, w.G, w.k_pages, device=dev,
+                            keep_scores=False)
+        rK, rV, ri = cache_inputs(stc, W, w, dev, r + 4)
+        t.build(rK, rV, logits=ri["logits"], kcount=ri["kcount"], mask_in=ri["mask_in"])
+        ph.append(t)
+        del ri, rK, rV
+    idx = torch.empty(w.B, w.Hq, k, dtype=torch.int32, device=dev)
+
+    def ws(which, kk):
+        return torch.empty(max(16, stc.stc_workspace_bytes(c.shape, which, kk)), dtype=torch.uint8,
+                           device=dev)
+    ws_s, ws_a = ws(stc.STC_WS_SELECT_PER_HEAD, k), ws(stc.STC_WS_ATTENTION_PER_HEAD, k)
+    out = torch.empty(w.B, w.Hq, w.D, dtype=torch.float32, device=dev)
+    if w.k_pages < w.NP:
+        def sel(i):
+            t = ph[i % 2]
+            stc.stc_select_pages_per_head(t.shape, qs[i % 8], t.bounds, k, idx, None, ws_s)
+        row("stc_select_pages_per_head", timed(sel, n, torch),
+            ab["parts"]["bounds"] + w.B * w.Hq * (w.NP * 4 + k * 4))
+
+        def att(i):
+            t = ph[i % 2]
+            stc.stc_decode_attention_per_head(t.shape, qs[0], t.K, t.vpacked, t.mask, t.tok_off, idx,
+                                              k, out, ws_a)
+        stc.stc_select_pages_per_head(ph[0].shape, qs[0], ph[0].bounds, k, idx, None, ws_s)
+        row("stc_decode_attention_per_head", timed(att, n, torch), R * ab["attention"],
+            "every head reads its own pages: R times the bytes of the shared-head form")
+        U = min(R * k, w.NP)
+        uidx = torch.empty(w.B, w.Hkv, U, dtype=torch.int32, device=dev)
+        uheads = torch.empty(w.B, w.Hkv, U, dtype=torch.int16, device=dev)
+        row("stc_union_pages", timed(lambda i: stc.stc_union_pages(c.shape, idx, k, uidx, uheads),
+                                     n, torch), w.B * w.Hq * k * 4 + streams * U * 6)
+        n_union = int((uidx >= 0).sum().item())
+        ws_u = ws(stc.STC_WS_ATTENTION, U)
+
+        def attu(i):
+            t = ph[i % 2]
+            stc.stc_decode_attention_union(t.shape, qs[0], t.K, t.vpacked, t.mask, t.tok_off, uidx,
+                                           uheads, out, ws_u)
+        row("stc_decode_attention_union", timed(attu, n, torch),
+            n_union * 16 * (w.D * 2 + mean_kept * gd * 2 + 2) + n_union * 14,
+            "%d pages in the union of %d lists of %d (per KV head, mean %.0f)"
+            % (n_union, R, k, n_union / streams))
+    return {"rows": rows, "workload": w.name, "launches": n, "unit": "us per call",
+            "peak_GBps": HBM_PEAK_GBPS, "mean_kept_groups": mean_kept}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)

@@ -92,7 +92,11 @@ enum {
 enum {
   STC_ROUTE_MASK = 0, /* mask_in gives the kept groups (bits >= G are ignored) */
   STC_ROUTE_TOPK = 1, /* top-k of `logits` per token; count from kcount[] or fixed_k */
-  STC_ROUTE_GLOBAL = 2 /* the N*fixed_k largest of a stream's N*G logits */
+  STC_ROUTE_GLOBAL = 2, /* the N*fixed_k largest of a stream's N*G logits */
+  /* flag, OR-ed into a mode: logits, kcount and mask_in hold ONE set per batch element
+   * ([B, 1, N, ...]) that all KV heads of the element read -- the router gives one mask per
+   * token and layer (App. B.1); stc_router_logits with Hkv = 1 writes logits of that shape */
+  STC_ROUTE_SHARED = 0x100
 };
 
 int stc_version(void);
@@ -133,10 +137,12 @@ size_t stc_bounds_bytes(const stc_shape_t *shape);
  *        M = N*fixed_k token-group pairs of largest logit over the whole [N, G] grid are
  *        kept (fixed_k in 0..G; equal logits, -0 == +0: lower t*G+g first), so a token keeps
  *        anything from 0 to G groups.  kcount is ignored.
+ *   mode | STC_ROUTE_SHARED: the three routing inputs below are [B, 1, ...] and shared by the
+ *        KV heads of a batch element (every head of the element then gets the same mask).
  *   V       [B, Hkv, N, D] bf16, in
  *   logits  [B, Hkv, N, G] float, in (TOPK and GLOBAL)
  *   kcount  [B, Hkv, N] uint8, in (TOPK, may be NULL)
- *   mask_in [B, Hkv, N] uint16, in (MASK only)
+ *   mask_in [B, Hkv, N] uint16, in (MASK only; must not alias mask when shared)
  *   mask    [B, Hkv, Ncap] uint16, out (may alias mask_in when Ncap == N)
  *   tok_off [B, Hkv, Ncap+1] uint32, out: exclusive prefix sum of popcount(mask)
  *           per stream, in group units; tok_off[N] = kept groups of the stream
@@ -347,7 +353,8 @@ int stc_decode_attention_union(const stc_shape_t *shape, const void *q, const vo
  * Value-group router (App. B.1: the S group logits of a token are one learned linear map of
  * its hidden state at the layer input), for feeding stc_route_and_pack_values:
  *   logits[b, kvh, t, g] = sum_c h[b, t, c] * W[g, c] (+ bias[g]), the same for every kvh
- *   (the router gives one mask per token and layer).
+ *   (the router gives one mask per token and layer).  With Hkv = 1 a single copy is written,
+ *   for stc_route_and_pack_values with STC_ROUTE_SHARED.
  * Float arithmetic in a fixed order, because masks are decided on these numbers: chunks of
  * 128 adjacent channels are summed as a balanced tree over adjacent channels, chunk sums are
  * accumulated left to right, the bias is added last.

@@ -20,6 +20,7 @@ STC_ERR_NULL, STC_ERR_SHAPE, STC_ERR_ALIGN, STC_ERR_WORKSPACE, STC_ERR_LAUNCH = 
 STC_WS_ROUTE, STC_WS_SELECT, STC_WS_ATTENTION, STC_WS_ATTENTION_TAIL = 1, 2, 3, 4
 STC_WS_SELECT_PER_HEAD, STC_WS_ATTENTION_PER_HEAD, STC_WS_STEP, STC_WS_STEP_TAIL = 5, 6, 7, 8
 STC_ROUTE_MASK, STC_ROUTE_TOPK, STC_ROUTE_GLOBAL = 0, 1, 2
+STC_ROUTE_SHARED = 0x100        # flag: one set of routing inputs per batch element
 
 EXPORTS = ["stc_version", "stc_status_string", "stc_workspace_bytes", "stc_bounds_bytes",
            "stc_build_page_bounds",
@@ -406,10 +407,12 @@ class RoutedCache:
                 src = self._scores_all[:n]
             self.page_score = src.view(B, Hkv, self.NP)
 
-    def build(self, K, V, logits=None, kcount=None, fixed_k=0, mask_in=None, global_k=None):
+    def build(self, K, V, logits=None, kcount=None, fixed_k=0, mask_in=None, global_k=None,
+              shared=False):
         """Cache construction: page bounds of K, routing mask + packed store of V.  The mask
         comes from mask_in, from a global budget of N*global_k token-group pairs per stream,
-        or from the per-token top kcount[t] / fixed_k of the logits."""
+        or from the per-token top kcount[t] / fixed_k of the logits.  shared: the routing
+        inputs are [B, 1, ...], one set per batch element for all its KV heads."""
         if self.n_cap:
             self.K[:, :, :self.N].copy_(K)
         else:
@@ -419,6 +422,8 @@ class RoutedCache:
         mode = STC_ROUTE_MASK if mask_in is not None else STC_ROUTE_TOPK
         if global_k is not None:
             mode, fixed_k, kcount = STC_ROUTE_GLOBAL, int(global_k), None
+        if shared:
+            mode |= STC_ROUTE_SHARED
         stc_route_and_pack_values(self.shape, mode, V, logits, kcount, fixed_k, mask_in, self.mask,
                                   self.tok_off, self.vpacked, self.dev_status, self._ws_route)
 

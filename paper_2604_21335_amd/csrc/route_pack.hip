@@ -42,15 +42,16 @@ __device__ __forceinline__ int block_exscan_256(int v, int* lds4, int* total) {
 __global__ __launch_bounds__(kChunk) void route_mask_kernel(
     int mode, const float* __restrict__ logits, const uint8_t* __restrict__ kcount, int fixed_k,
     const uint16_t* mask_in, uint16_t* mask, uint32_t* __restrict__ chunk_sum, int N, int G,
-    int nchunks, int Ncap, int mask_in_stride) {
+    int nchunks, int Ncap, int mask_in_stride, int share) {
   __shared__ int red[4];
   const int stream = blockIdx.y;
+  const int src = stream / share;  // the routing inputs of `share` streams are one set
   const int t = blockIdx.x * kChunk + threadIdx.x;
   uint32_t m = 0;
   if (t < N) {
-    const size_t tok = (size_t)stream * N + t;  // dense inputs: logits, kcount
+    const size_t tok = (size_t)src * N + t;  // dense inputs: logits, kcount
     if (mode == STC_ROUTE_MASK) {
-      m = mask_in[(size_t)stream * mask_in_stride + t] & ((1u << G) - 1u);
+      m = mask_in[(size_t)src * mask_in_stride + t] & ((1u << G) - 1u);
     } else {
       int c = kcount ? (int)kcount[tok] : fixed_k;
       m = rank_mask(logits + tok * G, min(c, G), G);
@@ -126,7 +127,7 @@ __global__ __launch_bounds__(256) void global_init_kernel(uint32_t* __restrict__
 // blockIdx.x covers logits [blockIdx.x * slice, +slice) of stream blockIdx.y.
 __global__ __launch_bounds__(kHistThreads) void global_hist_kernel(
     const float* __restrict__ logits, uint32_t* __restrict__ hist,
-    const GlobalState* __restrict__ state, uint32_t n, uint32_t slice, int pass) {
+    const GlobalState* __restrict__ state, uint32_t n, uint32_t slice, int pass, int share) {
   __shared__ uint32_t lh[kGlobalBins];
   const int stream = blockIdx.y;
   const int tid = threadIdx.x;
@@ -135,7 +136,7 @@ __global__ __launch_bounds__(kHistThreads) void global_hist_kernel(
   const uint32_t prefix = state[stream].prefix, decided = state[stream].decided;
   for (uint32_t i = tid; i < bins; i += kHistThreads) lh[i] = 0u;
   __syncthreads();
-  const float* a = logits + (size_t)stream * n;
+  const float* a = logits + (size_t)(stream / share) * n;
   const uint32_t lo = blockIdx.x * slice, hi = n - lo < slice ? n : lo + slice;
   auto count = [&](float f) {
     const uint32_t key = logit_key(f);
@@ -197,13 +198,13 @@ __global__ __launch_bounds__(kGlobalThreads) void global_pick_kernel(
 __global__ __launch_bounds__(kChunk) void global_eq_kernel(const float* __restrict__ logits,
                                                            const GlobalState* __restrict__ state,
                                                            uint32_t* __restrict__ chunk_eq, int N,
-                                                           int G, int nchunks) {
+                                                           int G, int nchunks, int share) {
   __shared__ int red[4];
   const int stream = blockIdx.y;
   if (state[stream].take_all) return;  // no ranks among equal pairs needed
   const uint32_t key = state[stream].prefix;
   const uint32_t n = (uint32_t)N * (uint32_t)G;
-  const float* a = logits + (size_t)stream * n;
+  const float* a = logits + (size_t)(stream / share) * n;
   const uint32_t lo = (uint32_t)blockIdx.x * kChunk * G;
   const uint32_t hi = n - lo < (uint32_t)kChunk * G ? n : lo + (uint32_t)kChunk * G;
   int eq = 0;
@@ -237,7 +238,7 @@ template <int G>
 __global__ __launch_bounds__(kChunk) void global_mask_kernel(
     const float* __restrict__ logits, const GlobalState* __restrict__ state,
     const uint32_t* __restrict__ chunk_eq, uint16_t* __restrict__ mask,
-    uint32_t* __restrict__ chunk_sum, int N, int nchunks, int Ncap, uint32_t budget) {
+    uint32_t* __restrict__ chunk_sum, int N, int nchunks, int Ncap, uint32_t budget, int share) {
   __shared__ int red[4];
   const int stream = blockIdx.y;
   const int t = blockIdx.x * kChunk + threadIdx.x;
@@ -245,7 +246,7 @@ __global__ __launch_bounds__(kChunk) void global_mask_kernel(
   const uint32_t prefix = gs.prefix, remaining = gs.remaining;
   const bool ranked = budget > 0 && !gs.take_all;  // equal pairs are taken in order
   float lg[G];
-  load_token_logits<G>(logits + ((size_t)stream * N + min(t, N - 1)) * G, lg);
+  load_token_logits<G>(logits + ((size_t)(stream / share) * N + min(t, N - 1)) * G, lg);
   uint32_t key[G];
   int eq = 0;
 #pragma unroll
@@ -381,6 +382,9 @@ int launch_route_pack(const stc_shape_t& s, int mode, const void* V, const float
                       const uint8_t* kcount, int fixed_k, const uint16_t* mask_in, uint16_t* mask,
                       uint32_t* tok_off, void* vpacked, int32_t* dev_status, void* ws,
                       hipStream_t st) {
+  // STC_ROUTE_SHARED: one set of routing inputs per batch element, read by all its KV heads
+  const int share = (mode & STC_ROUTE_SHARED) ? s.Hkv : 1;
+  mode &= ~STC_ROUTE_SHARED;
   const int streams = s.B * s.Hkv;
   const int nchunks = (s.N + kChunk - 1) / kChunk;
   const int Ncap = token_cap(s);  // stride of mask and tok_off; V, logits, kcount are dense
@@ -399,16 +403,17 @@ int launch_route_pack(const stc_shape_t& s, int mode, const void* V, const float
       dim3 hgrid((unsigned)(((unsigned long long)n + kHistSlice - 1) / kHistSlice), streams);
       for (int pass = 0; pass < 3; ++pass) {
         global_hist_kernel<<<hgrid, kHistThreads, 0, st>>>(logits, hist, state, n, kHistSlice,
-                                                           pass);
+                                                           pass, share);
         global_pick_kernel<<<streams, kGlobalThreads, 0, st>>>(hist, state, pass);
       }
-      global_eq_kernel<<<grid, kChunk, 0, st>>>(logits, state, chunk_eq, s.N, s.G, nchunks);
+      global_eq_kernel<<<grid, kChunk, 0, st>>>(logits, state, chunk_eq, s.N, s.G, nchunks,
+                                                share);
       global_eq_scan_kernel<<<streams, 256, 0, st>>>(chunk_eq, state, nchunks);
     }
 #define STC_GLOBAL_MASK(GG)                                                                   \
   case GG:                                                                                    \
     global_mask_kernel<GG><<<grid, kChunk, 0, st>>>(logits, state, chunk_eq, mask, chunk, s.N, \
-                                                    nchunks, Ncap, budget);                   \
+                                                    nchunks, Ncap, budget, share);            \
     break;
     switch (s.G) {
       STC_GLOBAL_MASK(1)
@@ -422,7 +427,7 @@ int launch_route_pack(const stc_shape_t& s, int mode, const void* V, const float
 #undef STC_GLOBAL_MASK
   } else {
     route_mask_kernel<<<grid, kChunk, 0, st>>>(mode, logits, kcount, fixed_k, mask_in, mask, chunk,
-                                               s.N, s.G, nchunks, Ncap, s.N);
+                                               s.N, s.G, nchunks, Ncap, s.N, share);
   }
   if (hipGetLastError() != hipSuccess) return -1;
   scan_chunks_kernel<<<streams, 256, 0, st>>>(chunk, tok_off, dev_status, s.N, nchunks,

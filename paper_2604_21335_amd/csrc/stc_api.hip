@@ -120,14 +120,16 @@ int stc_route_and_pack_values(const stc_shape_t* shape, int mode, const void* V,
                               void* stream) {
   if (!shape || !V || !mask || !tok_off || !vpacked) return STC_ERR_NULL;
   if (!shape_ok(shape)) return STC_ERR_SHAPE;
-  if (mode == STC_ROUTE_TOPK) {
+  const int base_mode = mode & ~STC_ROUTE_SHARED;
+  if (base_mode == STC_ROUTE_TOPK) {
     if (!logits) return STC_ERR_NULL;
     if (!kcount && (fixed_k < 0 || fixed_k > shape->G)) return STC_ERR_SHAPE;
-  } else if (mode == STC_ROUTE_GLOBAL) {
+  } else if (base_mode == STC_ROUTE_GLOBAL) {
     if (!logits) return STC_ERR_NULL;
     if (fixed_k < 0 || fixed_k > shape->G) return STC_ERR_SHAPE;
-  } else if (mode == STC_ROUTE_MASK) {
+  } else if (base_mode == STC_ROUTE_MASK) {
     if (!mask_in) return STC_ERR_NULL;
+    if ((mode & STC_ROUTE_SHARED) && (const void*)mask_in == (const void*)mask) return STC_ERR_SHAPE;
   } else {
     return STC_ERR_SHAPE;
   }

@@ -68,6 +68,12 @@ def test_null_alignment_and_workspace_errors():
     assert args(stc.STC_ROUTE_TOPK, FAKE, None, 9, None, FAKE, big) == stc.STC_ERR_SHAPE
     assert args(stc.STC_ROUTE_TOPK, FAKE, None, -1, None, FAKE, big) == stc.STC_ERR_SHAPE
     assert args(7, FAKE, None, 2, FAKE, FAKE, big) == stc.STC_ERR_SHAPE
+    assert args(stc.STC_ROUTE_SHARED | 7, FAKE, None, 2, FAKE, FAKE, big) == stc.STC_ERR_SHAPE
+    assert args(stc.STC_ROUTE_SHARED | stc.STC_ROUTE_TOPK, None, None, 2, None, FAKE,
+                big) == stc.STC_ERR_NULL
+    # shared masks cannot be routed in place (the output has one row per KV head)
+    assert args(stc.STC_ROUTE_SHARED | stc.STC_ROUTE_MASK, None, None, 0, FAKE, FAKE,
+                big) == stc.STC_ERR_SHAPE
     assert args(stc.STC_ROUTE_GLOBAL, None, None, 2, None, FAKE, big) == stc.STC_ERR_NULL
     assert args(stc.STC_ROUTE_GLOBAL, FAKE, None, 9, None, FAKE, big) == stc.STC_ERR_SHAPE
     assert args(stc.STC_ROUTE_GLOBAL, FAKE, None, 2, None, FAKE, 0) == stc.STC_ERR_WORKSPACE

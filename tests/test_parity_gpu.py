@@ -506,6 +506,52 @@ def test_router_logits_bits_and_routing(B, Hkv, N, dm, G, with_bias):
                 assert np.array_equal(hip["mask"][b, kvh], m)
 
 
+@pytest.mark.parametrize("mode", ["topk", "global", "mask"])
+def test_routing_inputs_shared_by_the_kv_heads(mode):
+    """One set of routing inputs per batch element (the paper's router gives one mask per token
+    and layer), read by all KV heads: the cache equals the one built from replicated inputs and
+    the oracle's; the router with Hkv = 1 writes the single copy."""
+    rng = np.random.default_rng(500)
+    B, Hq, Hkv, D, N, G, dm = 2, 8, 4, 128, 16 * 45 + 7, 8, 256
+    K, V, q, _, _ = _rand_case(501, B, Hq, Hkv, D, N, G)
+    h, Wr = randn_bf16(rng, (B, N, dm)), randn_bf16(rng, (G, dm))
+    dev = "cuda:0"
+    lg1 = torch.empty(B, 1, N, G, dtype=torch.float32, device=dev)
+    stc.stc_router_logits(PT.to_dev_bf16(h), PT.to_dev_bf16(Wr), None, lg1, 1)
+    torch.cuda.synchronize()
+    logits1 = lg1.cpu().numpy()
+    for b in range(B):
+        assert np.array_equal(logits1[b, 0].view(np.uint32),
+                              O.router_logits(h[b], Wr, None).view(np.uint32))
+    kc1 = rng.integers(0, G + 1, size=(B, 1, N)).astype(np.uint8)
+    m1 = rng.integers(0, 1 << G, size=(B, 1, N)).astype(np.uint16)
+    kw = dict(topk=dict(logits=lg1, kcount=torch.from_numpy(kc1).to(dev)),
+              mask=dict(mask_in=PT.to_dev_u16(m1)), **{"global": dict(logits=lg1, global_k=3)})[mode]
+    c = stc.RoutedCache(B, Hq, Hkv, D, N, G, 9, device=dev)
+    c.vpacked.view(torch.int16).fill_(0x7FC0)
+    c.build(PT.to_dev_bf16(K), PT.to_dev_bf16(V), shared=True, **kw)
+    c.step(PT.to_dev_bf16(q))
+    torch.cuda.synchronize()
+    assert int(c.dev_status.item()) == 0
+    mask, off, vp = PT.host_u16(c.mask), c.tok_off.cpu().numpy().view(np.uint32), PT.host_bf16(c.vpacked)
+    R = Hq // Hkv
+    for b in range(B):
+        if mode == "topk":
+            m = O.route_mask(logits1[b, 0], kc1[b, 0])
+        elif mode == "global":
+            m = O.route_mask_global(logits1[b, 0], 3 * N)
+        else:
+            m = m1[b, 0] & np.uint16((1 << G) - 1)
+        o = O.token_offsets(m, G)
+        for hh in range(Hkv):
+            assert np.array_equal(mask[b, hh], m) and np.array_equal(off[b, hh], o)
+            assert np.array_equal(vp[b, hh, :int(o[-1])], O.pack_values(V[b, hh], m, o, G))
+            qh = q[b, hh * R:(hh + 1) * R]
+            idx = O.select_pages(O.page_scores(qh, O.page_bounds(K[b, hh])), 9)
+            want = O.decode_attention(qh, K[b, hh], V[b, hh], m, idx, G)
+            assert np.abs(c.out[b, hh * R:(hh + 1) * R].cpu().numpy() - want).max() < PT.TIGHT
+
+
 def _plant_subnormals(rng, bits, frac=0.12):
     """bf16 bit patterns with a share of entries replaced by subnormal patterns of either sign."""
     out = bits.copy()
