@@ -249,9 +249,11 @@ static void launch_score_d(const stc_shape_t& s, const void* q, const void* boun
   const u32x4* t4 = (const u32x4*)bounds;
   const uint16_t* q16 = (const uint16_t*)q;
   if (D == 128 && R > 4 && R <= 8) {
-    // query operands in shared memory: four workgroups of four wavefronts per CU
+    // query operands in shared memory.  About three workgroups of four wavefronts per CU:
+    // more of them start later (the last of 1024 starts 3 us after the first, of 704 after 1 us)
+    // and end less evenly
     constexpr int WV = 4;
-    const int want = max(1, 1024 / streams);
+    const int want = max(1, 768 / streams);
     int tp = (ntiles + want - 1) / want;
     tp = (tp + WV - 1) / WV * WV;
     dim3 g2((ntiles + tp - 1) / tp, streams);
