@@ -43,6 +43,9 @@ CASES = [
     (48, 4, 4, 64, 600, 4, 9),         # 192 streams: a workgroup scores and selects a stream
     (49, 28, 4, 128, 1000, 8, 20),     # the same with 7 heads per KV head
     (64, 6, 3, 128, 20, 8, 1),         # 192 streams of two pages
+    (2, 10, 2, 128, 1300, 8, 17),      # GQA 5:1 at D = 128: query operands in shared memory
+    (1, 12, 2, 128, 905, 4, 11),       # GQA 6:1, ragged, more scoring workgroups than tiles
+    (3, 24, 3, 128, 40, 8, 2),         # GQA 8:1 on three pages
 ]
 
 
@@ -394,7 +397,8 @@ def test_append_then_attend_step_by_step():
 
 @pytest.mark.parametrize("B,Hq,Hkv,D,N,G,k", [
     (2, 14, 2, 128, 3000, 8, 20), (1, 8, 2, 64, 1000, 4, 9), (2, 4, 4, 128, 700, 8, 5),
-    (1, 12, 1, 128, 2048, 8, 100), (1, 16, 1, 64, 500, 2, 30)])
+    (1, 12, 1, 128, 2048, 8, 100), (1, 16, 1, 64, 500, 2, 30), (1, 10, 2, 128, 1100, 8, 12),
+    (2, 12, 2, 128, 333, 8, 7)])
 def test_per_head_selection_and_attention(B, Hq, Hkv, D, N, G, k):
     """Every query head selects and attends its own pages: scores and indices bit for bit per
     head, output within the bar; for MHA the calls equal the shared ones bit for bit."""
