@@ -86,22 +86,23 @@ __device__ __forceinline__ uint32_t block_exscan_once(uint32_t v, uint32_t* lds_
 // Top-k pages of a stream by one workgroup of THREADS threads with the keys held in
 // registers: thread t owns the IPT adjacent pages t*IPT .. (NP <= THREADS * IPT <= 65535).
 // The selected pages are handed to emit(position in the ascending list, page).  Each radix
-// pass is a shared-memory histogram of one key byte, a block scan over the digits in
-// descending order and a broadcast of the digit that holds the k-th largest key.
+// pass is a shared-memory histogram of one key byte, which every wavefront then scans for
+// itself (digits in descending order) to find the digit that holds the k-th largest key: no
+// broadcast and no second barrier.  The usual case (one pass, then at most 64 candidates
+// ranked directly) crosses six workgroup barriers.
 template <int IPT, int THREADS, class Emit>
 __device__ __forceinline__ void topk_block(const float* __restrict__ sc, int NP, int k,
                                            Emit emit) {
   constexpr int NW = THREADS / 64;
-  __shared__ int hist[256];
-  __shared__ uint32_t waves[2][NW];  // per-wavefront sums of the block scans, alternating
+  __shared__ __align__(16) int hist[256];
+  __shared__ uint32_t waves[NW];  // per-wavefront sums of the final scan
   __shared__ uint32_t s_min[NW], s_max[NW];
-  __shared__ uint32_t s_prefix;
-  __shared__ int s_remaining, s_cand, s_ncand;
+  __shared__ int s_ncand;
   __shared__ uint32_t cand[64];
   __shared__ int s_gt[64], s_ge[64];  // per candidate: candidates above it / not below it
   const int tid = threadIdx.x;
+  const int lane = tid & 63;
   const int i0 = tid * IPT;
-  int flip = 0;  // which buffer of `waves` the next scan uses
 
   // keys of absent pages (index >= NP) are 0, below the key of any finite float
   uint32_t key[IPT];
@@ -123,6 +124,7 @@ __device__ __forceinline__ void topk_block(const float* __restrict__ sc, int NP,
   }
   if (tid < 256) hist[tid] = 0;
   if (tid < 64) s_gt[tid] = 0, s_ge[tid] = 0;
+  if (tid == 0) s_ncand = 0;
 
   // Bits above the highest bit in which two keys differ are common to all keys and
   // need no pass; starting at that bit also spreads the first histogram over many
@@ -145,7 +147,7 @@ __device__ __forceinline__ void topk_block(const float* __restrict__ sc, int NP,
   int remaining = k;  // rank of the k-th largest key among the keys sharing the prefix
   // The last window may overlap bits that are already fixed; keys are filtered on all
   // fixed bits, so the digit found repeats them.  The histogram is zero on entry to every
-  // pass: each bin is cleared by the thread that read it.
+  // pass.
   for (;; shift = max(shift - 8, 0)) {
 #pragma unroll
     for (int j = 0; j < IPT; ++j) {
@@ -153,26 +155,28 @@ __device__ __forceinline__ void topk_block(const float* __restrict__ sc, int NP,
       if (in && i0 + j < NP) atomicAdd(&hist[(key[j] >> shift) & 255u], 1);
     }
     __syncthreads();
-    int cnt = 0;
-    if (tid < 256) {
-      cnt = hist[255 - tid];  // digits in descending order
-      hist[255 - tid] = 0;
+    // Every wavefront finds the digit for itself (no broadcast, no second barrier): lane l
+    // looks at digits 255-4l .. 252-4l, a wavefront scan gives the keys with a larger digit.
+    const int4 h4 = *(const int4*)&hist[252 - 4 * lane];
+    const int c4[4] = {h4.w, h4.z, h4.y, h4.x};
+    const int mine4 = c4[0] + c4[1] + c4[2] + c4[3];
+    int above = (int)wave_scan((uint32_t)mine4, OpAdd{}, 0u) - mine4;
+    int f_digit = 0, f_above = 0, f_cnt = 0;
+    bool found = false;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const bool hit = above < remaining && remaining <= above + c4[j];
+      if (hit) f_digit = 255 - 4 * lane - j, f_above = above, f_cnt = c4[j];
+      found |= hit;
+      above += c4[j];
     }
-    uint32_t tot;
-    const int above = (int)block_exscan_once<NW>((uint32_t)cnt, waves[flip], &tot);
-    flip ^= 1;
-    if (tid < 256 && above < remaining && remaining <= above + cnt) {
-      s_prefix = (prefix & ~(255u << shift)) | ((uint32_t)(255 - tid) << shift);
-      s_remaining = remaining - above;
-      s_cand = cnt;  // keys that share the new prefix
-      s_ncand = 0;
-    }
-    __syncthreads();
-    prefix = s_prefix;
-    remaining = s_remaining;
+    const int src = __builtin_amdgcn_readfirstlane(__ffsll((long long)__ballot(found)) - 1);
+    const int digit = __builtin_amdgcn_readlane(f_digit, src);
+    const int c = __builtin_amdgcn_readlane(f_cnt, src);  // keys that share the new prefix
+    remaining -= __builtin_amdgcn_readlane(f_above, src);
+    prefix = (prefix & ~(255u << shift)) | ((uint32_t)digit << shift);
     decided = ~((1u << shift) - 1u);
     if (shift == 0) break;
-    const int c = s_cand;
     if (c <= 64) {
       // Few keys are left: list them and rank them directly.
 #pragma unroll
@@ -199,18 +203,21 @@ __device__ __forceinline__ void topk_block(const float* __restrict__ sc, int NP,
         }
       }
       __syncthreads();
-      if (tid < c) {
-        const int gt = s_gt[tid], ge = s_ge[tid];
-        if (gt < remaining && remaining <= ge) {  // equal keys all write the same pair
-          s_prefix = cand[tid];
-          s_remaining = remaining - gt;
-        }
+      {  // every wavefront picks the k-th key itself: lane i looks at candidate i
+        const int ci = min(lane, c - 1);
+        const int gt = s_gt[ci], ge = s_ge[ci];
+        const uint32_t mine = cand[ci];
+        const bool kth = gt < remaining && remaining <= ge;  // equal keys agree
+        const int s2 = __builtin_amdgcn_readfirstlane(__ffsll((long long)__ballot(kth)) - 1);
+        prefix = (uint32_t)__builtin_amdgcn_readlane((int)mine, s2);
+        remaining -= __builtin_amdgcn_readlane(gt, s2);
       }
-      __syncthreads();
-      prefix = s_prefix;
-      remaining = s_remaining;
       break;
     }
+    // another pass: the histogram is cleared once every wavefront has read it
+    __syncthreads();
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
   }
   // prefix = key of the k-th largest score; `remaining` of the pages equal to it are
   // taken, lowest page index first.  One scan carries both counts of a thread: pages above
@@ -220,7 +227,7 @@ __device__ __forceinline__ void topk_block(const float* __restrict__ sc, int NP,
   for (int j = 0; j < IPT; ++j)
     if (i0 + j < NP) both += (key[j] > prefix ? 1u : 0u) + (key[j] == prefix ? 0x10000u : 0u);
   uint32_t tot;
-  const uint32_t before = block_exscan_once<NW>(both, waves[flip], &tot);
+  const uint32_t before = block_exscan_once<NW>(both, waves, &tot);
   int e = (int)(before >> 16);                           // equal pages in front of this thread
   int pos = (int)(before & 0xffffu) + min(e, remaining);  // selected pages in front of it
 #pragma unroll
