@@ -89,7 +89,7 @@ __device__ __forceinline__ uint32_t block_exscan_once(uint32_t v, uint32_t* lds_
 // pass is a shared-memory histogram of one key byte, which every wavefront then scans for
 // itself (digits in descending order) to find the digit that holds the k-th largest key: no
 // broadcast and no second barrier.  The usual case (one pass, then at most 64 candidates
-// ranked directly) crosses six workgroup barriers.
+// ranked directly) crosses five workgroup barriers.
 template <int IPT, int THREADS, class Emit>
 __device__ __forceinline__ void topk_block(const float* __restrict__ sc, int NP, int k,
                                            Emit emit) {
