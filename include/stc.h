@@ -360,14 +360,19 @@ int stc_decode_attention_union(const stc_shape_t *shape, const void *q, const vo
  * accumulated left to right, the bias is added last.
  *   h      [B, N, d_model] bf16, in; d_model a multiple of 128
  *   W      [G, d_model] bf16, in; G in {1, 2, 4, 8, 16}
- *   bias   [G] float, in, may be NULL
+ *   bias   [G] float (bias_per_batch == 0) or [B, G] float (bias_per_batch == 1), in, may be
+ *          NULL.  The per-element form carries the query term of the LLM setting's router
+ *          (Sec. 3.4: the group scores are a function of the token state and a summary s_Q of
+ *          the query region; for one linear map of the two, W [h; s_Q] + b = W_h h + (W_q s_Q +
+ *          b), the bracket is one vector per batch element: this routine on the summaries,
+ *          N = 1, gives it)
  *   logits [B, Hkv, N, G] float, out
  * An element of h or W that is subnormal as bf16 (|x| < 2^-126) counts as zero; products must
  * stay finite in float.
  */
 int stc_router_logits(int32_t B, int32_t Hkv, int32_t N, int32_t d_model, int32_t G,
-                      const void *h, const void *W, const float *bias, float *logits,
-                      void *stream);
+                      const void *h, const void *W, const float *bias, int32_t bias_per_batch,
+                      float *logits, void *stream);
 
 /*
  * Token-level compaction helper for caches reduced by a visual-token method

@@ -109,7 +109,7 @@ def load_library():
     lib.stc_append_tail.restype = ctypes.c_int
     lib.stc_append_tail.argtypes = [shp, vp, vp, vp, vp, ctypes.c_int, ctypes.c_int, vp]
     lib.stc_router_logits.restype = ctypes.c_int
-    lib.stc_router_logits.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+    lib.stc_router_logits.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, i32, vp, vp]
     lib.stc_compact_tokens.restype = ctypes.c_int
     lib.stc_compact_tokens.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
     _lib = lib
@@ -317,14 +317,20 @@ def stc_append_tail(shape, k_new, v_new, K_tail, V_tail, n_tail, tail_cap):
 
 
 def stc_router_logits(h, W, bias, logits, Hkv):
-    """h [B, N, d_model] bf16, W [G, d_model] bf16, bias [G] float32 or None ->
-    logits [B, Hkv, N, G] float32 (the same for every KV head)."""
+    """h [B, N, d_model] bf16, W [G, d_model] bf16, bias [G] or [B, G] float32 or None ->
+    logits [B, Hkv, N, G] float32 (the same for every KV head).  A [B, G] bias is one vector
+    per batch element (the query term of a query-conditioned router)."""
     B, N, dm = h.shape
     G = W.shape[0]
+    per_batch = 0
+    if bias is not None and bias.dim() == 2:
+        if tuple(bias.shape) != (B, G):
+            raise ValueError("a per-element bias must be [B, G]")
+        per_batch = 1
     _check(load_library().stc_router_logits(
         B, Hkv, N, dm, G, _ptr(h, torch.bfloat16, "h"), _ptr(W, torch.bfloat16, "W"),
-        _ptr(bias, torch.float32, "bias"), _ptr(logits, torch.float32, "logits"), _stream()),
-        "stc_router_logits")
+        _ptr(bias, torch.float32, "bias"), per_batch, _ptr(logits, torch.float32, "logits"),
+        _stream()), "stc_router_logits")
 
 
 def stc_compact_tokens(src, token_idx, dst, B, Hkv, N_src, n_keep, D, dev_status=None):

@@ -50,10 +50,12 @@ __global__ __launch_bounds__(256) void router_logits_kernel(const uint4* __restr
                                                             const uint4* __restrict__ W,
                                                             const float* __restrict__ bias,
                                                             float* __restrict__ logits, int N,
-                                                            int d_model, int Hkv) {
+                                                            int d_model, int Hkv,
+                                                            int bias_stride) {
   using C = RouterCfg<G>;
   constexpr int NH = C::NH, TG = C::TG;
   const int b = blockIdx.y;
+  if (bias) bias += (size_t)b * bias_stride;  // 0: one bias for the batch; G: one per element
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int j = lane & 3, dp = (lane >> 2) & 7, tq = lane >> 5;
   const int t_first = blockIdx.x * C::BLOCK_TOKENS + wave * C::WAVE_TOKENS + 4 * tq + j;
@@ -170,13 +172,14 @@ __global__ __launch_bounds__(256) void router_logits_kernel(const uint4* __restr
   }
 }
 
-int launch_router_logits(const void* h, const void* W, const float* bias, float* logits, int B,
-                         int Hkv, int N, int d_model, int G, hipStream_t st) {
+int launch_router_logits(const void* h, const void* W, const float* bias, int bias_stride,
+                         float* logits, int B, int Hkv, int N, int d_model, int G,
+                         hipStream_t st) {
 #define STC_ROUTER_CASE(GG)                                                                      \
   case GG: {                                                                                     \
     dim3 grid((N + RouterCfg<GG>::BLOCK_TOKENS - 1) / RouterCfg<GG>::BLOCK_TOKENS, B);           \
     router_logits_kernel<GG><<<grid, 256, 0, st>>>((const uint4*)h, (const uint4*)W, bias,       \
-                                                   logits, N, d_model, Hkv);                     \
+                                                   logits, N, d_model, Hkv, bias_stride);        \
     break;                                                                                       \
   }
   switch (G) {

@@ -415,16 +415,17 @@ int stc_append_tail(const stc_shape_t* shape, const void* k_new, const void* v_n
 }
 
 int stc_router_logits(int32_t B, int32_t Hkv, int32_t N, int32_t d_model, int32_t G,
-                      const void* h, const void* W, const float* bias, float* logits,
-                      void* stream) {
+                      const void* h, const void* W, const float* bias, int32_t bias_per_batch,
+                      float* logits, void* stream) {
   if (!h || !W || !logits) return STC_ERR_NULL;
+  if (bias_per_batch != 0 && bias_per_batch != 1) return STC_ERR_SHAPE;
   if (B < 1 || Hkv < 1 || N < 1 || d_model < 128 || d_model % 128 != 0 || B > kMaxGridY ||
       !(G == 1 || G == 2 || G == 4 || G == 8 || G == 16))
     return STC_ERR_SHAPE;
   if (!aligned16(h) || !aligned16(W) || !aligned16(logits) || (bias && ((uintptr_t)bias & 3)))
     return STC_ERR_ALIGN;
-  return stc::launch_router_logits(h, W, bias, logits, B, Hkv, N, d_model, G,
-                                   (hipStream_t)stream)
+  return stc::launch_router_logits(h, W, bias, bias_per_batch ? G : 0, logits, B, Hkv, N, d_model,
+                                   G, (hipStream_t)stream)
              ? STC_ERR_LAUNCH
              : STC_OK;
 }

@@ -74,8 +74,8 @@ int launch_flush_tail(const stc_shape_t& s, void* K_tail, void* V_tail, int n, i
 int launch_append_tail(const stc_shape_t& s, const void* k_new, const void* v_new, void* K_tail,
                        void* V_tail, int n_tail, int tail_cap, hipStream_t st);
 
-int launch_router_logits(const void* h, const void* W, const float* bias, float* logits, int B,
-                         int Hkv, int N, int d_model, int G, hipStream_t st);
+int launch_router_logits(const void* h, const void* W, const float* bias, int bias_stride,
+                         float* logits, int B, int Hkv, int N, int d_model, int G, hipStream_t st);
 
 int launch_compact(const void* src, const int32_t* token_idx, void* dst, int B, int Hkv, int N_src,
                    int n_keep, int D, int32_t* dev_status, hipStream_t st);

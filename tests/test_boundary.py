@@ -176,13 +176,15 @@ def test_null_alignment_and_workspace_errors():
     assert lib.stc_decode_attention_union(r, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, 7, FAKE,
                                           FAKE, big, None) == stc.STC_ERR_NULL
     # router projection
-    rl = lambda B, dm, G, h=FAKE, bias=None: lib.stc_router_logits(  # noqa: E731
-        B, 2, 10, dm, G, h, FAKE, bias, FAKE, None)
+    rl = lambda B, dm, G, h=FAKE, bias=None, per=0: lib.stc_router_logits(  # noqa: E731
+        B, 2, 10, dm, G, h, FAKE, bias, per, FAKE, None)
     assert rl(1, 100, 8) == stc.STC_ERR_SHAPE and rl(1, 256, 3) == stc.STC_ERR_SHAPE
     assert rl(0, 256, 8) == stc.STC_ERR_SHAPE
     assert rl(1, 256, 8, None) == stc.STC_ERR_NULL
     assert rl(1, 256, 8, ODD) == stc.STC_ERR_ALIGN
     assert rl(1, 256, 8, FAKE, ctypes.c_void_p(0x1002)) == stc.STC_ERR_ALIGN
+    assert rl(1, 256, 8, FAKE, FAKE, 2) == stc.STC_ERR_SHAPE     # bias_per_batch is 0 or 1
+    assert rl(1, 256, 8, FAKE, FAKE, -1) == stc.STC_ERR_SHAPE
     # compact
     assert lib.stc_compact_tokens(FAKE, FAKE, FAKE, 1, 1, 10, 4, 100, None, None) == stc.STC_ERR_SHAPE
     assert lib.stc_compact_tokens(FAKE, None, FAKE, 1, 1, 10, 4, 128, None, None) == stc.STC_ERR_NULL

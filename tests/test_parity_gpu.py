@@ -510,6 +510,32 @@ def test_router_logits_bits_and_routing(B, Hkv, N, dm, G, with_bias):
                 assert np.array_equal(hip["mask"][b, kvh], m)
 
 
+@pytest.mark.parametrize("B,Hkv,N,dm,G", [(3, 2, 203, 512, 8), (5, 1, 64, 128, 4), (2, 1, 130, 3584, 16)])
+def test_router_logits_with_a_query_term_per_batch_element(B, Hkv, N, dm, G):
+    """Query-conditioned router (Sec. 3.4; one linear map of the token state and the query
+    summary, App. B.1): W_h h + (W_q s_Q + b).  The bracket comes from the same routine on the
+    summaries (N = 1) and enters as one bias vector per batch element; both steps bit for bit."""
+    rng = np.random.default_rng(120 + dm)
+    h, sq = randn_bf16(rng, (B, N, dm)), randn_bf16(rng, (B, 1, dm))
+    Wh, Wq = randn_bf16(rng, (G, dm)), randn_bf16(rng, (G, dm))
+    b0 = rng.standard_normal(G).astype(np.float32)
+    dev = "cuda:0"
+    qterm = torch.full((B, 1, 1, G), float("nan"), dtype=torch.float32, device=dev)
+    stc.stc_router_logits(PT.to_dev_bf16(sq), PT.to_dev_bf16(Wq), torch.from_numpy(b0).to(dev), qterm, 1)
+    logits = torch.full((B, Hkv, N, G), float("nan"), dtype=torch.float32, device=dev)
+    stc.stc_router_logits(PT.to_dev_bf16(h), PT.to_dev_bf16(Wh), qterm.view(B, G), logits, Hkv)
+    torch.cuda.synchronize()
+    got_q, got = qterm.cpu().numpy().reshape(B, G), logits.cpu().numpy()
+    for b in range(B):
+        want_q = O.router_logits(sq[b], Wq, b0)[0]
+        assert np.array_equal(got_q[b].view(np.uint32), want_q.view(np.uint32))
+        want = O.router_logits(h[b], Wh, want_q)
+        for kvh in range(Hkv):
+            assert np.array_equal(got[b, kvh].view(np.uint32), want.view(np.uint32))
+    with pytest.raises(ValueError):
+        stc.stc_router_logits(PT.to_dev_bf16(h), PT.to_dev_bf16(Wh), qterm.view(B * G, 1), logits, Hkv)
+
+
 @pytest.mark.parametrize("mode", ["topk", "global", "mask"])
 def test_routing_inputs_shared_by_the_kv_heads(mode):
     """One set of routing inputs per batch element (the paper's router gives one mask per token
