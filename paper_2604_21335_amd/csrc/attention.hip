@@ -550,10 +550,20 @@ struct AttnPlan {
   int waves, ppw, splits;
 };
 
+// Few streams of 2049..8192 pages (a long context at batch 1) can select inside the attention
+// kernel, 16 keys per thread: that wants workgroups of 512 threads, so the plan (which depends
+// on the shape alone: the two-call step gives the same bits) uses them there.
+static bool long_select_shape(const stc_shape_t& s, int k_pages) {
+  const int NP = (s.N + kPage - 1) / kPage;
+  return NP > 2048 && NP <= 8192 && k_pages > 8 &&
+         (long long)s.B * s.Hkv * ((k_pages + 15) / 16) <= 128;
+}
+
 static AttnPlan attention_plan(const stc_shape_t& s, int k_pages) {
   const int streams = s.B * s.Hkv;
   AttnPlan p{8, 2, 0};
   if (k_pages <= 8 || (long long)streams * ((k_pages + 15) / 16) < 256) p.waves = 4;
+  if (long_select_shape(s, k_pages)) p.waves = 8;
   p.splits = (k_pages + p.waves * p.ppw - 1) / (p.waves * p.ppw);
   return p;
 }
@@ -600,7 +610,8 @@ int attn_go(const AttnLaunch& a) {
 
 template <int D>
 int attn_dispatch(const AttnLaunch& a, const AttnPlan& plan, bool tail, bool select) {
-  if (select) {  // selection inside the kernel: 2048 keys over the workgroup's threads
+  if (select) {  // selection inside the kernel: 2048 (8192) keys over the workgroup's threads
+    if (a.p.NP > 2048) return tail ? attn_go<D, 8, true, 16>(a) : attn_go<D, 8, false, 16>(a);
     if (plan.waves == 8)
       return tail ? attn_go<D, 8, true, 4>(a) : attn_go<D, 8, false, 4>(a);
     return tail ? attn_go<D, 4, true, 8>(a) : attn_go<D, 4, false, 8>(a);
@@ -617,7 +628,9 @@ int attn_dispatch(const AttnLaunch& a, const AttnPlan& plan, bool tail, bool sel
 // slower beyond (the repeated prologue then delays a second round of workgroups).
 bool attention_can_select(const stc_shape_t& s, int k_pages, int tail_pages) {
   const int NP = (s.N + kPage - 1) / kPage;
-  if (k_pages >= NP || NP > 2048) return false;
+  if (k_pages >= NP) return false;
+  // long streams: only where the launch is latency-bound anyway (few workgroups)
+  if (NP > 2048) return long_select_shape(s, k_pages + tail_pages);
   return (long long)s.B * s.Hkv * attention_plan(s, k_pages + tail_pages).splits <= 512;
 }
 
@@ -638,7 +651,7 @@ int launch_attention(const stc_shape_t& s0, const void* q, const void* K, const 
                 tail_cap, per_head ? s0.Hq / s0.Hkv : 1, page_heads, token_cap(s), sel_score,
                 sel_list, 0},
                dim3(plan.splits, streams), st};
-  if (sel_score && (NP > 2048 || per_head || page_heads)) return -1;
+  if (sel_score && (NP > 8192 || per_head || page_heads)) return -1;
   // with the selection inside, the workgroups of a stream all read the stream's scores: keep
   // them on one XCD (measured on the headline shape: 34.2 against 34.6 us per step)
   constexpr int kXcds = 8;
