@@ -178,6 +178,9 @@ __device__ __forceinline__ void attn_block(const AttnParams& P, const int stream
     const int slot = pi0 + lane;
     if (slot < k_pages) {
       my_pg = page_idx ? page_idx[(size_t)stream * k_pages + slot] : slot;  // no list: pages 0..
+      // every page attended and the caller wants the list: each wavefront writes its own part
+      if (SELECT_IPT == 0 && !page_idx && sel_list)
+        sel_list[(size_t)stream * k_pages + slot] = slot;
       if (page_heads) my_heads = page_heads[(size_t)stream * k_pages + slot];
       if (my_pg < 0 || my_pg >= NP) my_pg = -1;
     } else {

@@ -289,7 +289,14 @@ int decode_step_impl(const stc_shape_t* shape, const void* q, const void* bounds
   if (rc) return rc;
   const hipStream_t st = (hipStream_t)stream;
   const int tail_pages = (n_tail + shape->P - 1) / shape->P;
-  if (!selecting || !stc::attention_can_select(*shape, k_pages, tail_pages)) {
+  if (!selecting) {  // every page: the attention kernel writes the list 0 .. NP-1 itself
+    return stc::launch_attention(*shape, q, K, vpacked, mask, tok_off, nullptr, k_pages, K_tail,
+                                 V_tail, n_tail, tail_cap, false, nullptr, nullptr, page_idx, out,
+                                 attn_ws, st)
+               ? STC_ERR_LAUNCH
+               : STC_OK;
+  }
+  if (!stc::attention_can_select(*shape, k_pages, tail_pages)) {
     if (stc::launch_select(*shape, q, bounds, k_pages, page_idx, (float*)ws, false, st) ||
         stc::launch_attention(*shape, q, K, vpacked, mask, tok_off,
                               selecting ? page_idx : nullptr, k_pages, K_tail, V_tail, n_tail,

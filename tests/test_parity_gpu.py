@@ -132,6 +132,16 @@ def test_missing_page_list_means_leading_pages():
         assert torch.equal(a, b_)
         if k == NP:
             assert np.array_equal(a.cpu().numpy(), hip["out"])
+    # the one-call step with every page kept: no selection, the list 0 .. NP-1 is still written
+    # (by the attention kernel itself), the output is the attention call's
+    lst = torch.full((B, Hkv, NP), -7, dtype=torch.int32, device="cuda:0")
+    o = torch.full_like(c.out, float("nan"))
+    ws = torch.empty(max(16, stc.stc_workspace_bytes(c.shape, stc.STC_WS_STEP, NP)),
+                     dtype=torch.uint8, device="cuda:0")
+    stc.stc_decode_step(c.shape, dq, c.bounds, c.K, c.vpacked, c.mask, c.tok_off, NP, lst, o, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(lst, torch.arange(NP, dtype=torch.int32, device="cuda:0").expand(B, Hkv, NP))
+    assert np.array_equal(o.cpu().numpy(), hip["out"])
 
 
 @pytest.mark.parametrize("B,Hkv,R,N,k", [
