@@ -187,7 +187,8 @@ __device__ __forceinline__ void attn_block(const AttnParams& P, const int stream
       my_pg = kTailPage | (slot - k_pages);
     }
   }
-  if constexpr (SELECT_IPT > 0) {
+  // (a workgroup whose page slots all lie in the uncompressed tail needs no list)
+  if constexpr (SELECT_IPT > 0) if (split * WAVES * ppw < k_pages) {
     __shared__ int32_t s_pages[WAVES * ppw];
     if (threadIdx.x < WAVES * ppw) s_pages[threadIdx.x] = -1;
     __syncthreads();
@@ -634,7 +635,12 @@ bool attention_can_select(const stc_shape_t& s, int k_pages, int tail_pages) {
   if (k_pages >= NP) return false;
   // long streams: only where the launch is latency-bound anyway (few workgroups)
   if (NP > 2048) return long_select_shape(s, k_pages + tail_pages);
-  return (long long)s.B * s.Hkv * attention_plan(s, k_pages + tail_pages).splits <= 512;
+  // the workgroups that select must all be resident at once; those that hold only pages of
+  // the tail skip the selection and may come in a second round
+  const AttnPlan p = attention_plan(s, k_pages + tail_pages);
+  const long long streams = (long long)s.B * s.Hkv;
+  const int per_wg = p.waves * p.ppw;
+  return streams * ((k_pages + per_wg - 1) / per_wg) <= 512 && streams * p.splits <= 768;
 }
 
 int launch_attention(const stc_shape_t& s0, const void* q, const void* K, const void* vpacked,
