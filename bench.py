@@ -145,10 +145,13 @@ def layer_batched(stc, W, w, dev, queries, steps, warmup, torch):
     return ms
 
 
-def timed(fn, n, torch):
+def timed(fn, n, torch, warm=3):
     """Average milliseconds per call of fn(i) over n back-to-back calls, from HIP events
-    recorded on the stream the kernels are launched on (torch's current stream)."""
+    recorded on the stream the kernels are launched on (torch's current stream); `warm` calls
+    come first, untimed (the first launch of a kernel pays for loading it)."""
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for i in range(warm):
+        fn(i)
     torch.cuda.synchronize()
     a.record()
     for i in range(n):
@@ -544,7 +547,7 @@ def main():
 
     for i in range(args.warmup):
         step(i)
-    ms_step = timed(step, args.steps, torch)
+    ms_step = timed(step, args.steps, torch, warm=0)   # exactly --warmup steps came before
     ms_two = ms_step
     if selecting:
         for i in range(min(args.warmup, 50)):      # its kernels have not run yet
