@@ -960,6 +960,42 @@ def test_tail_decode_across_the_launch_plan_switch(B, k_pages, tail_cap):
                 assert err < PT.TIGHT, (n_tail, one_call, b, h, err)
 
 
+@pytest.mark.parametrize("NP,k_pages", [(2500, 40), (8192, 100)])
+def test_long_streams_select_inside_the_attention_kernel_with_and_without_a_tail(NP, k_pages):
+    """Few streams of more than 2048 pages: the one-call step selects inside the attention
+    kernel with 16 keys per thread; with a tail, the workgroups that hold only tail pages skip
+    the selection.  Page lists bit-exact, outputs within the tight bound, one call and two."""
+    B, Hq, Hkv, D, G, N, tail_cap = 1, 14, 2, 128, 8, 16 * NP - 5, 48
+    K, V, q, logits, kcount = _rand_case(420 + NP, B, Hq, Hkv, D, N, G)
+    rng = np.random.default_rng(421)
+    Kt, Vt = randn_bf16(rng, (B, Hkv, tail_cap, D)), randn_bf16(rng, (B, Hkv, tail_cap, D))
+    dev = "cuda:0"
+    c = stc.RoutedCache(B, Hq, Hkv, D, N, G, k_pages, device=dev, tail_cap=tail_cap)
+    c.build(PT.to_dev_bf16(K), PT.to_dev_bf16(V), logits=torch.from_numpy(logits).to(dev),
+            kcount=torch.from_numpy(kcount).to(dev))
+    c.K_tail.copy_(PT.to_dev_bf16(Kt))
+    c.V_tail.copy_(PT.to_dev_bf16(Vt))
+    R = Hq // Hkv
+    want_idx = [O.select_pages(O.page_scores(q[0, h * R:(h + 1) * R], O.page_bounds(K[0, h])),
+                               k_pages) for h in range(Hkv)]
+    masks = [O.route_mask(logits[0, h], kcount[0, h]) for h in range(Hkv)]
+    for n_tail in (0, 17, tail_cap):
+        c.n_tail = n_tail
+        for one_call in (True, False):
+            c.out.fill_(float("nan"))
+            c.page_idx.fill_(-7)
+            c.step(PT.to_dev_bf16(q), one_call=one_call)
+            torch.cuda.synchronize()
+            got, idx = c.out.cpu().numpy(), c.page_idx.cpu().numpy()
+            for h in range(Hkv):
+                assert np.array_equal(idx[0, h], want_idx[h]), (n_tail, one_call, h)
+                want = O.decode_attention(q[0, h * R:(h + 1) * R], K[0, h], V[0, h], masks[h],
+                                          want_idx[h], G, K_tail=Kt[0, h, :n_tail],
+                                          V_tail=Vt[0, h, :n_tail])
+                err = np.abs(got[0, h * R:(h + 1) * R] - want).max()
+                assert err < PT.TIGHT, (n_tail, one_call, h, err)
+
+
 def test_global_budget_at_full_llm_size():
     """The LLM-mode routing of the paper (budget N*K over the whole stream, K = 4 of 8) on
     the headline shape: exact budget on every stream, masks of sampled streams bit for bit,
